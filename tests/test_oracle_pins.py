@@ -1,0 +1,460 @@
+"""Pins for the CPU oracle: every expected value below comes from a closed form,
+a pure-Python brute force, a library routine (torch on CPU) or an invariant --
+never from the oracle itself and never from the GPU path."""
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import efim_oracle as O
+from paper_2505_21889_amd import workloads as W
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+# ---------------------------------------------------------------- bf16 ----
+
+def _bf16_value(bits):
+    return np.array([bits << 16], dtype=np.uint32).view(np.float32)[0]
+
+
+def test_bf16_decode_known_values():
+    # 1.0 = 0x3F80, -2.0 = 0xC000, 0.5 = 0x3F00, 3.140625 = 0x4049
+    got = O.bf16_to_f64(np.array([0x3F80, 0xC000, 0x3F00, 0x4049, 0x0000, 0x8000], dtype=np.uint16))
+    assert got.tolist()[:4] == [1.0, -2.0, 0.5, 3.140625]
+    assert got[4] == 0.0 and math.copysign(1.0, got[5]) == -1.0
+
+
+def test_bf16_round_identity_on_all_finite_bf16():
+    bits = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    vals = O.bf16_to_f64(bits)
+    finite = np.isfinite(vals)
+    assert np.array_equal(O.f64_to_bf16(vals[finite]), bits[finite])
+
+
+def test_bf16_round_matches_torch_cast_on_fp32():
+    rng = np.random.default_rng(7)
+    x = np.concatenate([
+        rng.standard_normal(200000).astype(np.float32),
+        (rng.standard_normal(50000) * 1e-30).astype(np.float32),
+        (rng.standard_normal(50000) * 1e30).astype(np.float32),
+        (rng.standard_normal(20000) * 1e-39).astype(np.float32),   # bf16 subnormals
+        rng.integers(0, 2**32, 200000, dtype=np.uint64).astype(np.uint32).view(np.float32),
+    ])
+    x = x[np.isfinite(x)]
+    want = torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    got = O.f64_to_bf16(x.astype(np.float64))
+    assert np.array_equal(got, want)
+
+
+def test_bf16_round_ties_to_even_and_fp64_near_ties():
+    # midpoint between 1.0 (0x3F80, even) and 1.0078125 (0x3F81, odd) -> even
+    assert O.f64_to_bf16(np.array([1.00390625]))[0] == 0x3F80
+    # midpoint between 0x3F81 and 0x3F82 -> 0x3F82 (even)
+    assert O.f64_to_bf16(np.array([1.01171875]))[0] == 0x3F82
+    # one fp64 ulp above/below a midpoint must not be treated as a tie (a detour
+    # through fp32 would lose this)
+    up = np.nextafter(1.00390625, 2.0)
+    dn = np.nextafter(1.01171875, 0.0)
+    assert O.f64_to_bf16(np.array([up]))[0] == 0x3F81
+    assert O.f64_to_bf16(np.array([dn]))[0] == 0x3F81
+    # carry into the next binade, overflow to inf, signed zero
+    assert O.f64_to_bf16(np.array([1.998046875]))[0] == 0x4000      # rounds to 2.0
+    assert O.f64_to_bf16(np.array([3.4e38]))[0] == 0x7F80
+    assert O.f64_to_bf16(np.array([-0.0]))[0] == 0x8000
+    # all exact midpoints between neighbouring positive normal bf16 values
+    lo = np.arange(0x0080, 0x7F7F, dtype=np.uint32)
+    mid = (O.bf16_to_f64(lo.astype(np.uint16)) + O.bf16_to_f64((lo + 1).astype(np.uint16))) / 2
+    want = np.where(lo % 2 == 0, lo, lo + 1).astype(np.uint16)
+    assert np.array_equal(O.f64_to_bf16(mid), want)
+
+
+# ---------------------------------------------------------------- RoPE ----
+
+def _read_golden_rope():
+    d2, d4 = [], []
+    with open(os.path.join(GOLDEN, "rope_closed_form.txt")) as fh:
+        for line in fh:
+            if line.startswith("#D4"):
+                _, p, c, s = line.split()
+                d4.append((int(p), float(c), float(s)))
+            elif line.strip() and not line.startswith("#"):
+                p, c, s = line.split()
+                d2.append((int(p), float(c), float(s)))
+    return d2, d4
+
+
+def test_rope_closed_form_d2_and_d4():
+    d2, d4 = _read_golden_rope()
+    for pos, c, s in d2:
+        cos, sin = O.rope_cos_sin([pos], 2, 12345.0)
+        y = O.rope_rotate(np.array([[[1.0, 0.0], [0.0, 1.0]]]), cos, sin)
+        np.testing.assert_allclose(y[0, 0], [c, s], rtol=0, atol=2e-16)
+        np.testing.assert_allclose(y[0, 1], [-s, c], rtol=0, atol=2e-16)
+    for pos, c, s in d4:
+        cos, sin = O.rope_cos_sin([pos], 4, 10000.0)
+        # rotate-half pairs (0,2) and (1,3); pair 1 has frequency 10000^(-2/4) = 1/100
+        y = O.rope_rotate(np.array([[[0.0, 1.0, 0.0, 0.0]]]), cos, sin)
+        np.testing.assert_allclose(y[0, 0], [0.0, c, 0.0, s], rtol=0, atol=1e-15)
+        # interleaved pairs (0,1) and (2,3)
+        y = O.rope_rotate(np.array([[[0.0, 0.0, 1.0, 0.0]]]), cos, sin, interleaved=True)
+        np.testing.assert_allclose(y[0, 0], [0.0, 0.0, c, s], rtol=0, atol=1e-15)
+
+
+def test_rope_inv_freq_values():
+    f = O.rope_inv_freq(128, 10000.0)
+    assert f[0] == 1.0
+    np.testing.assert_allclose(f[32], 0.01, rtol=1e-15)          # 10000^(-64/128)
+    np.testing.assert_allclose(f[63], 10000.0 ** (-126 / 128), rtol=1e-15)
+    f = O.rope_inv_freq(64, 1.0e6)
+    np.testing.assert_allclose(f[16], 1.0e-3, rtol=1e-15)         # (1e6)^(-32/64)
+
+
+def test_rope_pos0_identity_norms_and_relative_property():
+    rng = np.random.default_rng(3)
+    d = 64
+    x = rng.standard_normal((5, 3, d))
+    cos, sin = O.rope_cos_sin(np.zeros(5, dtype=np.int64), d, 1e4)
+    assert np.array_equal(O.rope_rotate(x, cos, sin), x)
+    pos = np.array([0, 1, 17, 4095, 16383])
+    cos, sin = O.rope_cos_sin(pos, d, 1e4)
+    y = O.rope_rotate(x, cos, sin)
+    pair_norm = lambda z: z[..., : d // 2] ** 2 + z[..., d // 2:] ** 2
+    np.testing.assert_allclose(pair_norm(y), pair_norm(x), rtol=1e-13)
+    # <R_m q, R_n k> depends only on m - n
+    q = rng.standard_normal((1, 1, d))
+    k = rng.standard_normal((1, 1, d))
+    def dot(m, n):
+        cm, sm = O.rope_cos_sin([m], d, 1e4)
+        cn, sn = O.rope_cos_sin([n], d, 1e4)
+        return float(np.sum(O.rope_rotate(q, cm, sm) * O.rope_rotate(k, cn, sn)))
+    assert abs(dot(1000, 900) - dot(100, 0)) < 1e-11
+    assert abs(dot(5000, 4990) - dot(10, 0)) < 1e-11
+
+
+def test_rope_interleaved_is_permuted_rotate_half():
+    rng = np.random.default_rng(4)
+    d = 16
+    x = rng.standard_normal((6, 2, d))
+    cos, sin = O.rope_cos_sin(np.arange(6) * 37, d, 1e4)
+    perm = np.concatenate([np.arange(0, d, 2), np.arange(1, d, 2)])   # interleaved -> halves
+    y_half = O.rope_rotate(x[..., perm], cos, sin)
+    y_int = O.rope_rotate(x, cos, sin, interleaved=True)
+    assert np.array_equal(y_int[..., perm], y_half)
+
+
+def test_new_token_positions_are_offset_by_cached_length():
+    pos = O.new_token_positions([5, 0, 7], [3, 2, 0])
+    assert pos.tolist() == [5, 6, 7, 0, 1]
+
+
+# ------------------------------------------------- brute-force definition ----
+
+def _brute_force(cached_len, new_len, table, page, q_bits, kc, vc, hq, hkv, d, scale):
+    """Triple loop with math.exp on Python floats; its own bf16 decode and paging."""
+    def val(b):
+        return float(np.array([int(b) << 16], dtype=np.uint32).view(np.float32)[0])
+    out = {}
+    row0 = 0
+    for r in range(len(new_len)):
+        c, n = int(cached_len[r]), int(new_len[r])
+        for i in range(n):
+            for a in range(hq):
+                h = a // (hq // hkv)
+                logits = []
+                for j in range(c + i + 1):
+                    pg, sl = int(table[r][j // page]), j % page
+                    acc = 0.0
+                    for t in range(d):
+                        acc += val(q_bits[row0 + i][a][t]) * val(kc[pg][h][sl][t])
+                    logits.append(scale * acc)
+                mx = max(logits)
+                w = [math.exp(x - mx) for x in logits]
+                z = sum(w)
+                o = [0.0] * d
+                for j, wj in enumerate(w):
+                    pg, sl = int(table[r][j // page]), j % page
+                    for t in range(d):
+                        o[t] += wj / z * val(vc[pg][h][sl][t])
+                out[(row0 + i, a)] = o
+        row0 += n
+    return out
+
+
+@pytest.mark.parametrize("hq,hkv,d,page", [(2, 2, 4, 2), (2, 1, 2, 4), (4, 2, 4, 4)])
+def test_attention_matches_pure_python_brute_force(hq, hkv, d, page):
+    rng = np.random.default_rng(11 + d + page)
+    c = np.array([3, 0], dtype=np.int32)
+    n = np.array([4, 5], dtype=np.int32)
+    table, num_pages = W.make_block_table(c, n, page, rng)
+    kc = W.gaussian_bf16(rng, (num_pages, hkv, page, d), 1.0)
+    vc = W.gaussian_bf16(rng, (num_pages, hkv, page, d), 1.0)
+    q = W.gaussian_bf16(rng, (int(n.sum()), hq, d), 1.0)
+    scale = 0.7
+    got = O.extend_attention(c, n, table, page, q, kc, vc, scale)
+    want = _brute_force(c, n, table, page, q, kc, vc, hq, hkv, d, scale)
+    for (row, a), o in want.items():
+        np.testing.assert_allclose(got[row, a], o, rtol=0, atol=1e-13)
+
+
+def test_rope_append_matches_pure_python_slot_math():
+    rng = np.random.default_rng(21)
+    hkv, d, page = 2, 4, 4
+    c = np.array([5, 0, 8], dtype=np.int32)      # mid-page start, empty cache, page-aligned start
+    n = np.array([9, 4, 1], dtype=np.int32)      # spans 3 pages, ends on a boundary, single token
+    table, num_pages = W.make_block_table(c, n, page, rng)
+    k = W.gaussian_bf16(rng, (int(n.sum()), hkv, d), 1.0)
+    v = W.gaussian_bf16(rng, (int(n.sum()), hkv, d), 1.0)
+    kc = np.full((num_pages, hkv, page, d), 0xFFFF, dtype=np.uint16)
+    vc = np.full((num_pages, hkv, page, d), 0xFFFF, dtype=np.uint16)
+    base = 100.0
+    O.rope_append(c, n, table, page, None, k, v, kc, vc, base)
+    # expected, element by element, with math.cos / math.sin and Python floats
+    def val(b):
+        return float(np.array([int(b) << 16], dtype=np.uint32).view(np.float32)[0])
+    written = np.zeros((num_pages, page), dtype=bool)
+    row = 0
+    for r in range(3):
+        for i in range(int(n[r])):
+            pos = int(c[r]) + i
+            pg, sl = int(table[r][pos // page]), pos % page
+            written[pg, sl] = True
+            for h in range(hkv):
+                assert np.array_equal(vc[pg, h, sl], v[row, h])
+                for j in range(d // 2):
+                    th = pos * base ** (-2.0 * j / d)
+                    x1, x2 = val(k[row, h, j]), val(k[row, h, j + d // 2])
+                    y1 = x1 * math.cos(th) - x2 * math.sin(th)
+                    y2 = x2 * math.cos(th) + x1 * math.sin(th)
+                    w1 = torch.tensor([y1], dtype=torch.float64).to(torch.bfloat16).view(torch.int16).item() & 0xFFFF
+                    w2 = torch.tensor([y2], dtype=torch.float64).to(torch.bfloat16).view(torch.int16).item() & 0xFFFF
+                    # torch casts f64 -> bf16 through f32; allow the rare double-rounding ulp
+                    assert abs(int(kc[pg, h, sl, j]) - w1) <= 1
+                    assert abs(int(kc[pg, h, sl, j + d // 2]) - w2) <= 1
+                    assert abs(val(kc[pg, h, sl, j]) - y1) <= 2.0 ** -8 * abs(y1) + 1e-40
+            row += 1
+    # every slot that was not appended to still holds the sentinel
+    for pg in range(num_pages):
+        for sl in range(page):
+            if not written[pg, sl]:
+                assert np.all(kc[pg, :, sl] == 0xFFFF) and np.all(vc[pg, :, sl] == 0xFFFF)
+
+
+# ------------------------------------------------------- library routine ----
+
+def _dense_from_pages(cache, row, length, page, h):
+    return O.bf16_to_f64(np.stack([cache[int(row[p // page]), h, p % page] for p in range(length)]))
+
+
+@pytest.mark.parametrize("c_len", [0, 37])
+def test_attention_equals_torch_sdpa_fp64(c_len):
+    rng = np.random.default_rng(31 + c_len)
+    hq, hkv, d, page, n_len = 4, 2, 16, 4, 19
+    c = np.array([c_len], dtype=np.int32)
+    n = np.array([n_len], dtype=np.int32)
+    table, num_pages = W.make_block_table(c, n, page, rng)
+    kc = W.gaussian_bf16(rng, (num_pages, hkv, page, d), 1.0)
+    vc = W.gaussian_bf16(rng, (num_pages, hkv, page, d), 1.0)
+    q = W.gaussian_bf16(rng, (n_len, hq, d), 1.0)
+    got = O.extend_attention(c, n, table, page, q, kc, vc)
+    length = c_len + n_len
+    for a in range(hq):
+        h = a // 2
+        kd = torch.from_numpy(_dense_from_pages(kc, table[0], length, page, h))
+        vd = torch.from_numpy(_dense_from_pages(vc, table[0], length, page, h))
+        qd = torch.from_numpy(O.bf16_to_f64(q[:, a, :]))
+        if c_len == 0:
+            ref = torch.nn.functional.scaled_dot_product_attention(qd[None], kd[None], vd[None], is_causal=True)[0]
+        else:
+            mask = torch.arange(length)[None, :] <= (c_len + torch.arange(n_len))[:, None]
+            ref = torch.nn.functional.scaled_dot_product_attention(qd[None], kd[None], vd[None], attn_mask=mask)[0]
+        np.testing.assert_allclose(got[:, a, :], ref.numpy(), rtol=0, atol=1e-12)
+
+
+# ------------------------------------------------------------ invariants ----
+
+def _small_batch(seed=5, name="c1", **kw):
+    return W.make_batch(name, seed=seed, **kw)
+
+
+def _build_cache(b):
+    """History appended at positions 0..C-1 by the oracle, then the new tokens."""
+    kc, vc = W.poisoned_cache(b), W.poisoned_cache(b)
+    zeros = np.zeros_like(b.cached_len)
+    if b.k_hist is not None and int(b.cached_len.sum()) > 0:
+        O.rope_append(zeros, b.cached_len, b.block_table, b.page_size, None,
+                      b.k_hist, b.v_hist, kc, vc, b.rope_base)
+    q_roped, _ = O.rope_append(b.cached_len, b.new_len, b.block_table, b.page_size,
+                               b.q_new, b.k_new, b.v_new, kc, vc, b.rope_base)
+    return q_roped, kc, vc
+
+
+def test_extend_equals_full_recompute_and_two_shot_cache_is_bit_identical():
+    rng = np.random.default_rng(41)
+    lengths = (np.array([21, 0, 40], dtype=np.int32), np.array([11, 9, 1], dtype=np.int32))
+    b = W.make_batch("c1", seed=41, lengths=lengths, heads=(4, 2), head_dim=8, page_size=4)
+    q_roped, kc, vc = _build_cache(b)
+    out = O.extend_attention(b.cached_len, b.new_len, b.block_table, b.page_size, q_roped, kc, vc)
+    # one-shot cache: every position appended in a single call with C = 0
+    total = b.cached_len + b.new_len
+    k_all, v_all, q_all = [], [], []
+    hs = ns = 0
+    for r in range(b.batch):
+        c, n = int(b.cached_len[r]), int(b.new_len[r])
+        k_all.append(np.concatenate([b.k_hist[hs:hs + c], b.k_new[ns:ns + n]]))
+        v_all.append(np.concatenate([b.v_hist[hs:hs + c], b.v_new[ns:ns + n]]))
+        q_hist = W.gaussian_bf16(rng, (c, b.num_q_heads, b.head_dim), 1.0)
+        q_all.append(np.concatenate([q_hist, b.q_new[ns:ns + n]]))
+        hs += c
+        ns += n
+    kc1, vc1 = W.poisoned_cache(b), W.poisoned_cache(b)
+    O.rope_append(np.zeros_like(total), total, b.block_table, b.page_size, None,
+                  np.concatenate(k_all), np.concatenate(v_all), kc1, vc1, b.rope_base)
+    assert np.array_equal(kc1, kc) and np.array_equal(vc1, vc)
+    ns = 0
+    for r in range(b.batch):
+        n = int(b.new_len[r])
+        ref = O.full_recompute(q_all[r], k_all[r], v_all[r], b.rope_base)
+        np.testing.assert_allclose(out[ns:ns + n], ref[-n:], rtol=0, atol=1e-12)
+        ns += n
+
+
+def test_single_key_returns_its_value_row():
+    b = W.make_batch("c1", seed=51, lengths=(np.array([0, 0], dtype=np.int32), np.array([1, 1], dtype=np.int32)),
+                     heads=(6, 2), head_dim=8)
+    q_roped, kc, vc = _build_cache(b)
+    out = O.extend_attention(b.cached_len, b.new_len, b.block_table, b.page_size, q_roped, kc, vc)
+    for r in range(2):
+        for a in range(6):
+            assert np.array_equal(out[r, a], O.bf16_to_f64(b.v_new[r, a // 3]))
+
+
+def test_zero_query_gives_running_mean_of_values():
+    lengths = (np.array([13, 0], dtype=np.int32), np.array([7, 6], dtype=np.int32))
+    b = W.make_batch("c1", seed=52, lengths=lengths, heads=(2, 1), head_dim=8, page_size=4)
+    _, kc, vc = _build_cache(b)
+    q0 = np.zeros_like(b.q_new)
+    out = O.extend_attention(b.cached_len, b.new_len, b.block_table, b.page_size, q0, kc, vc)
+    v_seq0 = O.bf16_to_f64(np.concatenate([b.v_hist[:13], b.v_new[:7]]))[:, 0, :]
+    v_seq1 = O.bf16_to_f64(b.v_new[7:])[:, 0, :]
+    for i in range(7):
+        np.testing.assert_allclose(out[i, 1], v_seq0[: 13 + i + 1].mean(axis=0), rtol=0, atol=1e-13)
+    for i in range(6):
+        np.testing.assert_allclose(out[7 + i, 0], v_seq1[: i + 1].mean(axis=0), rtol=0, atol=1e-13)
+    # the same limit is reached by a vanishing softmax scale
+    q_roped, _, _ = _build_cache(b)
+    out_s = O.extend_attention(b.cached_len, b.new_len, b.block_table, b.page_size, q_roped, kc, vc, sm_scale=1e-30)
+    np.testing.assert_allclose(out_s, out, rtol=0, atol=1e-13)
+
+
+def test_softmax_is_stable_and_saturates_to_dominant_key():
+    lengths = (np.array([9], dtype=np.int32), np.array([3], dtype=np.int32))
+    b = W.make_batch("c1", seed=53, lengths=lengths, heads=(1, 1), head_dim=8, page_size=4)
+    q_roped, kc, vc = _build_cache(b)
+    out = O.extend_attention(b.cached_len, b.new_len, b.block_table, b.page_size, q_roped, kc, vc, sm_scale=1e4)
+    assert np.all(np.isfinite(out))
+    # with a huge scale each row returns the value row of its best visible key
+    k_seq = O.bf16_to_f64(np.stack([kc[int(b.block_table[0, p // 4]), 0, p % 4] for p in range(12)]))
+    v_seq = O.bf16_to_f64(np.stack([vc[int(b.block_table[0, p // 4]), 0, p % 4] for p in range(12)]))
+    q = O.bf16_to_f64(q_roped[:, 0, :])
+    for i in range(3):
+        best = int(np.argmax(k_seq[: 9 + i + 1] @ q[i]))
+        np.testing.assert_allclose(out[i, 0], v_seq[best], rtol=0, atol=1e-9)
+
+
+def test_page_permutation_invariance_is_bit_exact():
+    b = W.make_batch("c1", seed=54)
+    q_roped, kc, vc = _build_cache(b)
+    out = O.extend_attention(b.cached_len, b.new_len, b.block_table, b.page_size, q_roped, kc, vc)
+    perm = np.random.default_rng(1).permutation(b.num_pages)
+    kc2, vc2 = np.empty_like(kc), np.empty_like(vc)
+    kc2[perm] = kc
+    vc2[perm] = vc
+    table2 = perm[b.block_table].astype(np.int32)
+    out2 = O.extend_attention(b.cached_len, b.new_len, table2, b.page_size, q_roped, kc2, vc2)
+    assert np.array_equal(out, out2)
+
+
+def test_causality_and_poison_independence():
+    lengths = (np.array([10], dtype=np.int32), np.array([9], dtype=np.int32))
+    b = W.make_batch("c1", seed=55, lengths=lengths, heads=(2, 2), head_dim=8, page_size=4)
+    q_roped, kc, vc = _build_cache(b)
+    out = O.extend_attention(b.cached_len, b.new_len, b.block_table, b.page_size, q_roped, kc, vc)
+    assert np.all(np.isfinite(out))           # poison in unused slots / spare pages never leaks
+    # perturb new token j = 5: rows i < 5 are bit-identical, rows >= 5 change
+    pos = 10 + 5
+    pg, sl = int(b.block_table[0, pos // 4]), pos % 4
+    kc2, vc2 = kc.copy(), vc.copy()
+    kc2[pg, :, sl, :] ^= 0x0100
+    vc2[pg, :, sl, :] ^= 0x0100
+    out2 = O.extend_attention(b.cached_len, b.new_len, b.block_table, b.page_size, q_roped, kc2, vc2)
+    assert np.array_equal(out2[:5], out[:5])
+    assert not np.array_equal(out2[5:], out[5:])
+    # slot L (first unused slot of the last page) and spare pages do not matter
+    kc3, vc3 = kc.copy(), vc.copy()
+    pg, sl = int(b.block_table[0, 19 // 4]), 19 % 4
+    kc3[pg, :, sl, :] = 0x3F80
+    vc3[pg, :, sl, :] = 0x3F80
+    used = set(b.block_table[0, :5].tolist())
+    for spare in set(range(b.num_pages)) - used:
+        kc3[spare] = 0x4000
+        vc3[spare] = 0x4000
+    out3 = O.extend_attention(b.cached_len, b.new_len, b.block_table, b.page_size, q_roped, kc3, vc3)
+    assert np.array_equal(out3, out)
+
+
+def test_gqa_equals_mha_with_repeated_kv_heads():
+    lengths = (np.array([6, 3], dtype=np.int32), np.array([5, 4], dtype=np.int32))
+    b = W.make_batch("c1", seed=56, lengths=lengths, heads=(6, 2), head_dim=8, page_size=4)
+    q_roped, kc, vc = _build_cache(b)
+    out = O.extend_attention(b.cached_len, b.new_len, b.block_table, b.page_size, q_roped, kc, vc)
+    kc_rep, vc_rep = np.repeat(kc, 3, axis=1), np.repeat(vc, 3, axis=1)
+    out_rep = O.extend_attention(b.cached_len, b.new_len, b.block_table, b.page_size, q_roped, kc_rep, vc_rep)
+    assert np.array_equal(out, out_rep)
+
+
+def test_batch_independence():
+    lengths = (np.array([6, 0, 11], dtype=np.int32), np.array([5, 4, 2], dtype=np.int32))
+    b = W.make_batch("c1", seed=57, lengths=lengths, heads=(2, 1), head_dim=8, page_size=4)
+    q_roped, kc, vc = _build_cache(b)
+    out = O.extend_attention(b.cached_len, b.new_len, b.block_table, b.page_size, q_roped, kc, vc)
+    # request 2 alone, as a batch of one
+    out_single = O.extend_attention(b.cached_len[2:], b.new_len[2:], b.block_table[2:], b.page_size,
+                                    q_roped[9:], kc, vc)
+    assert np.array_equal(out_single, out[9:])
+    # zero-length request contributes no rows and shifts nothing
+    c = np.array([6, 3, 0, 11], dtype=np.int32)
+    n = np.array([5, 0, 4, 2], dtype=np.int32)
+    table = np.stack([b.block_table[0], b.block_table[0], b.block_table[1], b.block_table[2]])
+    out_z = O.extend_attention(c, n, table, b.page_size, q_roped, kc, vc)
+    assert np.array_equal(out_z, out)
+
+
+def test_append_writes_exactly_the_new_slots():
+    lengths = (np.array([5, 16, 0], dtype=np.int32), np.array([27, 16, 3], dtype=np.int32))
+    b = W.make_batch("c1", seed=58, lengths=lengths, heads=(2, 2), head_dim=8, page_size=16)
+    kc = np.full(b.cache_shape(), 0xABCD, dtype=np.uint16)
+    vc = np.full(b.cache_shape(), 0xABCD, dtype=np.uint16)
+    O.rope_append(b.cached_len, b.new_len, b.block_table, b.page_size, b.q_new, b.k_new, b.v_new, kc, vc, b.rope_base)
+    touched = np.zeros((b.num_pages, b.page_size), dtype=bool)
+    for r in range(3):
+        for p in range(int(b.cached_len[r]), int(b.cached_len[r] + b.new_len[r])):
+            touched[int(b.block_table[r, p // 16]), p % 16] = True
+    assert touched.sum() == 27 + 16 + 3
+    untouched = ~touched
+    assert np.all(kc.transpose(0, 2, 1, 3)[untouched] == 0xABCD)
+    assert np.all(vc.transpose(0, 2, 1, 3)[untouched] == 0xABCD)
+    # V is a bit copy; position-0 keys are unrotated (request 2 starts at position 0)
+    assert np.array_equal(vc[int(b.block_table[2, 0]), :, 0, :], b.v_new[43])
+    assert np.array_equal(kc[int(b.block_table[2, 0]), :, 0, :], b.k_new[43])
+
+
+def test_gather_kv_walks_the_block_table_in_logical_order():
+    page, d = 4, 2
+    cache = np.arange(6 * 1 * page * d, dtype=np.uint16).reshape(6, 1, page, d)
+    row = np.array([4, 1, 5], dtype=np.int32)
+    got = O.gather_kv(cache, row, 10, page, 0)
+    want = np.concatenate([cache[4, 0], cache[1, 0], cache[5, 0, :2]])
+    assert np.array_equal(got, want)
