@@ -1,0 +1,168 @@
+/*
+ * efim.h -- C ABI of the EFIM cache-hit attention library for AMD MI355X (gfx950).
+ *
+ * EFIM (Sec. 1, Sec. 3.1 step 4 of the paper) reorders an infilling prompt to
+ * <P>prefix<S>suffix<M>inc so that the serving engine's cross-request KV cache
+ * covers prefix and suffix and only the incremental tokens `inc` are computed.
+ * Per attention layer this leaves, for every request r of a serving step,
+ *   C_r  cached tokens  (everything in front of `inc`; 0 when nothing is reused --
+ *        the "Baseline" scheme of Sec. 4.2), and
+ *   N_r  new tokens     (`inc`, or the whole prompt on a miss),
+ * and two operations, which are the two calls below:
+ *   1. rotary-embed the new tokens at positions C_r + i and append their K/V to
+ *      the paged cache;
+ *   2. let the new queries attend causally over the cached pages plus themselves.
+ * The paper changes nothing in the model (Sec. 3), so both are the standard
+ * definitions; the cache is the paged cache of the engine it serves with (Sec. 4.2).
+ *
+ * General conventions
+ *  - Every function returns EFIM_OK (0) or a negative efim_status_t.  No exceptions,
+ *    no errno, nothing is printed.
+ *  - All device buffers are owned by the caller.  The library allocates no device
+ *    memory.  It keeps a small ring of pinned host staging buffers (host memory only)
+ *    for the work list it sends to the device.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
+ *    enqueue work and return; they do not wait for the device.
+ *  - Host arrays named in efim_batch_t are read before the call returns and may be
+ *    reused or freed immediately afterwards.
+ *  - bf16 tensors are raw 16-bit patterns; all tensor base pointers must be 16-byte
+ *    aligned.  Offsets are computed in 64 bits.
+ *  - Contents of device arrays (block_table entries) are not validated.
+ */
+#ifndef EFIM_H_
+#define EFIM_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum efim_status {
+  EFIM_OK = 0,
+  EFIM_ERR_INVALID_ARG = -1, /* NULL pointer, negative size, misaligned pointer, Hq % Hkv != 0 ... */
+  EFIM_ERR_UNSUPPORTED = -2, /* head_dim not in {64,128}, page_size != 16, batch too large       */
+  EFIM_ERR_WORKSPACE = -3,   /* workspace NULL/misaligned or smaller than efim_extend_workspace_bytes */
+  EFIM_ERR_LAUNCH = -4       /* a HIP call failed; efim_last_hip_error() holds its hipError_t     */
+} efim_status_t;
+
+/*
+ * One serving step's ragged batch (plain data, caller-owned, read-only).
+ *
+ * New-token tensors are packed: the rows of request r start at sum_{s<r} new_len[s];
+ * T = sum_r new_len[r] is the total number of new tokens.
+ * Logical position p of request r is stored in physical page
+ * block_table[r * max_pages_per_req + p / page_size] at slot p % page_size.
+ * Entries [0, ceil((C_r + N_r) / page_size)) of row r must be valid page ids in
+ * [0, num_pages); later entries are never dereferenced.
+ * A request with new_len 0 contributes no rows and causes no reads or writes.
+ */
+typedef struct efim_batch {
+  int32_t batch;             /* B >= 0                                                   */
+  int32_t num_q_heads;       /* Hq, a multiple of num_kv_heads                           */
+  int32_t num_kv_heads;      /* Hkv >= 1                                                 */
+  int32_t head_dim;          /* D: 64 or 128                                             */
+  int32_t page_size;         /* P: 16                                                    */
+  int32_t max_pages_per_req; /* row stride of block_table                                */
+  int64_t num_pages;         /* pages in each of k_cache and v_cache                     */
+  const int32_t* cached_len; /* HOST  [B]  C_r >= 0                                      */
+  const int32_t* new_len;    /* HOST  [B]  N_r >= 0                                      */
+  const int32_t* block_table;/* DEVICE [B, max_pages_per_req] int32 physical page ids    */
+} efim_batch_t;
+
+/*
+ * efim_rope_append -- rotary embedding at offset positions + paged KV append.
+ *
+ * For new token i of request r, position pos = C_r + i (its index in the reordered
+ * prompt, Sec. 1), and for pair j < D/2 with angle pos * rope_base^(-2j/D):
+ *   rotate-half pairing (rope_interleaved = 0): (x[j], x[j + D/2])
+ *   interleaved pairing (rope_interleaved = 1): (x[2j], x[2j + 1])
+ * The rotation is evaluated in fp64 and rounded once to bf16 (nearest even).
+ *
+ *   q        DEVICE bf16 [T, Hq, D]   in/out: rotated in place.  May be NULL (keys only).
+ *   k_new    DEVICE bf16 [T, Hkv, D]  raw keys of the new tokens (read only)
+ *   v_new    DEVICE bf16 [T, Hkv, D]  values of the new tokens (read only, copied bit for bit)
+ *   k_cache  DEVICE bf16 [num_pages, Hkv, P, D]  receives the rotated keys
+ *   v_cache  DEVICE bf16 [num_pages, Hkv, P, D]  receives the values
+ * Exactly the slots [C_r, C_r + N_r) of every request are written; no other byte of
+ * the caches changes.  Pages written by one call must not be shared between requests.
+ * B = 0 or T = 0: returns EFIM_OK without launching.
+ */
+int efim_rope_append(const efim_batch_t* batch, void* q, const void* k_new, const void* v_new,
+                     void* k_cache, void* v_cache, double rope_base, int rope_interleaved,
+                     void* stream);
+
+/*
+ * efim_extend_workspace_bytes -- device workspace efim_extend_attention needs for this
+ * batch (work list plus split-KV partial results).  Pure host function; returns 0 for an
+ * invalid batch.  The size depends only on the host fields of `batch`.
+ */
+size_t efim_extend_workspace_bytes(const efim_batch_t* batch);
+
+/*
+ * efim_extend_attention -- causal softmax attention of the new tokens over the cached
+ * pages plus themselves.
+ *
+ * New row i of request r and query head a (kv head a / (Hq/Hkv)) sees keys 0 .. C_r + i:
+ *   s_j = sm_scale * <q_i, k_j>,  p = softmax_j(s),  out_i = sum_j p_j v_j.
+ * Scores and outputs are accumulated in fp32 from bf16 operands; out is rounded to bf16.
+ *
+ *   q        DEVICE bf16 [T, Hq, D]  queries, already rotated (efim_rope_append's output)
+ *   k_cache  DEVICE bf16 [num_pages, Hkv, P, D]  must already hold slots [0, C_r + N_r)
+ *   v_cache  DEVICE bf16 [num_pages, Hkv, P, D]
+ *   out      DEVICE bf16 [T, Hq, D]  must not alias q or the caches
+ *   sm_scale softmax scale; 0 selects 1/sqrt(D)
+ *   workspace DEVICE, 256-byte aligned, at least efim_extend_workspace_bytes(batch) bytes;
+ *            its contents are scratch and it must not be used by an overlapping call
+ * Slots at or beyond C_r + N_r in a request's last page, and pages not named in the used
+ * part of its block-table row, may hold anything (NaN included) and do not influence out.
+ * B = 0 or T = 0: returns EFIM_OK without launching.
+ */
+int efim_extend_attention(const efim_batch_t* batch, const void* q, const void* k_cache,
+                          const void* v_cache, void* out, float sm_scale, void* workspace,
+                          size_t workspace_bytes, void* stream);
+
+/*
+ * Work-list introspection (pure host; used by tests and tools).
+ * One item = one workgroup's job: rows [row_begin, row_begin + row_count) of the
+ * (request, kv head) row space -- row = token * (Hq/Hkv) + head-in-group -- against keys
+ * [key_begin, key_end) of that request.  partial_slot < 0: the item covers all visible keys
+ * of its rows and writes `out` directly; otherwise it writes partial results that a merge
+ * pass combines.  Items with row_count 0 are padding.
+ * Returns the number of items (writing at most `capacity` of them; items may be NULL), or a
+ * negative efim_status_t.
+ */
+typedef struct efim_work_item {
+  int32_t req;
+  int32_t kv_head;
+  int32_t row_begin;
+  int32_t row_count;
+  int32_t key_begin;
+  int32_t key_end;
+  int32_t partial_slot;
+  int32_t merge_id;
+} efim_work_item_t;
+
+int64_t efim_extend_plan_items(const efim_batch_t* batch, efim_work_item_t* items, int64_t capacity);
+
+/*
+ * Process-wide tuning knobs for tests and benchmarks (not needed in normal use).
+ * Returns EFIM_OK or EFIM_ERR_INVALID_ARG for an unknown key / bad value.
+ */
+typedef enum efim_tuning_key {
+  EFIM_TUNE_SPLIT_KV = 0,   /* -1 automatic (default), 0 never split, n > 0 split into chunks of n keys (multiple of 64) */
+  EFIM_TUNE_XCD_GROUPING = 1, /* 1 (default): items sharing K/V are placed on one XCD; 0: plain cost order */
+  EFIM_TUNE_NUM_SLOTS = 2   /* concurrent workgroup slots assumed by the planner; 0 = query the device */
+} efim_tuning_key_t;
+
+int efim_set_tuning(int key, int value);
+
+const char* efim_status_string(int status);
+int efim_last_hip_error(void); /* hipError_t of the most recent EFIM_ERR_LAUNCH on this thread */
+int efim_version(void);        /* major * 10000 + minor * 100 + patch */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EFIM_H_ */

@@ -168,10 +168,9 @@ def rope_append(cached_len, new_len, block_table, page_size, q_new, k_new, v_new
 
 def gather_kv(cache, block_table_row, length, page_size, kv_head):
     """Logical rows 0..length-1 of one request and kv head, as bf16 bits [length, D]."""
-    rows = np.empty((length, cache.shape[-1]), dtype=np.uint16)
-    for p in range(length):
-        rows[p] = cache[int(block_table_row[p // page_size]), kv_head, p % page_size]
-    return rows
+    pos = np.arange(length)
+    pages = np.asarray(block_table_row)[pos // page_size]
+    return cache[pages, kv_head, pos % page_size]
 
 
 def extend_attention_rows(r, q_head, cached_len, new_len, block_table, page_size,

@@ -1,0 +1,188 @@
+"""ctypes binding of libefim: argument marshalling only.
+
+Every function has the name and argument order of its C counterpart in
+``include/efim.h``.  Device buffers are passed as torch tensors (or raw
+integer addresses); nothing is computed here and there is no fallback: if the
+HIP library cannot be loaded the import fails.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+
+from . import build as _build
+
+EFIM_OK = 0
+EFIM_ERR_INVALID_ARG = -1
+EFIM_ERR_UNSUPPORTED = -2
+EFIM_ERR_WORKSPACE = -3
+EFIM_ERR_LAUNCH = -4
+
+EFIM_TUNE_SPLIT_KV = 0
+EFIM_TUNE_XCD_GROUPING = 1
+EFIM_TUNE_NUM_SLOTS = 2
+
+
+class EfimBatch(ctypes.Structure):
+    _fields_ = [
+        ("batch", ctypes.c_int32),
+        ("num_q_heads", ctypes.c_int32),
+        ("num_kv_heads", ctypes.c_int32),
+        ("head_dim", ctypes.c_int32),
+        ("page_size", ctypes.c_int32),
+        ("max_pages_per_req", ctypes.c_int32),
+        ("num_pages", ctypes.c_int64),
+        ("cached_len", ctypes.c_void_p),
+        ("new_len", ctypes.c_void_p),
+        ("block_table", ctypes.c_void_p),
+    ]
+
+
+class EfimWorkItem(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in (
+        "req", "kv_head", "row_begin", "row_count", "key_begin", "key_end", "partial_slot", "merge_id")]
+
+
+WORK_ITEM_DTYPE = np.dtype([(n, np.int32) for n, _ in EfimWorkItem._fields_])
+
+
+class EfimError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        msg = _lib.efim_status_string(status).decode()
+        if status == EFIM_ERR_LAUNCH:
+            msg += " (hipError %d)" % _lib.efim_last_hip_error()
+        super().__init__("%s: %s" % (where, msg))
+
+
+def _load():
+    path = _build.LIB_PATH
+    if not os.path.exists(path):
+        _build.build_library()
+    lib = ctypes.CDLL(path)
+    vp, i32, i64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64
+    bp = ctypes.POINTER(EfimBatch)
+    lib.efim_rope_append.argtypes = [bp, vp, vp, vp, vp, vp, ctypes.c_double, i32, vp]
+    lib.efim_rope_append.restype = i32
+    lib.efim_extend_workspace_bytes.argtypes = [bp]
+    lib.efim_extend_workspace_bytes.restype = ctypes.c_size_t
+    lib.efim_extend_attention.argtypes = [bp, vp, vp, vp, vp, ctypes.c_float, vp, ctypes.c_size_t, vp]
+    lib.efim_extend_attention.restype = i32
+    lib.efim_extend_plan_items.argtypes = [bp, vp, i64]
+    lib.efim_extend_plan_items.restype = i64
+    lib.efim_set_tuning.argtypes = [i32, i32]
+    lib.efim_set_tuning.restype = i32
+    lib.efim_status_string.argtypes = [i32]
+    lib.efim_status_string.restype = ctypes.c_char_p
+    lib.efim_last_hip_error.argtypes = []
+    lib.efim_last_hip_error.restype = i32
+    lib.efim_version.argtypes = []
+    lib.efim_version.restype = i32
+    return lib
+
+
+_lib = _load()
+LIBRARY_PATH = _build.LIB_PATH
+EXPORTED_SYMBOLS = (
+    "efim_rope_append", "efim_extend_workspace_bytes", "efim_extend_attention",
+    "efim_extend_plan_items", "efim_set_tuning", "efim_status_string",
+    "efim_last_hip_error", "efim_version",
+)
+
+
+def _ptr(x):
+    """Address of a torch tensor / numpy array, or an integer address, or None."""
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    if hasattr(x, "data_ptr"):
+        return x.data_ptr()
+    if isinstance(x, np.ndarray):
+        return x.ctypes.data
+    raise TypeError("cannot take the address of %r" % type(x))
+
+
+def _stream_ptr(stream):
+    if stream is None:
+        return None
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+class BatchDesc:
+    """Owns the host arrays behind an efim_batch_t and keeps the device block table alive."""
+
+    def __init__(self, cached_len, new_len, block_table, num_q_heads, num_kv_heads, head_dim,
+                 page_size, num_pages, max_pages_per_req=None):
+        self.cached_len = np.ascontiguousarray(cached_len, dtype=np.int32)
+        self.new_len = np.ascontiguousarray(new_len, dtype=np.int32)
+        self.block_table = block_table
+        if max_pages_per_req is None:
+            max_pages_per_req = int(block_table.shape[1]) if hasattr(block_table, "shape") else 0
+        self.c = EfimBatch(
+            int(self.cached_len.shape[0]), num_q_heads, num_kv_heads, head_dim, page_size,
+            max_pages_per_req, num_pages,
+            self.cached_len.ctypes.data if self.cached_len.size else None,
+            self.new_len.ctypes.data if self.new_len.size else None,
+            _ptr(block_table))
+
+    @property
+    def total_new(self):
+        return int(self.new_len.sum())
+
+
+def _check(status, where):
+    if status != EFIM_OK:
+        raise EfimError(status, where)
+
+
+def efim_rope_append(batch, q, k_new, v_new, k_cache, v_cache, rope_base, rope_interleaved=0, stream=None):
+    _check(_lib.efim_rope_append(ctypes.byref(batch.c), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(k_cache),
+                                 _ptr(v_cache), float(rope_base), int(rope_interleaved), _stream_ptr(stream)),
+           "efim_rope_append")
+
+
+def efim_extend_workspace_bytes(batch):
+    return int(_lib.efim_extend_workspace_bytes(ctypes.byref(batch.c)))
+
+
+def efim_extend_attention(batch, q, k_cache, v_cache, out, sm_scale, workspace, workspace_bytes, stream=None):
+    _check(_lib.efim_extend_attention(ctypes.byref(batch.c), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(out),
+                                      float(sm_scale), _ptr(workspace), int(workspace_bytes), _stream_ptr(stream)),
+           "efim_extend_attention")
+
+
+def efim_extend_plan_items(batch):
+    n = _lib.efim_extend_plan_items(ctypes.byref(batch.c), None, 0)
+    if n < 0:
+        raise EfimError(int(n), "efim_extend_plan_items")
+    items = np.zeros(int(n), dtype=WORK_ITEM_DTYPE)
+    if n:
+        m = _lib.efim_extend_plan_items(ctypes.byref(batch.c), items.ctypes.data, int(n))
+        assert m == n
+    return items
+
+
+def efim_set_tuning(key, value):
+    _check(_lib.efim_set_tuning(int(key), int(value)), "efim_set_tuning")
+
+
+def efim_status_string(status):
+    return _lib.efim_status_string(int(status)).decode()
+
+
+def efim_last_hip_error():
+    return int(_lib.efim_last_hip_error())
+
+
+def efim_version():
+    return int(_lib.efim_version())
+
+
+def raw_library():
+    """The ctypes handle, for tests that exercise error returns of the C functions."""
+    return _lib

@@ -1,0 +1,187 @@
+// C ABI entry points of libefim: argument checks, planning, staging of the work list.
+#include <cstring>
+#include <mutex>
+
+#include "efim_internal.h"
+
+namespace efim {
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Concurrent workgroup slots the planner balances for: two attention workgroups fit on a
+// compute unit (64 KB of LDS each).  Falls back to the MI355X figure when no device is
+// visible so that the pure host functions also work on a machine without a GPU.
+int num_slots() {
+  if (tuning().num_slots > 0) return tuning().num_slots;
+  static int cached = 0;
+  if (cached == 0) {
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
+      cached = 2 * cus;
+    else {
+      (void)hipGetLastError();
+      return 512;
+    }
+  }
+  return cached;
+}
+
+// Ring of pinned host buffers through which work lists travel to the device.  A slot is
+// reused only after the copy that read it has finished (event recorded behind the copy).
+struct StageSlot {
+  void* host = nullptr;
+  size_t capacity = 0;
+  hipEvent_t done = nullptr;
+  bool in_flight = false;
+};
+constexpr int kStageSlots = 8;
+StageSlot g_stage[kStageSlots];
+int g_stage_next = 0;
+std::mutex g_stage_mutex;
+
+int stage_and_copy(const Plan& plan, void* workspace, hipStream_t stream) {
+  std::lock_guard<std::mutex> lock(g_stage_mutex);
+  StageSlot& s = g_stage[g_stage_next];
+  g_stage_next = (g_stage_next + 1) % kStageSlots;
+  hipError_t e;
+  if (!s.done) {
+    e = hipEventCreateWithFlags(&s.done, hipEventDisableTiming);
+    if (e != hipSuccess) { set_last_hip_error(e); return EFIM_ERR_LAUNCH; }
+  }
+  if (s.in_flight) {
+    e = hipEventSynchronize(s.done);
+    if (e != hipSuccess) { set_last_hip_error(e); return EFIM_ERR_LAUNCH; }
+    s.in_flight = false;
+  }
+  if (s.capacity < plan.header_bytes) {
+    if (s.host) (void)hipHostFree(s.host);
+    s.host = nullptr;
+    s.capacity = 0;
+    size_t cap = 1 << 16;
+    while (cap < plan.header_bytes) cap <<= 1;
+    e = hipHostMalloc(&s.host, cap, hipHostMallocDefault);
+    if (e != hipSuccess) { set_last_hip_error(e); return EFIM_ERR_LAUNCH; }
+    s.capacity = cap;
+  }
+  char* h = static_cast<char*>(s.host);
+  std::memcpy(h + plan.off_reqs, plan.reqs.data(), plan.reqs.size() * sizeof(ReqInfo));
+  std::memcpy(h + plan.off_items, plan.items.data(), plan.items.size() * sizeof(WorkItem));
+  if (!plan.merges.empty())
+    std::memcpy(h + plan.off_merges, plan.merges.data(), plan.merges.size() * sizeof(MergeItem));
+  e = hipMemcpyAsync(workspace, s.host, plan.header_bytes, hipMemcpyHostToDevice, stream);
+  if (e != hipSuccess) { set_last_hip_error(e); return EFIM_ERR_LAUNCH; }
+  e = hipEventRecord(s.done, stream);
+  if (e != hipSuccess) { set_last_hip_error(e); return EFIM_ERR_LAUNCH; }
+  s.in_flight = true;
+  return EFIM_OK;
+}
+
+}  // namespace
+
+void set_last_hip_error(hipError_t e) { g_last_hip_error = (int)e; }
+
+}  // namespace efim
+
+using namespace efim;
+
+extern "C" {
+
+int efim_rope_append(const efim_batch_t* batch, void* q, const void* k_new, const void* v_new,
+                     void* k_cache, void* v_cache, double rope_base, int rope_interleaved,
+                     void* stream) {
+  int64_t total = 0;
+  int rc = validate_batch(batch, &total);
+  if (rc != EFIM_OK) return rc;
+  if (!(rope_base > 0.0) || (rope_interleaved != 0 && rope_interleaved != 1)) return EFIM_ERR_INVALID_ARG;
+  if (total == 0) return EFIM_OK;
+  if (!k_new || !v_new || !k_cache || !v_cache) return EFIM_ERR_INVALID_ARG;
+  if (!aligned16(q) || !aligned16(k_new) || !aligned16(v_new) || !aligned16(k_cache) ||
+      !aligned16(v_cache) || (reinterpret_cast<uintptr_t>(batch->block_table) & 3u))
+    return EFIM_ERR_INVALID_ARG;
+  return launch_rope_append(batch, total, q, k_new, v_new, k_cache, v_cache, rope_base,
+                            rope_interleaved, static_cast<hipStream_t>(stream));
+}
+
+size_t efim_extend_workspace_bytes(const efim_batch_t* batch) {
+  int64_t total = 0;
+  if (validate_batch(batch, &total) != EFIM_OK) return 0;
+  Plan plan;
+  build_plan(batch, num_slots(), &plan);
+  return plan.total_bytes < 256 ? 256 : plan.total_bytes;
+}
+
+int efim_extend_attention(const efim_batch_t* batch, const void* q, const void* k_cache,
+                          const void* v_cache, void* out, float sm_scale, void* workspace,
+                          size_t workspace_bytes, void* stream) {
+  int64_t total = 0;
+  int rc = validate_batch(batch, &total);
+  if (rc != EFIM_OK) return rc;
+  if (!(sm_scale >= 0.f)) return EFIM_ERR_INVALID_ARG;
+  if (total == 0) return EFIM_OK;
+  if (!q || !k_cache || !v_cache || !out || q == out || out == k_cache || out == v_cache)
+    return EFIM_ERR_INVALID_ARG;
+  if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(out) ||
+      (reinterpret_cast<uintptr_t>(batch->block_table) & 3u))
+    return EFIM_ERR_INVALID_ARG;
+  Plan plan;
+  build_plan(batch, num_slots(), &plan);
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) || workspace_bytes < plan.total_bytes)
+    return EFIM_ERR_WORKSPACE;
+  if (sm_scale == 0.f) sm_scale = 1.0f / sqrtf((float)batch->head_dim);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  rc = stage_and_copy(plan, workspace, s);
+  if (rc != EFIM_OK) return rc;
+  return launch_extend_attention(batch, plan, q, k_cache, v_cache, out, sm_scale, workspace, s);
+}
+
+int64_t efim_extend_plan_items(const efim_batch_t* batch, efim_work_item_t* items, int64_t capacity) {
+  int64_t total = 0;
+  int rc = validate_batch(batch, &total);
+  if (rc != EFIM_OK) return rc;
+  if (capacity < 0 || (capacity > 0 && !items)) return EFIM_ERR_INVALID_ARG;
+  Plan plan;
+  build_plan(batch, num_slots(), &plan);
+  const int64_t n = (int64_t)plan.items.size();
+  for (int64_t i = 0; i < n && i < capacity; ++i) items[i] = plan.items[i];
+  return n;
+}
+
+int efim_set_tuning(int key, int value) {
+  switch (key) {
+    case EFIM_TUNE_SPLIT_KV:
+      if (value < -1 || (value > 0 && value % kKeyTile != 0)) return EFIM_ERR_INVALID_ARG;
+      tuning().split_kv = value;
+      return EFIM_OK;
+    case EFIM_TUNE_XCD_GROUPING:
+      if (value != 0 && value != 1) return EFIM_ERR_INVALID_ARG;
+      tuning().xcd_grouping = value;
+      return EFIM_OK;
+    case EFIM_TUNE_NUM_SLOTS:
+      if (value < 0) return EFIM_ERR_INVALID_ARG;
+      tuning().num_slots = value;
+      return EFIM_OK;
+    default:
+      return EFIM_ERR_INVALID_ARG;
+  }
+}
+
+const char* efim_status_string(int status) {
+  switch (status) {
+    case EFIM_OK: return "ok";
+    case EFIM_ERR_INVALID_ARG: return "invalid argument";
+    case EFIM_ERR_UNSUPPORTED: return "unsupported configuration";
+    case EFIM_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case EFIM_ERR_LAUNCH: return "HIP call failed";
+    default: return "unknown status";
+  }
+}
+
+int efim_last_hip_error(void) { return g_last_hip_error; }
+
+int efim_version(void) { return 100; }
+
+}  // extern "C"

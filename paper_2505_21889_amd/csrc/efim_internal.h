@@ -1,0 +1,74 @@
+// Internal declarations shared by the translation units of libefim (host side).
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <cstddef>
+#include <cstdint>
+#include <vector>
+
+#include "efim.h"
+
+namespace efim {
+
+constexpr int kPageSize = 16;         // tokens per KV page
+constexpr int kKeyTile = 64;          // keys staged in LDS per main-loop iteration (4 pages)
+constexpr int kWavesPerGroup = 4;     // wavefronts per attention workgroup
+constexpr int kMaxRowsPerItem = 256;  // largest query-row tile of one workgroup
+
+// Device-side view of one request.
+struct ReqInfo {
+  int32_t cached;     // C_r
+  int32_t new_len;    // N_r
+  int32_t row_start;  // first packed new-token row of the request
+  int32_t pad;
+};
+
+// Device-side work item: identical fields to efim_work_item_t.
+using WorkItem = efim_work_item_t;
+
+// One query tile whose key range was split: `nsplit` partial results in consecutive slots.
+struct MergeItem {
+  int32_t req;
+  int32_t kv_head;
+  int32_t row_begin;
+  int32_t row_count;
+  int32_t first_slot;
+  int32_t nsplit;
+  int32_t pad0, pad1;
+};
+
+struct Tuning {
+  int split_kv = -1;
+  int xcd_grouping = 1;
+  int num_slots = 0;
+};
+Tuning& tuning();
+
+struct Plan {
+  int rows_per_item = 128;  // query rows per workgroup tile (32 per wave and row block)
+  std::vector<ReqInfo> reqs;
+  std::vector<WorkItem> items;
+  std::vector<MergeItem> merges;
+  int64_t num_partial_slots = 0;
+  // byte offsets inside the device workspace
+  size_t off_reqs = 0, off_items = 0, off_merges = 0, off_part_o = 0, off_part_ml = 0, total_bytes = 0;
+  size_t header_bytes = 0;  // bytes that are copied from the host (reqs + items + merges)
+};
+
+// Validates the host-visible part of a batch. total_new receives T.
+int validate_batch(const efim_batch_t* b, int64_t* total_new);
+
+// Builds the work list. num_slots = number of workgroups the device runs concurrently.
+void build_plan(const efim_batch_t* b, int num_slots, Plan* plan);
+
+int launch_rope_append(const efim_batch_t* b, int64_t total_new, void* q, const void* k_new,
+                       const void* v_new, void* k_cache, void* v_cache, double rope_base,
+                       int interleaved, hipStream_t stream);
+
+int launch_extend_attention(const efim_batch_t* b, const Plan& plan, const void* q,
+                            const void* k_cache, const void* v_cache, void* out, float sm_scale,
+                            void* workspace, hipStream_t stream);
+
+void set_last_hip_error(hipError_t e);
+
+}  // namespace efim

@@ -1,0 +1,350 @@
+// efim_extend_attention: causal softmax attention of the new ("inc") tokens over the cached
+// prefix+suffix pages plus themselves (EFIM Sec. 1: only the incremental part is computed,
+// the rest of the reordered prompt is read from the KV cache).
+//
+// One workgroup (4 wavefronts) handles one work item: a tile of query rows of one
+// (request, kv head) against a range of keys.  Rows are (token, head-in-group) pairs so all
+// query heads that share a kv head read its K/V once.  Per 64-key tile:
+//   * the four 16-token pages are gathered through the block table straight from HBM into
+//     LDS (16 bytes per lane, 1 KB per wave instruction, XOR-swizzled 16-byte chunks),
+//     double buffered, the next tile in flight while the current one is consumed;
+//   * S^T = K Q^T with 32x32x16 bf16 MFMA: every lane ends up with 32 scores of ONE query
+//     row, so the running max / sum are per-lane scalars plus one cross-half exchange;
+//   * P is rounded to bf16 in registers and is directly the B operand of O^T += V^T P^T;
+//     V^T operands come from the row-major V tile through the transposing LDS read.
+// Accumulation is fp32; partial results of split key ranges are merged by a second kernel.
+#include "efim_internal.h"
+
+namespace efim {
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+
+#define LDS_PTR(T) __attribute__((address_space(3))) T*
+#define GLOBAL_PTR(T) __attribute__((address_space(1))) T*
+
+struct AttnParams {
+  const ReqInfo* reqs;
+  const WorkItem* items;
+  const uint16_t* q;
+  const uint16_t* k_cache;
+  const uint16_t* v_cache;
+  uint16_t* out;
+  float* part_o;   // [slot][rows_per_item][D]
+  float* part_ml;  // [slot][rows_per_item][2] = (running max in log2 units, running sum)
+  const int32_t* block_table;
+  int32_t max_pages;
+  int32_t num_q_heads;
+  int32_t num_kv_heads;
+  int32_t group;          // Hq / Hkv
+  int32_t rows_per_item;
+  float scale_log2;       // sm_scale * log2(e)
+};
+
+constexpr int kThreads = 64 * kWavesPerGroup;
+
+template <int D>
+struct Geometry {
+  static constexpr int kRowBytes = D * 2;            // one key/value row
+  static constexpr int kChunks = D / 8;              // 16-byte chunks per row
+  static constexpr int kSteps = D / 16;              // MFMA k-steps over the head dimension
+  static constexpr int kDBlocks = D / 32;            // 32-wide blocks of the head dimension
+  static constexpr int kTileBytes = kKeyTile * kRowBytes;
+  static constexpr int kStageBytes = 2 * kTileBytes; // K tile then V tile
+  static constexpr int kLoadsPerPage = kPageSize * kRowBytes / 1024;
+  static constexpr int kKeysPerLoad = 1024 / kRowBytes;
+  // chunk swizzles (XOR masks) that spread the K rows read by ds_read_b128 and the V rows
+  // read by the transposing read over the LDS banks
+  __device__ static int kswz(int row) { return row & (kChunks - 1); }
+  __device__ static int vswz(int row) { return (row & (kChunks / 4 - 1)) << 2; }
+};
+
+template <int D>
+__global__ __launch_bounds__(kThreads, 2) void extend_attention_kernel(const AttnParams p) {
+  using G = Geometry<D>;
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+
+  const WorkItem it = p.items[blockIdx.x];
+  if (it.row_count == 0) return;
+  const ReqInfo rq = p.reqs[it.req];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int i32 = lane & 31;
+  const int hi = lane >> 5;
+  const int g = p.group;
+
+  // --- this lane's query row (column of S^T / O^T) ----------------------------------
+  const int local_row = wave * 32 + i32;
+  const bool row_ok = local_row < it.row_count;
+  const int row = it.row_begin + local_row;
+  const int tok = row / g;
+  const int head_in_group = row - tok * g;
+  const int n_vis = row_ok ? rq.cached + tok + 1 : 0;  // keys visible to this row
+  const int64_t q_off =
+      ((int64_t)(rq.row_start + tok) * p.num_q_heads + it.kv_head * g + head_in_group) * D;
+
+  const bool wave_active = wave * 32 < it.row_count;
+  const int wave_first_row = it.row_begin + wave * 32;
+  const int wave_last_row = it.row_begin + min(it.row_count, wave * 32 + 32) - 1;
+  const int wave_min_vis = rq.cached + wave_first_row / g + 1;
+  const int wave_max_vis = rq.cached + wave_last_row / g + 1;
+
+  bf16x8 qb[G::kSteps];
+#pragma unroll
+  for (int s = 0; s < G::kSteps; ++s) {
+    u32x4 v = {0u, 0u, 0u, 0u};
+    if (row_ok) v = *reinterpret_cast<const u32x4*>(p.q + q_off + 16 * s + 8 * hi);
+    qb[s] = __builtin_bit_cast(bf16x8, v);
+  }
+
+  f32x16 o[G::kDBlocks];
+#pragma unroll
+  for (int d = 0; d < G::kDBlocks; ++d)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) o[d][r] = 0.f;
+  float m_run = -INFINITY;  // running max of scaled scores (log2 units)
+  float l_run = 0.f;        // this lane's share of the running sum
+
+  const int k_begin = it.key_begin;
+  const int k_end = it.key_end;
+  const int ntiles = (k_end - k_begin + kKeyTile - 1) / kKeyTile;
+  const int32_t* bt = p.block_table + (int64_t)it.req * p.max_pages;
+  const int last_page = (k_end - 1) / kPageSize;
+
+  // --- gather of one 64-key tile: wave w moves page w of the tile, K and V ------------
+  auto issue_tile = [&](int t, int stage) {
+    const int key0 = k_begin + t * kKeyTile;
+    const int page_idx = min(key0 / kPageSize + wave, last_page);
+    const int64_t page = __builtin_amdgcn_readfirstlane(bt[page_idx]);
+    const int64_t page_off = ((page * p.num_kv_heads + it.kv_head) * kPageSize) * (int64_t)G::kRowBytes;
+    const char* kp = reinterpret_cast<const char*>(p.k_cache) + page_off;
+    const char* vp = reinterpret_cast<const char*>(p.v_cache) + page_off;
+    char* ks = smem + stage * G::kStageBytes + wave * kPageSize * G::kRowBytes;
+    char* vs = ks + G::kTileBytes;
+#pragma unroll
+    for (int j = 0; j < G::kLoadsPerPage; ++j) {
+      const int key_in_page = j * G::kKeysPerLoad + lane / G::kChunks;
+      const int pc = lane % G::kChunks;  // physical chunk this lane fills
+      const int tile_row = wave * kPageSize + key_in_page;
+      const int key = key0 + tile_row;
+      if (key < k_end) {
+        const char* ksrc = kp + key_in_page * G::kRowBytes + ((pc ^ G::kswz(tile_row)) << 4);
+        const char* vsrc = vp + key_in_page * G::kRowBytes + ((pc ^ G::vswz(tile_row)) << 4);
+        __builtin_amdgcn_global_load_lds((GLOBAL_PTR(const void))ksrc, (LDS_PTR(void))(ks + j * 1024), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((GLOBAL_PTR(const void))vsrc, (LDS_PTR(void))(vs + j * 1024), 16, 0, 0);
+      } else {
+        // rows past the end of the key range: never fetched (their pages may not exist);
+        // zero them so that 0 * garbage cannot become NaN in the PV product
+        const u32x4 z = {0u, 0u, 0u, 0u};
+        *reinterpret_cast<u32x4*>(ks + j * 1024 + lane * 16) = z;
+        *reinterpret_cast<u32x4*>(vs + j * 1024 + lane * 16) = z;
+      }
+    }
+  };
+
+  issue_tile(0, 0);
+  for (int t = 0; t < ntiles; ++t) {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (t + 1 < ntiles) issue_tile(t + 1, (t + 1) & 1);
+
+    const int key0 = k_begin + t * kKeyTile;
+    if (!wave_active || key0 >= wave_max_vis) continue;
+
+    const char* ks = smem + (t & 1) * G::kStageBytes;
+    const char* vs = ks + G::kTileBytes;
+
+    // ---- S^T[key][row] = sum_d K[key][d] Q[row][d] -----------------------------------
+    f32x16 s[2];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s[kb][r] = 0.f;
+      const char* krow = ks + (kb * 32 + i32) * G::kRowBytes;
+#pragma unroll
+      for (int st = 0; st < G::kSteps; ++st) {
+        const int pc = (2 * st + hi) ^ G::kswz(i32);
+        const u32x4 a = *reinterpret_cast<const u32x4*>(krow + (pc << 4));
+        s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), qb[st], s[kb], 0, 0, 0);
+      }
+    }
+    // element r of block kb is key  key0 + kb*32 + (r/4)*8 + hi*4 + r%4  of row i32
+    if (key0 + kKeyTile > wave_min_vis) {
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int key = key0 + kb * 32 + (r >> 2) * 8 + hi * 4 + (r & 3);
+          if (key >= n_vis) s[kb][r] = -INFINITY;
+        }
+    }
+    // ---- online softmax (per-lane row statistics) ------------------------------------
+    float tmax = s[0][0];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, s[kb][r]);
+    tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+    const float m_new = fmaxf(m_run, tmax * p.scale_log2);
+    const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+    const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
+    m_run = m_new;
+    float psum = 0.f;
+    bf16x8 pb[4];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float e = __builtin_amdgcn_exp2f(s[kb][r] * p.scale_log2 - m_use);
+        psum += e;
+        pb[kb * 2 + (r >> 3)][r & 7] = (__bf16)e;
+      }
+    l_run = l_run * alpha + psum;
+#pragma unroll
+    for (int d = 0; d < G::kDBlocks; ++d)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) o[d][r] *= alpha;
+
+    // ---- O^T[d][row] += sum_key V[key][d] P[row][key] ---------------------------------
+    // 16-lane block b of the wave reads a 4-key x 16-d patch; lane w of the block supplies
+    // the address of key w/4, d-offset 4*(w%4) and receives column w of the patch.
+    const int blk = lane >> 4;
+    const int w16 = lane & 15;
+#pragma unroll
+    for (int ks4 = 0; ks4 < 4; ++ks4) {
+      const int kfirst = (ks4 >> 1) * 32 + (ks4 & 1) * 16 + (blk >> 1) * 4 + (w16 >> 2);
+#pragma unroll
+      for (int d = 0; d < G::kDBlocks; ++d) {
+        const int c = d * 4 + 2 * (blk & 1) + ((w16 & 3) >> 1);
+        const int sub = (w16 & 1) * 8;
+        const int r0 = kfirst, r1 = kfirst + 8;
+        const char* a0 = vs + r0 * G::kRowBytes + ((c ^ G::vswz(r0)) << 4) + sub;
+        const char* a1 = vs + r1 * G::kRowBytes + ((c ^ G::vswz(r1)) << 4) + sub;
+        const bf16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))a0);
+        const bf16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))a1);
+        const bf16x8 a = __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
+        o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[ks4], o[d], 0, 0, 0);
+      }
+    }
+  }
+
+  // --- epilogue ---------------------------------------------------------------------
+  if (!wave_active) return;
+  const float l_tot = l_run + __shfl_xor(l_run, 32);
+  if (!row_ok) return;
+  if (it.partial_slot < 0) {
+    const float inv = 1.f / l_tot;
+    uint16_t* dst = p.out + q_off;
+#pragma unroll
+    for (int d = 0; d < G::kDBlocks; ++d)
+#pragma unroll
+      for (int rr = 0; rr < 4; ++rr) {
+        bf16x4 v;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = (__bf16)(o[d][rr * 4 + e] * inv);
+        *reinterpret_cast<u32x2*>(dst + d * 32 + rr * 8 + hi * 4) = __builtin_bit_cast(u32x2, v);
+      }
+  } else {
+    const int64_t prow = (int64_t)it.partial_slot * p.rows_per_item + local_row;
+    float* dst = p.part_o + prow * D;
+#pragma unroll
+    for (int d = 0; d < G::kDBlocks; ++d)
+#pragma unroll
+      for (int rr = 0; rr < 4; ++rr) {
+        f32x4 v;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = o[d][rr * 4 + e];
+        *reinterpret_cast<f32x4*>(dst + d * 32 + rr * 8 + hi * 4) = v;
+      }
+    if (hi == 0) {
+      p.part_ml[prow * 2] = m_run;
+      p.part_ml[prow * 2 + 1] = l_tot;
+    }
+  }
+}
+
+// Combines the partial results of a split key range: with M = max_s m_s and
+// w_s = 2^(m_s - M):  out = sum_s w_s O_s / sum_s w_s l_s, splits taken in index order.
+template <int D>
+__global__ __launch_bounds__(256) void merge_kernel(const AttnParams p, const MergeItem* merges) {
+  const MergeItem mi = merges[blockIdx.x];
+  const ReqInfo rq = p.reqs[mi.req];
+  const int g = p.group;
+  constexpr int VEC = D / 4;
+  for (int idx = threadIdx.x; idx < mi.row_count * VEC; idx += blockDim.x) {
+    const int lr = idx / VEC;
+    const int dv = (idx - lr * VEC) * 4;
+    float mx = -INFINITY;
+    for (int s = 0; s < mi.nsplit; ++s)
+      mx = fmaxf(mx, p.part_ml[((int64_t)(mi.first_slot + s) * p.rows_per_item + lr) * 2]);
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    float l = 0.f;
+    for (int s = 0; s < mi.nsplit; ++s) {
+      const int64_t prow = (int64_t)(mi.first_slot + s) * p.rows_per_item + lr;
+      const float w = __builtin_amdgcn_exp2f(p.part_ml[prow * 2] - mx);
+      l += w * p.part_ml[prow * 2 + 1];
+      const f32x4 v = *reinterpret_cast<const f32x4*>(p.part_o + prow * D + dv);
+      acc += v * w;
+    }
+    const float inv = 1.f / l;
+    const int row = mi.row_begin + lr;
+    const int tok = row / g;
+    const int hg = row - tok * g;
+    uint16_t* dst = p.out + ((int64_t)(rq.row_start + tok) * p.num_q_heads + mi.kv_head * g + hg) * D + dv;
+    bf16x4 v;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) v[e] = (__bf16)(acc[e] * inv);
+    *reinterpret_cast<u32x2*>(dst) = __builtin_bit_cast(u32x2, v);
+  }
+}
+
+}  // namespace
+
+int launch_extend_attention(const efim_batch_t* b, const Plan& plan, const void* q,
+                            const void* k_cache, const void* v_cache, void* out, float sm_scale,
+                            void* workspace, hipStream_t stream) {
+  char* ws = static_cast<char*>(workspace);
+  AttnParams p;
+  p.reqs = reinterpret_cast<const ReqInfo*>(ws + plan.off_reqs);
+  p.items = reinterpret_cast<const WorkItem*>(ws + plan.off_items);
+  p.q = static_cast<const uint16_t*>(q);
+  p.k_cache = static_cast<const uint16_t*>(k_cache);
+  p.v_cache = static_cast<const uint16_t*>(v_cache);
+  p.out = static_cast<uint16_t*>(out);
+  p.part_o = reinterpret_cast<float*>(ws + plan.off_part_o);
+  p.part_ml = reinterpret_cast<float*>(ws + plan.off_part_ml);
+  p.block_table = b->block_table;
+  p.max_pages = b->max_pages_per_req;
+  p.num_q_heads = b->num_q_heads;
+  p.num_kv_heads = b->num_kv_heads;
+  p.group = b->num_q_heads / b->num_kv_heads;
+  p.rows_per_item = plan.rows_per_item;
+  p.scale_log2 = sm_scale * 1.4426950408889634f;
+  const MergeItem* merges = reinterpret_cast<const MergeItem*>(ws + plan.off_merges);
+
+  const dim3 grid((unsigned)plan.items.size());
+  if (b->head_dim == 128) {
+    extend_attention_kernel<128><<<grid, kThreads, 2 * Geometry<128>::kStageBytes, stream>>>(p);
+  } else {
+    extend_attention_kernel<64><<<grid, kThreads, 2 * Geometry<64>::kStageBytes, stream>>>(p);
+  }
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) { set_last_hip_error(e); return EFIM_ERR_LAUNCH; }
+  if (!plan.merges.empty()) {
+    const dim3 mgrid((unsigned)plan.merges.size());
+    if (b->head_dim == 128) merge_kernel<128><<<mgrid, 256, 0, stream>>>(p, merges);
+    else merge_kernel<64><<<mgrid, 256, 0, stream>>>(p, merges);
+    e = hipGetLastError();
+    if (e != hipSuccess) { set_last_hip_error(e); return EFIM_ERR_LAUNCH; }
+  }
+  return EFIM_OK;
+}
+
+}  // namespace efim

@@ -1,0 +1,208 @@
+// Host-side planner: turns the ragged batch into a list of workgroup-sized work items.
+//
+// Row space of a (request, kv head) pair: row = token * g + head_in_group with g = Hq/Hkv,
+// so rows of one token are adjacent and the causal limit C_r + token + 1 grows with the row.
+// A query tile is a run of `rows_per_item` such rows; it needs keys [0, C_r + last_token + 1).
+// When there are too few tiles to fill the device, or some are much longer than the average,
+// the key range of a tile is cut into chunks (multiples of the 64-key LDS tile) whose partial
+// results a merge pass combines in a fixed order.
+#include <algorithm>
+#include <cstring>
+
+#include "efim_internal.h"
+
+namespace efim {
+
+Tuning& tuning() {
+  static Tuning t;
+  return t;
+}
+
+int validate_batch(const efim_batch_t* b, int64_t* total_new) {
+  if (!b) return EFIM_ERR_INVALID_ARG;
+  if (b->batch < 0 || b->num_q_heads <= 0 || b->num_kv_heads <= 0 || b->head_dim <= 0 ||
+      b->page_size <= 0 || b->max_pages_per_req < 0 || b->num_pages < 0)
+    return EFIM_ERR_INVALID_ARG;
+  if (b->num_q_heads % b->num_kv_heads != 0) return EFIM_ERR_INVALID_ARG;
+  if (b->head_dim != 64 && b->head_dim != 128) return EFIM_ERR_UNSUPPORTED;
+  if (b->page_size != kPageSize) return EFIM_ERR_UNSUPPORTED;
+  if (b->num_q_heads / b->num_kv_heads > 64) return EFIM_ERR_UNSUPPORTED;
+  int64_t total = 0;
+  if (b->batch > 0) {
+    if (!b->cached_len || !b->new_len) return EFIM_ERR_INVALID_ARG;
+    for (int r = 0; r < b->batch; ++r) {
+      const int64_t c = b->cached_len[r], n = b->new_len[r];
+      if (c < 0 || n < 0) return EFIM_ERR_INVALID_ARG;
+      if (c + n > (int64_t)1 << 30) return EFIM_ERR_UNSUPPORTED;
+      if (n > 0) {
+        const int64_t pages = (c + n + b->page_size - 1) / b->page_size;
+        if (pages > b->max_pages_per_req || pages > b->num_pages) return EFIM_ERR_INVALID_ARG;
+      }
+      total += n;
+    }
+    if (total * b->num_q_heads > (int64_t)1 << 31) return EFIM_ERR_UNSUPPORTED;
+    if (total > 0 && !b->block_table) return EFIM_ERR_INVALID_ARG;
+  }
+  if (total_new) *total_new = total;
+  return EFIM_OK;
+}
+
+namespace {
+
+struct Tile {
+  int32_t req, kv_head, row_begin, row_count, key_end;
+  int32_t ktiles;  // ceil(key_end / kKeyTile)
+};
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+}  // namespace
+
+void build_plan(const efim_batch_t* b, int num_slots, Plan* plan) {
+  const int g = b->num_q_heads / b->num_kv_heads;
+  const int D = b->head_dim;
+  plan->reqs.clear();
+  plan->items.clear();
+  plan->merges.clear();
+  plan->num_partial_slots = 0;
+
+  int64_t row = 0;
+  int64_t max_rows = 0;
+  for (int r = 0; r < b->batch; ++r) {
+    ReqInfo ri{b->cached_len[r], b->new_len[r], (int32_t)row, 0};
+    plan->reqs.push_back(ri);
+    row += b->new_len[r];
+    max_rows = std::max<int64_t>(max_rows, (int64_t)g * b->new_len[r]);
+  }
+  // Query-row tile of a workgroup: each of the 4 waves owns 32 rows.
+  const int M = 128;
+  plan->rows_per_item = M;
+
+  std::vector<Tile> tiles;
+  int64_t total_cost = 0;
+  int64_t max_cost = 0;
+  for (int r = 0; r < b->batch; ++r) {
+    const int64_t n = b->new_len[r], c = b->cached_len[r];
+    if (n == 0) continue;
+    const int64_t rows = n * g;
+    for (int h = 0; h < b->num_kv_heads; ++h) {
+      for (int64_t r0 = 0; r0 < rows; r0 += M) {
+        Tile t;
+        t.req = r;
+        t.kv_head = h;
+        t.row_begin = (int32_t)r0;
+        t.row_count = (int32_t)std::min<int64_t>(M, rows - r0);
+        const int64_t last_token = (r0 + t.row_count - 1) / g;
+        t.key_end = (int32_t)(c + last_token + 1);
+        t.ktiles = (t.key_end + kKeyTile - 1) / kKeyTile;
+        tiles.push_back(t);
+        total_cost += t.ktiles + 4;
+        max_cost = std::max<int64_t>(max_cost, t.ktiles + 4);
+      }
+    }
+  }
+
+  // Split policy.  chunk = key tiles per work item (0 = no split).  A workgroup slot's fair
+  // share of the whole step is `avg`; a tile much longer than that would finish last, so it
+  // is cut into pieces of about one share.
+  const Tuning& tn = tuning();
+  int64_t chunk = 0;
+  if (tn.split_kv > 0) {
+    chunk = std::max(1, tn.split_kv / kKeyTile);
+  } else if (tn.split_kv < 0 && !tiles.empty()) {
+    const double avg = (double)total_cost / std::max(1, num_slots);
+    if ((double)max_cost > 1.3 * avg) chunk = (int64_t)std::max(4.0, avg);
+  }
+
+  struct Pending { WorkItem w; int64_t cost; int64_t group; };
+  std::vector<Pending> pend;
+  pend.reserve(tiles.size() * 2);
+  int64_t slot = 0;
+  for (const Tile& t : tiles) {
+    int nsplit = 1;
+    if (chunk > 0 && 10 * (int64_t)t.ktiles > 13 * chunk) nsplit = (int)((t.ktiles + chunk - 1) / chunk);
+    const int64_t group = (int64_t)t.req * b->num_kv_heads + t.kv_head;
+    if (nsplit == 1) {
+      WorkItem w{t.req, t.kv_head, t.row_begin, t.row_count, 0, t.key_end, -1, -1};
+      pend.push_back({w, t.ktiles + 4, group});
+    } else {
+      const int per = (t.ktiles + nsplit - 1) / nsplit;  // key tiles per chunk
+      MergeItem m{t.req, t.kv_head, t.row_begin, t.row_count, (int32_t)slot, 0, 0, 0};
+      int made = 0;
+      for (int s = 0; s < nsplit; ++s) {
+        const int64_t kb = (int64_t)s * per * kKeyTile;
+        if (kb >= t.key_end) break;
+        const int64_t ke = std::min<int64_t>(t.key_end, kb + (int64_t)per * kKeyTile);
+        WorkItem w{t.req, t.kv_head, t.row_begin, t.row_count, (int32_t)kb, (int32_t)ke,
+                   (int32_t)(slot + made), (int32_t)plan->merges.size()};
+        pend.push_back({w, (ke - kb + kKeyTile - 1) / kKeyTile + 4, group});
+        ++made;
+      }
+      m.nsplit = made;
+      slot += made;
+      plan->merges.push_back(m);
+    }
+  }
+  plan->num_partial_slots = slot;
+
+  // Order: heaviest first.  With XCD grouping, items that read the same K/V (same request and
+  // kv head) are given workgroup ids congruent modulo 8, so they run on one XCD and share its
+  // L2; the groups are spread over the 8 XCDs by greedy load balancing.
+  constexpr int kXcds = 8;
+  auto by_cost = [](const Pending& a, const Pending& c) { return a.cost > c.cost; };
+  const int64_t ngroups = (int64_t)b->batch * b->num_kv_heads;
+  bool group_xcd = tn.xcd_grouping && pend.size() >= (size_t)4 * kXcds;
+  if (group_xcd) {
+    // only worthwhile when several items share a group
+    group_xcd = pend.size() > (size_t)tiles.size() || tiles.size() > (size_t)ngroups;
+  }
+  if (!group_xcd) {
+    std::stable_sort(pend.begin(), pend.end(), by_cost);
+    plan->items.reserve(pend.size());
+    for (auto& p : pend) plan->items.push_back(p.w);
+  } else {
+    std::vector<int64_t> gcost(ngroups, 0);
+    for (auto& p : pend) gcost[p.group] += p.cost;
+    std::vector<int64_t> order(ngroups);
+    for (int64_t i = 0; i < ngroups; ++i) order[i] = i;
+    std::stable_sort(order.begin(), order.end(), [&](int64_t a, int64_t c) { return gcost[a] > gcost[c]; });
+    std::vector<int> gx(ngroups, 0);
+    int64_t load[kXcds] = {0};
+    for (int64_t gi : order) {
+      if (gcost[gi] == 0) continue;
+      int best = 0;
+      for (int x = 1; x < kXcds; ++x) if (load[x] < load[best]) best = x;
+      gx[gi] = best;
+      load[best] += gcost[gi];
+    }
+    std::vector<Pending> per[kXcds];
+    for (auto& p : pend) per[gx[p.group]].push_back(p);
+    size_t longest = 0;
+    for (int x = 0; x < kXcds; ++x) {
+      std::stable_sort(per[x].begin(), per[x].end(), by_cost);
+      longest = std::max(longest, per[x].size());
+    }
+    plan->items.reserve(longest * kXcds);
+    const WorkItem nothing{0, 0, 0, 0, 0, 0, -1, -1};
+    for (size_t k = 0; k < longest; ++k)
+      for (int x = 0; x < kXcds; ++x) plan->items.push_back(k < per[x].size() ? per[x][k].w : nothing);
+    while (!plan->items.empty() && plan->items.back().row_count == 0) plan->items.pop_back();
+  }
+
+  // Workspace layout.
+  size_t off = 0;
+  plan->off_reqs = off;
+  off = align_up(off + plan->reqs.size() * sizeof(ReqInfo), 256);
+  plan->off_items = off;
+  off = align_up(off + plan->items.size() * sizeof(WorkItem), 256);
+  plan->off_merges = off;
+  off = align_up(off + plan->merges.size() * sizeof(MergeItem), 256);
+  plan->header_bytes = off;
+  plan->off_part_o = off;
+  off = align_up(off + (size_t)plan->num_partial_slots * M * D * sizeof(float), 256);
+  plan->off_part_ml = off;
+  off = align_up(off + (size_t)plan->num_partial_slots * M * 2 * sizeof(float), 256);
+  plan->total_bytes = off;
+}
+
+}  // namespace efim

@@ -1,0 +1,222 @@
+// efim_rope_append: rotary embedding of the new tokens at their offset positions and
+// append of their K/V into the paged cache (EFIM Sec. 1 / Sec. 3.1: the incremental tokens
+// come after the cached <P>prefix<S>suffix<M>, so token i of request r sits at position
+// C_r + i).  Streaming kernel, bound by HBM bandwidth: 2*(Hq + 2*Hkv)*D*2 bytes per token.
+//
+// The rotation is done in fp64 and rounded once to bf16 so that the cache contents agree
+// bit for bit with a double-precision definition.  One workgroup handles kTokens tokens:
+// first one thread per (token, pair index) evaluates sincos once and parks it in LDS, then
+// all threads stream the (Hq + 2*Hkv) head rows of those tokens with 16-byte accesses.
+#include "efim_internal.h"
+
+namespace efim {
+namespace {
+
+constexpr int kTokens = 4;       // tokens per workgroup
+constexpr int kThreads = 256;
+constexpr int kMaxReqPerLaunch = 384;
+
+struct RopeArgs {
+  double inv_freq[64];                      // base^(-2j/D), computed on the host
+  int32_t cached[kMaxReqPerLaunch];         // C_r of the requests of this launch
+  int32_t row_start[kMaxReqPerLaunch + 1];  // first packed row of each request, and the end
+  int32_t nreq;
+  int32_t req_base;                         // index of the first request (block_table row)
+  int32_t max_pages;
+  int32_t num_q_heads;
+  int32_t num_kv_heads;
+  int32_t rotate_q;                         // 0 when q is NULL
+};
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ double bf16_bits_to_f64(uint32_t bits16) {
+  return (double)__uint_as_float(bits16 << 16);
+}
+
+// fp64 -> bf16, round to nearest even, with a single rounding.  The conversion goes through
+// fp32; the only case where the detour could round twice is an inexact fp32 result sitting
+// exactly on a bf16 midpoint, which is nudged to the side the exact value lies on.
+__device__ __forceinline__ uint32_t f64_to_bf16_bits(double x) {
+  float f = (float)x;
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0xFFFFu) == 0x8000u) {
+    double back = (double)f;
+    if (back != x) u = (fabs(x) > fabs(back)) ? u + 1u : u - 1u;
+  }
+  // round to nearest even on the upper 16 bits (NaN stays NaN: quiet bit is in the upper half)
+  uint32_t lsb = (u >> 16) & 1u;
+  if ((u & 0x7F800000u) != 0x7F800000u) u += 0x7FFFu + lsb;
+  return u >> 16;
+}
+
+template <int D, bool INTERLEAVED>
+__global__ __launch_bounds__(kThreads) void rope_append_kernel(
+    const RopeArgs args, uint16_t* __restrict__ q, const uint16_t* __restrict__ k_new,
+    const uint16_t* __restrict__ v_new, uint16_t* __restrict__ k_cache,
+    uint16_t* __restrict__ v_cache, const int32_t* __restrict__ block_table) {
+#pragma clang fp contract(off)
+  constexpr int HALF = D / 2;
+  __shared__ double s_cos[kTokens][HALF];
+  __shared__ double s_sin[kTokens][HALF];
+  __shared__ int64_t s_dst[kTokens];  // element offset of (page, head 0, slot, 0) in the caches
+
+  const int tid = threadIdx.x;
+  const int first_row = args.row_start[0];
+  const int end_row = args.row_start[args.nreq];
+  const int tok0 = first_row + blockIdx.x * kTokens;
+
+  {
+    const int tt = tid >> 6;
+    const int j = tid & 63;
+    const int row = tok0 + tt;
+    if (j < HALF && row < end_row) {
+      // request of this row: last r with row_start[r] <= row < row_start[r + 1]
+      int lo = 0, hi = args.nreq;  // invariant: row_start[lo] <= row, row_start[hi] > row
+      while (hi - lo > 1) {
+        int mid = (lo + hi) >> 1;
+        if (args.row_start[mid] <= row) lo = mid; else hi = mid;
+      }
+      const int pos = args.cached[lo] + (row - args.row_start[lo]);
+      double s, c;
+      sincos((double)pos * args.inv_freq[j], &s, &c);
+      s_cos[tt][j] = c;
+      s_sin[tt][j] = s;
+      if (j == 0) {
+        const int64_t page =
+            block_table[(int64_t)(args.req_base + lo) * args.max_pages + (pos / kPageSize)];
+        s_dst[tt] = (page * args.num_kv_heads * kPageSize + (pos % kPageSize)) * D;
+      }
+    }
+  }
+  __syncthreads();
+
+  const int hq = args.num_q_heads, hkv = args.num_kv_heads;
+  // A unit is 16 bytes of one head row together with its partner 16 bytes: for rotate-half
+  // the chunk D/2 elements further on, for interleaved pairing (and for the plain copy of V)
+  // simply the next chunk.
+  constexpr int UNITS_PER_ROW = D / 16;
+  const int rows_per_tok = hq + 2 * hkv;
+  const int units_per_tok = rows_per_tok * UNITS_PER_ROW;
+  const int ntok = min(kTokens, end_row - tok0);
+  for (int u = tid; u < ntok * units_per_tok; u += kThreads) {
+    const int tt = u / units_per_tok;
+    const int w = u - tt * units_per_tok;
+    const int hr = w / UNITS_PER_ROW;   // 0..Hq-1: q heads, then Hkv k heads, then Hkv v heads
+    const int cp = w - hr * UNITS_PER_ROW;
+    const int64_t row = tok0 + tt;
+    int e0, e1;  // element offsets of the two chunks inside the head row
+    if (INTERLEAVED) { e0 = cp * 16; e1 = cp * 16 + 8; } else { e0 = cp * 8; e1 = cp * 8 + HALF; }
+
+    const uint16_t* src;
+    uint16_t* dst;
+    bool rotate = true;
+    if (hr < hq) {
+      if (!args.rotate_q) continue;
+      src = q + (row * hq + hr) * D;
+      dst = q + (row * hq + hr) * D;
+    } else if (hr < hq + hkv) {
+      const int h = hr - hq;
+      src = k_new + (row * hkv + h) * D;
+      dst = k_cache + s_dst[tt] + (int64_t)h * kPageSize * D;
+    } else {
+      const int h = hr - hq - hkv;
+      src = v_new + (row * hkv + h) * D;
+      dst = v_cache + s_dst[tt] + (int64_t)h * kPageSize * D;
+      rotate = false;
+    }
+    u32x4 a = *reinterpret_cast<const u32x4*>(src + e0);
+    u32x4 b = *reinterpret_cast<const u32x4*>(src + e1);
+    if (rotate) {
+      uint32_t xa[8], xb[8];
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        xa[2 * t] = a[t] & 0xFFFFu; xa[2 * t + 1] = a[t] >> 16;
+        xb[2 * t] = b[t] & 0xFFFFu; xb[2 * t + 1] = b[t] >> 16;
+      }
+      uint32_t ya[8], yb[8];
+      if (INTERLEAVED) {
+        // 16 consecutive elements = pairs 8*cp .. 8*cp+7, stored (even, odd)
+        uint32_t x[16], y[16];
+#pragma unroll
+        for (int t = 0; t < 8; ++t) { x[t] = xa[t]; x[8 + t] = xb[t]; }
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+          const int j = cp * 8 + t;
+          const double c = s_cos[tt][j], s = s_sin[tt][j];
+          const double x1 = bf16_bits_to_f64(x[2 * t]), x2 = bf16_bits_to_f64(x[2 * t + 1]);
+          y[2 * t] = f64_to_bf16_bits(x1 * c - x2 * s);
+          y[2 * t + 1] = f64_to_bf16_bits(x2 * c + x1 * s);
+        }
+#pragma unroll
+        for (int t = 0; t < 8; ++t) { ya[t] = y[t]; yb[t] = y[8 + t]; }
+      } else {
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+          const int j = cp * 8 + t;
+          const double c = s_cos[tt][j], s = s_sin[tt][j];
+          const double x1 = bf16_bits_to_f64(xa[t]), x2 = bf16_bits_to_f64(xb[t]);
+          ya[t] = f64_to_bf16_bits(x1 * c - x2 * s);
+          yb[t] = f64_to_bf16_bits(x2 * c + x1 * s);
+        }
+      }
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        a[t] = ya[2 * t] | (ya[2 * t + 1] << 16);
+        b[t] = yb[2 * t] | (yb[2 * t + 1] << 16);
+      }
+    }
+    *reinterpret_cast<u32x4*>(dst + e0) = a;
+    *reinterpret_cast<u32x4*>(dst + e1) = b;
+  }
+}
+
+}  // namespace
+
+int launch_rope_append(const efim_batch_t* b, int64_t total_new, void* q, const void* k_new,
+                       const void* v_new, void* k_cache, void* v_cache, double rope_base,
+                       int interleaved, hipStream_t stream) {
+  (void)total_new;
+  const int D = b->head_dim;
+  RopeArgs args;
+  for (int j = 0; j < 64; ++j) args.inv_freq[j] = 0.0;
+  for (int j = 0; j < D / 2; ++j) args.inv_freq[j] = pow(rope_base, -2.0 * j / D);
+  args.max_pages = b->max_pages_per_req;
+  args.num_q_heads = b->num_q_heads;
+  args.num_kv_heads = b->num_kv_heads;
+  args.rotate_q = q != nullptr;
+
+  int64_t row = 0;
+  for (int r0 = 0; r0 < b->batch; r0 += kMaxReqPerLaunch) {
+    const int n = (b->batch - r0 < kMaxReqPerLaunch) ? b->batch - r0 : kMaxReqPerLaunch;
+    const int64_t first = row;
+    for (int i = 0; i < n; ++i) {
+      args.cached[i] = b->cached_len[r0 + i];
+      args.row_start[i] = (int32_t)row;
+      row += b->new_len[r0 + i];
+    }
+    args.row_start[n] = (int32_t)row;
+    args.nreq = n;
+    args.req_base = r0;
+    const int64_t ntok = row - first;
+    if (ntok == 0) continue;
+    const dim3 grid((unsigned)((ntok + kTokens - 1) / kTokens));
+    auto qp = static_cast<uint16_t*>(q);
+    auto kn = static_cast<const uint16_t*>(k_new);
+    auto vn = static_cast<const uint16_t*>(v_new);
+    auto kc = static_cast<uint16_t*>(k_cache);
+    auto vc = static_cast<uint16_t*>(v_cache);
+    if (D == 128) {
+      if (interleaved) rope_append_kernel<128, true><<<grid, kThreads, 0, stream>>>(args, qp, kn, vn, kc, vc, b->block_table);
+      else rope_append_kernel<128, false><<<grid, kThreads, 0, stream>>>(args, qp, kn, vn, kc, vc, b->block_table);
+    } else {
+      if (interleaved) rope_append_kernel<64, true><<<grid, kThreads, 0, stream>>>(args, qp, kn, vn, kc, vc, b->block_table);
+      else rope_append_kernel<64, false><<<grid, kThreads, 0, stream>>>(args, qp, kn, vn, kc, vc, b->block_table);
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) { set_last_hip_error(e); return EFIM_ERR_LAUNCH; }
+  }
+  return EFIM_OK;
+}
+
+}  // namespace efim

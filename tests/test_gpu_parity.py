@@ -1,0 +1,172 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU oracle on the same
+seeded inputs.  Integer/byte work (append, gather) must be bit-exact; attention outputs from
+bf16 inputs with fp32 accumulation must reach max abs error <= 1e-2 and relative L2 <= 5e-3."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import efim_oracle as O
+from paper_2505_21889_amd import workloads as W
+
+import gpu_util as U
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def E():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2505_21889_amd import binding
+    return binding
+
+
+def _ragged(seed, cached, new, **kw):
+    return W.make_batch("c1", seed=seed, lengths=(np.array(cached, dtype=np.int32), np.array(new, dtype=np.int32)), **kw)
+
+
+# ------------------------------------------------------------ rope_append ----
+
+@pytest.mark.parametrize("name", ["c1", "c2", "c3"])
+def test_rope_append_bit_exact(E, name):
+    b = W.make_batch(name)
+    kc, vc = U.oracle_cache(b, fill=0xABCD)
+    q_gpu, kc_gpu, vc_gpu = U.gpu_rope_append(E, b, kc, vc)
+    q_ref, _ = O.rope_append(b.cached_len, b.new_len, b.block_table, b.page_size, b.q_new, b.k_new,
+                             b.v_new, kc, vc, b.rope_base)
+    assert np.array_equal(vc_gpu, vc)          # values: bit copy, and no other byte touched
+    assert np.array_equal(kc_gpu, kc)          # rotated keys: fp64 rotation, one rounding
+    assert np.array_equal(q_gpu, q_ref)
+
+
+@pytest.mark.parametrize("interleaved", [0, 1])
+@pytest.mark.parametrize("d", [64, 128])
+def test_rope_append_ragged_edges(E, interleaved, d):
+    # mid-page start, page-aligned start, empty request, single token, full miss, >3 pages
+    b = _ragged(77 + d, [5, 16, 9, 0, 0, 31], [27, 16, 0, 1, 70, 3], heads=(6, 2), head_dim=d)
+    kc, vc = U.oracle_cache(b, fill=0x1234)
+    q_gpu, kc_gpu, vc_gpu = U.gpu_rope_append(E, b, kc, vc, interleaved=interleaved)
+    q_ref, _ = O.rope_append(b.cached_len, b.new_len, b.block_table, b.page_size, b.q_new, b.k_new,
+                             b.v_new, kc, vc, b.rope_base, interleaved=bool(interleaved))
+    assert np.array_equal(vc_gpu, vc) and np.array_equal(kc_gpu, kc) and np.array_equal(q_gpu, q_ref)
+
+
+def test_rope_append_without_queries_and_large_positions(E):
+    b = _ragged(78, [100000, 65535], [5, 40], heads=(2, 2), head_dim=128, rope_base=1.0e6)
+    b.k_hist = b.v_hist = None
+    kc, vc = U.oracle_cache(b, fill=0)
+    _, kc_gpu, vc_gpu = U.gpu_rope_append(E, b, kc, vc, with_q=False)
+    O.rope_append(b.cached_len, b.new_len, b.block_table, b.page_size, None, b.k_new, b.v_new, kc, vc, b.rope_base)
+    assert np.array_equal(kc_gpu, kc) and np.array_equal(vc_gpu, vc)
+
+
+# ------------------------------------------------------- extend attention ----
+
+def _oracle_inputs(b):
+    kc, vc = U.oracle_cache(b)
+    q_roped, _ = O.rope_append(b.cached_len, b.new_len, b.block_table, b.page_size, b.q_new, b.k_new,
+                               b.v_new, kc, vc, b.rope_base)
+    return q_roped, kc, vc
+
+
+def test_extend_attention_c1_exhaustive(E):
+    b = W.make_batch("c1")
+    q_roped, kc, vc = _oracle_inputs(b)
+    ref = O.extend_attention(b.cached_len, b.new_len, b.block_table, b.page_size, q_roped, kc, vc)
+    got = U.gpu_extend_attention(E, b, q_roped, kc, vc)
+    U.assert_close(got, ref, "c1")
+
+
+@pytest.mark.parametrize("heads,d", [((4, 4), 64), ((6, 2), 128), ((8, 1), 128), ((7, 1), 64)])
+def test_extend_attention_ragged_small(E, heads, d):
+    # several 64-key tiles with ragged tails, rows spanning several waves, empty request,
+    # decode-like single token, full misses, a request shorter than one page
+    b = _ragged(90 + d + heads[0], [200, 0, 63, 129, 0, 5, 1000], [37, 150, 1, 64, 3, 0, 9], heads=heads, head_dim=d)
+    q_roped, kc, vc = _oracle_inputs(b)
+    ref = O.extend_attention(b.cached_len, b.new_len, b.block_table, b.page_size, q_roped, kc, vc)
+    got = U.gpu_extend_attention(E, b, q_roped, kc, vc)
+    U.assert_close(got, ref, "ragged")
+
+
+@pytest.mark.parametrize("split", [0, 64, 256])
+def test_extend_attention_split_kv_agrees(E, split):
+    b = _ragged(95, [700, 0, 300], [40, 300, 2], heads=(4, 2), head_dim=128)
+    q_roped, kc, vc = _oracle_inputs(b)
+    ref = O.extend_attention(b.cached_len, b.new_len, b.block_table, b.page_size, q_roped, kc, vc)
+    E.efim_set_tuning(E.EFIM_TUNE_SPLIT_KV, split)
+    try:
+        got = U.gpu_extend_attention(E, b, q_roped, kc, vc)
+    finally:
+        E.efim_set_tuning(E.EFIM_TUNE_SPLIT_KV, -1)
+    U.assert_close(got, ref, "split %d" % split)
+
+
+def test_single_key_is_bit_exact_value_row(E):
+    b = _ragged(96, [0, 0], [1, 1], heads=(6, 2), head_dim=128)
+    q_roped, kc, vc = _oracle_inputs(b)
+    got = U.gpu_extend_attention(E, b, q_roped, kc, vc)
+    for r in range(2):
+        for a in range(6):
+            assert np.array_equal(got[r, a], b.v_new[r, a // 3])
+
+
+def test_zero_query_gives_running_mean(E):
+    b = _ragged(97, [130, 0], [70, 66], heads=(2, 1), head_dim=128)
+    q_roped, kc, vc = _oracle_inputs(b)
+    q0 = np.zeros_like(q_roped)
+    ref = O.extend_attention(b.cached_len, b.new_len, b.block_table, b.page_size, q0, kc, vc)
+    got = U.gpu_extend_attention(E, b, q0, kc, vc)
+    U.assert_close(got, ref, "q=0")
+
+
+def test_page_permutation_invariance_bit_exact(E):
+    b = W.make_batch("c1", seed=98)
+    q_roped, kc, vc = _oracle_inputs(b)
+    got = U.gpu_extend_attention(E, b, q_roped, kc, vc)
+    perm = np.random.default_rng(2).permutation(b.num_pages)
+    kc2, vc2 = np.empty_like(kc), np.empty_like(vc)
+    kc2[perm], vc2[perm] = kc, vc
+    got2 = U.gpu_extend_attention(E, b, q_roped, kc2, vc2, table=perm[b.block_table].astype(np.int32))
+    assert np.array_equal(got, got2)
+
+
+def test_sm_scale_argument(E):
+    b = _ragged(99, [90], [20], heads=(2, 2), head_dim=64)
+    q_roped, kc, vc = _oracle_inputs(b)
+    ref = O.extend_attention(b.cached_len, b.new_len, b.block_table, b.page_size, q_roped, kc, vc, sm_scale=0.31)
+    got = U.gpu_extend_attention(E, b, q_roped, kc, vc, sm_scale=0.31)
+    U.assert_close(got, ref, "scale")
+
+
+def test_repeated_runs_are_deterministic(E):
+    b = _ragged(100, [500, 0], [33, 200], heads=(4, 1), head_dim=128)
+    q_roped, kc, vc = _oracle_inputs(b)
+    first = U.gpu_extend_attention(E, b, q_roped, kc, vc)
+    for _ in range(3):
+        assert np.array_equal(U.gpu_extend_attention(E, b, q_roped, kc, vc), first)
+
+
+def test_end_to_end_gpu_append_then_attention_equals_full_recompute(E):
+    """Both calls on the GPU, cache built by the library itself in two shots (history, then
+    the new tokens), against the oracle's cache-free recomputation of the whole prompt."""
+    rng = np.random.default_rng(5)
+    b = _ragged(101, [150, 0, 64], [45, 80, 17], heads=(4, 2), head_dim=128)
+    # shot 1: the history as a miss (C = 0, N = C_r); shot 2: the new tokens
+    hist = W.ExtendBatch(b.name, b.num_q_heads, b.num_kv_heads, b.head_dim, b.page_size, b.rope_base, b.sigma,
+                         np.zeros_like(b.cached_len), b.cached_len.copy(), b.block_table, b.num_pages,
+                         W.gaussian_bf16(rng, (int(b.cached_len.sum()), b.num_q_heads, b.head_dim), 1.0),
+                         b.k_hist, b.v_hist)
+    kc, vc = W.poisoned_cache(b), W.poisoned_cache(b)
+    _, kc, vc = U.gpu_rope_append(E, hist, kc, vc)
+    q_gpu, kc, vc = U.gpu_rope_append(E, b, kc, vc)
+    got = U.gpu_extend_attention(E, b, q_gpu, kc, vc)
+    hs = ns = 0
+    for r in range(b.batch):
+        c, n = int(b.cached_len[r]), int(b.new_len[r])
+        k_all = np.concatenate([b.k_hist[hs:hs + c], b.k_new[ns:ns + n]])
+        v_all = np.concatenate([b.v_hist[hs:hs + c], b.v_new[ns:ns + n]])
+        q_all = np.concatenate([hist.q_new[hs:hs + c], b.q_new[ns:ns + n]])
+        ref = O.full_recompute(q_all, k_all, v_all, b.rope_base)[-n:]
+        U.assert_close(got[ns:ns + n], ref, "request %d" % r)
+        hs += c
+        ns += n
