@@ -1,0 +1,260 @@
+#!/usr/bin/env python3
+"""Benchmark of the EFIM serving hot path on one MI355X.
+
+A step is one pass of the whole path over one synthetic ragged batch:
+efim_rope_append (RoPE at offset positions + paged KV append) followed by
+efim_extend_attention, i.e. one attention layer's worth of a serving step (no
+projections or MLP: those are not part of this path).  The headline workload is
+the mixed serving step (64 requests, half cache hits, half misses); the other
+workloads and the fixed-inc sweeps are reported in the same JSON line under
+"workloads".
+
+Prints ONE JSON line.  All inputs are seeded and synthetic and resident in HBM
+before the timed region starts.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak
+PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E peak
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="c5", help="headline workload (c2..c5)")
+    ap.add_argument("--no-extra", action="store_true", help="skip the other workloads and sweeps")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--extra-iters", type=int, default=30)
+    return ap.parse_args()
+
+
+class DeviceBatch:
+    """A workload's lengths and block table plus `copies` independent sets of device tensors
+    (rotated between iterations so that the 256 MB last-level cache cannot hold the K/V)."""
+
+    def __init__(self, torch, E, W, name, lengths=None, copies=1, seed=0):
+        self.name = name
+        self.host = W.make_batch(name, with_history=False, with_tensors=False, lengths=lengths)
+        b = self.host
+        self.table = torch.from_numpy(b.block_table).cuda()
+        self.desc = E.BatchDesc(b.cached_len, b.new_len, self.table, b.num_q_heads, b.num_kv_heads,
+                                b.head_dim, b.page_size, b.num_pages)
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(1000 + seed)
+        t = b.total_new
+
+        def gauss(shape):
+            x = torch.empty(shape, dtype=torch.float32, device="cuda")
+            x.normal_(0.0, b.sigma, generator=gen)
+            return x.to(torch.bfloat16)
+
+        self.sets = []
+        for _ in range(copies):
+            s = {
+                # a rotation of iid Gaussian pairs is again Gaussian, so the cached part of the
+                # cache is drawn directly instead of being built by appending a history
+                "k_cache": gauss(b.cache_shape()), "v_cache": gauss(b.cache_shape()),
+                "q_raw": gauss((t, b.num_q_heads, b.head_dim)),
+                "k_new": gauss((t, b.num_kv_heads, b.head_dim)),
+                "v_new": gauss((t, b.num_kv_heads, b.head_dim)),
+            }
+            s["q"] = s["q_raw"].clone()
+            s["out"] = torch.empty_like(s["q"])
+            self.sets.append(s)
+        self.ws_bytes = E.efim_extend_workspace_bytes(self.desc)
+        self.ws = torch.empty(max(self.ws_bytes, 256), dtype=torch.uint8, device="cuda")
+        self.flops = W.attention_flops(b)
+        self.attn_bytes = W.attention_bytes(b)
+        self.rope_bytes = W.rope_append_bytes(b)
+
+
+def run_step(E, db, s, stream):
+    b = db.host
+    E.efim_rope_append(db.desc, s["q"], s["k_new"], s["v_new"], s["k_cache"], s["v_cache"], b.rope_base, 0, stream)
+    E.efim_extend_attention(db.desc, s["q"], s["k_cache"], s["v_cache"], s["out"], 0.0, db.ws, db.ws_bytes, stream)
+
+
+def time_parts(torch, E, db, iters, warmup):
+    """Per-call device times (HIP events on the launch stream): rope_append, the whole
+    efim_extend_attention call, and its main kernel alone.  Returns median/min in microseconds."""
+    stream = torch.cuda.current_stream()
+    ev = [E.HipEvent() for _ in range(4)]
+    k0, k1 = E.HipEvent(), E.HipEvent()
+    E.efim_set_kernel_events(k0.ptr, k1.ptr)
+    rope, attn, kern = [], [], []
+    b = db.host
+    try:
+        for it in range(warmup + iters):
+            s = db.sets[it % len(db.sets)]
+            s["q"].copy_(s["q_raw"])
+            ev[0].record(stream)
+            E.efim_rope_append(db.desc, s["q"], s["k_new"], s["v_new"], s["k_cache"], s["v_cache"], b.rope_base, 0, stream)
+            ev[1].record(stream)
+            ev[2].record(stream)
+            E.efim_extend_attention(db.desc, s["q"], s["k_cache"], s["v_cache"], s["out"], 0.0, db.ws, db.ws_bytes, stream)
+            ev[3].record(stream)
+            ev[3].synchronize()
+            if it >= warmup:
+                rope.append(ev[0].elapsed_ms(ev[1]) * 1e3)
+                attn.append(ev[2].elapsed_ms(ev[3]) * 1e3)
+                kern.append(k0.elapsed_ms(k1) * 1e3)
+    finally:
+        E.efim_set_kernel_events(None, None)
+    med = lambda x: float(np.median(x))
+    return {"rope_us": med(rope), "attn_call_us": med(attn), "attn_kernel_us": med(kern),
+            "attn_kernel_us_mean": float(np.mean(kern)), "attn_kernel_us_min": float(np.min(kern))}
+
+
+def summarize(db, parts):
+    us = parts["attn_kernel_us"]
+    call = parts["attn_call_us"]
+    return {
+        "T_new": db.host.total_new,
+        "rope_append_us": round(parts["rope_us"], 2),
+        "rope_append_GBps": round(db.rope_bytes / parts["rope_us"] / 1e3, 1),
+        "rope_append_frac_hbm": round(db.rope_bytes / parts["rope_us"] / 1e3 / PEAK_HBM_GBPS, 4),
+        "attn_call_us": round(call, 2),
+        "attn_kernel_us": round(us, 2),
+        "attn_TFLOPs": round(db.flops / call / 1e6, 2),
+        "attn_frac_mfma": round(db.flops / call / 1e6 / PEAK_BF16_TFLOPS, 4),
+        "attn_GBps": round(db.attn_bytes / call / 1e3, 1),
+        "attn_frac_hbm": round(db.attn_bytes / call / 1e3 / PEAK_HBM_GBPS, 4),
+        "step_us": round(parts["rope_us"] + call, 2),
+    }
+
+
+def cpu_baseline(W, name):
+    """The CPU oracle timed on a bounded sample of the headline workload."""
+    from oracle import efim_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    full = W.make_batch(name, with_history=False, with_tensors=False)
+    c, n = full.cached_len, full.new_len
+    if name == "c5":
+        hits = [r for r in range(len(c)) if c[r] > 0][:4]
+        misses = [r for r in range(len(c)) if c[r] == 0][:1]
+        sel = sorted(hits + misses)
+        what = "requests %s of the mixed step (4 hits, 1 miss), all heads" % sel
+    else:
+        sel = list(range(min(2, len(c))))
+        what = "requests %s, all heads" % sel
+    b = W.make_batch(name, with_history=False, lengths=(c[sel], n[sel]), seed=4242)
+    rng = np.random.default_rng(4243)
+    kc = W.gaussian_bf16(rng, b.cache_shape(), b.sigma)
+    vc = W.gaussian_bf16(rng, b.cache_shape(), b.sigma)
+    t0 = time.perf_counter()
+    q_roped, _ = O.rope_append(b.cached_len, b.new_len, b.block_table, b.page_size, b.q_new, b.k_new,
+                               b.v_new, kc, vc, b.rope_base)
+    O.extend_attention(b.cached_len, b.new_len, b.block_table, b.page_size, q_roped, kc, vc)
+    dt = time.perf_counter() - t0
+    flops = W.attention_flops(b)
+    return {"value": round(flops / dt / 1e12, 5), "unit": "TFLOP/s", "cores": int(threads), "kind": "oracle",
+            "sample": what + "; %.1f s, %.3e flop" % (dt, flops), "seconds": round(dt, 2)}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        sys.stderr.write("bench.py: this path runs on ONE GPU only (no sharding, no collectives); "
+                         "--gpus %d is not supported\n" % args.gpus)
+        sys.exit(2)
+    import torch
+    from paper_2505_21889_amd import binding as E, workloads as W
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    stream = torch.cuda.current_stream()
+
+    name = args.workload
+    copies = 1 if name == "c5" else 3
+    db = DeviceBatch(torch, E, W, name, copies=copies)
+
+    # ---- headline: K timed steps, wall clock around a synchronised region ------------
+    for it in range(args.warmup):
+        run_step(E, db, db.sets[it % copies], stream)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for it in range(args.steps):
+        run_step(E, db, db.sets[it % copies], stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall / args.steps * 1e3
+
+    parts = time_parts(torch, E, db, iters=max(5, min(args.steps, 30)), warmup=2)
+    head = summarize(db, parts)
+    kernel_us = parts["attn_kernel_us_mean"]
+    mfma_bound = db.flops / PEAK_BF16_TFLOPS / 1e12 >= db.attn_bytes / PEAK_HBM_GBPS / 1e9
+    if mfma_bound:
+        ach = db.flops / kernel_us / 1e6
+        roofline = {"bound": "mfma", "achieved": round(ach, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                    "frac": round(ach / PEAK_BF16_TFLOPS, 4), "traffic": None}
+    else:
+        ach = db.attn_bytes / kernel_us / 1e3
+        roofline = {"bound": "hbm", "achieved": round(ach, 1), "peak": PEAK_HBM_GBPS, "unit": "GB/s",
+                    "frac": round(ach / PEAK_HBM_GBPS, 4), "traffic": None}
+    roofline["kernel"] = "extend_attention_kernel<%d>" % db.host.head_dim
+    roofline["kernel_avg_us"] = round(kernel_us, 2)
+
+    result = {
+        "metric": "extend-attention TFLOP/s over one serving step (rope_append + extend_attention)",
+        "value": round(db.flops / (ms_per_step * 1e-3) / 1e12, 2),
+        "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "us_per_step": round(ms_per_step * 1e3, 1),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "%s: %s" % (name, W.SPECS[name].describe), "batch": db.host.batch,
+                   "total_new_tokens": db.host.total_new, "page_size": db.host.page_size,
+                   "heads": "%d/%d" % (db.host.num_q_heads, db.host.num_kv_heads), "head_dim": db.host.head_dim},
+        "pct_bf16_mfma_peak": round(100 * db.flops / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 2),
+        "step_hbm_GBps": round((db.attn_bytes + db.rope_bytes) / (ms_per_step * 1e-3) / 1e9, 1),
+        "headline_parts": head,
+        "roofline": roofline,
+    }
+    del db
+    torch.cuda.empty_cache()
+
+    # ---- the other workloads and the fixed-inc sweeps (device times per call) ---------
+    if not args.no_extra:
+        extra = {}
+        todo = [(n, None) for n in ("c2", "c3", "c4", "c5") if n != name]
+        for base in ("c2", "c3"):
+            spec = W.make_batch(base, with_history=False, with_tensors=False)
+            for inc in (1, 8, 16):
+                todo.append(("%s_inc%d" % (base, inc), (base, (spec.cached_len, np.full_like(spec.new_len, inc)))))
+        spec = W.make_batch("c4", with_history=False, with_tensors=False)
+        for inc in (256, 1024):
+            todo.append(("c4_inc%d" % inc, ("c4", (spec.cached_len, np.full_like(spec.new_len, inc)))))
+        for label, over in todo:
+            base, lengths = (label, None) if over is None else over
+            d = DeviceBatch(torch, E, W, base, lengths=lengths, copies=1 if base == "c5" else 3)
+            extra[label] = summarize(d, time_parts(torch, E, d, iters=args.extra_iters, warmup=5))
+            del d
+            torch.cuda.empty_cache()
+        result["workloads"] = extra
+
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(W, name)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

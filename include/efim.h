@@ -158,6 +158,13 @@ typedef enum efim_tuning_key {
 
 int efim_set_tuning(int key, int value);
 
+/*
+ * Timing hook for benchmarks.  While both handles (hipEvent_t passed as void*) are non-NULL,
+ * every efim_extend_attention call records `start` immediately before and `stop` immediately
+ * after its main attention kernel, on the call's stream.  Pass NULLs to clear.  Process-wide.
+ */
+int efim_set_kernel_events(void* start, void* stop);
+
 const char* efim_status_string(int status);
 int efim_last_hip_error(void); /* hipError_t of the most recent EFIM_ERR_LAUNCH on this thread */
 int efim_version(void);        /* major * 10000 + minor * 100 + patch */

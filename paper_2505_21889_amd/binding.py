@@ -74,6 +74,8 @@ def _load():
     lib.efim_extend_plan_items.restype = i64
     lib.efim_set_tuning.argtypes = [i32, i32]
     lib.efim_set_tuning.restype = i32
+    lib.efim_set_kernel_events.argtypes = [vp, vp]
+    lib.efim_set_kernel_events.restype = i32
     lib.efim_status_string.argtypes = [i32]
     lib.efim_status_string.restype = ctypes.c_char_p
     lib.efim_last_hip_error.argtypes = []
@@ -87,7 +89,7 @@ _lib = _load()
 LIBRARY_PATH = _build.LIB_PATH
 EXPORTED_SYMBOLS = (
     "efim_rope_append", "efim_extend_workspace_bytes", "efim_extend_attention",
-    "efim_extend_plan_items", "efim_set_tuning", "efim_status_string",
+    "efim_extend_plan_items", "efim_set_tuning", "efim_set_kernel_events", "efim_status_string",
     "efim_last_hip_error", "efim_version",
 )
 
@@ -171,6 +173,10 @@ def efim_set_tuning(key, value):
     _check(_lib.efim_set_tuning(int(key), int(value)), "efim_set_tuning")
 
 
+def efim_set_kernel_events(start, stop):
+    _check(_lib.efim_set_kernel_events(_ptr(start), _ptr(stop)), "efim_set_kernel_events")
+
+
 def efim_status_string(status):
     return _lib.efim_status_string(int(status)).decode()
 
@@ -186,3 +192,47 @@ def efim_version():
 def raw_library():
     """The ctypes handle, for tests that exercise error returns of the C functions."""
     return _lib
+
+
+class HipEvent:
+    """A timing hipEvent_t created through the HIP runtime (used by the benchmark)."""
+    _hip = None
+
+    @classmethod
+    def _rt(cls):
+        if cls._hip is None:
+            hip = ctypes.CDLL("libamdhip64.so")
+            hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+            hip.hipEventRecord.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
+            hip.hipEventSynchronize.argtypes = [ctypes.c_void_p]
+            hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+            hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+            cls._hip = hip
+        return cls._hip
+
+    def __init__(self):
+        self.handle = ctypes.c_void_p()
+        rc = self._rt().hipEventCreate(ctypes.byref(self.handle))
+        if rc != 0:
+            raise RuntimeError("hipEventCreate failed: %d" % rc)
+
+    @property
+    def ptr(self):
+        return self.handle.value
+
+    def record(self, stream=None):
+        rc = self._rt().hipEventRecord(self.handle, _stream_ptr(stream))
+        if rc != 0:
+            raise RuntimeError("hipEventRecord failed: %d" % rc)
+
+    def synchronize(self):
+        rc = self._rt().hipEventSynchronize(self.handle)
+        if rc != 0:
+            raise RuntimeError("hipEventSynchronize failed: %d" % rc)
+
+    def elapsed_ms(self, end):
+        ms = ctypes.c_float()
+        rc = self._rt().hipEventElapsedTime(ctypes.byref(ms), self.handle, end.handle)
+        if rc != 0:
+            raise RuntimeError("hipEventElapsedTime failed: %d" % rc)
+        return float(ms.value)

@@ -80,6 +80,44 @@ int stage_and_copy(const Plan& plan, void* workspace, hipStream_t stream) {
   return EFIM_OK;
 }
 
+// A serving engine calls efim_extend_attention once per layer with the same batch, so the last
+// plan is kept and reused while the host-visible batch description and the knobs are unchanged.
+struct PlanCache {
+  std::vector<int32_t> key;
+  Plan plan;
+  bool valid = false;
+};
+PlanCache g_plan_cache;
+std::mutex g_plan_mutex;
+
+void plan_key(const efim_batch_t* b, int slots, std::vector<int32_t>* key) {
+  const Tuning& t = tuning();
+  key->clear();
+  key->reserve(2 * (size_t)b->batch + 8);
+  key->push_back(b->batch);
+  key->push_back(b->num_q_heads);
+  key->push_back(b->num_kv_heads);
+  key->push_back(b->head_dim);
+  key->push_back(slots);
+  key->push_back(t.split_kv);
+  key->push_back(t.xcd_grouping);
+  key->insert(key->end(), b->cached_len, b->cached_len + b->batch);
+  key->insert(key->end(), b->new_len, b->new_len + b->batch);
+}
+
+// Returns a copy-free reference valid while g_plan_mutex is held by the caller.
+const Plan& cached_plan(const efim_batch_t* b) {
+  static thread_local std::vector<int32_t> key;
+  const int slots = num_slots();
+  plan_key(b, slots, &key);
+  if (!g_plan_cache.valid || g_plan_cache.key != key) {
+    build_plan(b, slots, &g_plan_cache.plan);
+    g_plan_cache.key = key;
+    g_plan_cache.valid = true;
+  }
+  return g_plan_cache.plan;
+}
+
 }  // namespace
 
 void set_last_hip_error(hipError_t e) { g_last_hip_error = (int)e; }
@@ -109,8 +147,8 @@ int efim_rope_append(const efim_batch_t* batch, void* q, const void* k_new, cons
 size_t efim_extend_workspace_bytes(const efim_batch_t* batch) {
   int64_t total = 0;
   if (validate_batch(batch, &total) != EFIM_OK) return 0;
-  Plan plan;
-  build_plan(batch, num_slots(), &plan);
+  std::lock_guard<std::mutex> lock(g_plan_mutex);
+  const Plan& plan = cached_plan(batch);
   return plan.total_bytes < 256 ? 256 : plan.total_bytes;
 }
 
@@ -127,8 +165,8 @@ int efim_extend_attention(const efim_batch_t* batch, const void* q, const void* 
   if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(out) ||
       (reinterpret_cast<uintptr_t>(batch->block_table) & 3u))
     return EFIM_ERR_INVALID_ARG;
-  Plan plan;
-  build_plan(batch, num_slots(), &plan);
+  std::lock_guard<std::mutex> lock(g_plan_mutex);
+  const Plan& plan = cached_plan(batch);
   if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) || workspace_bytes < plan.total_bytes)
     return EFIM_ERR_WORKSPACE;
   if (sm_scale == 0.f) sm_scale = 1.0f / sqrtf((float)batch->head_dim);
@@ -143,8 +181,8 @@ int64_t efim_extend_plan_items(const efim_batch_t* batch, efim_work_item_t* item
   int rc = validate_batch(batch, &total);
   if (rc != EFIM_OK) return rc;
   if (capacity < 0 || (capacity > 0 && !items)) return EFIM_ERR_INVALID_ARG;
-  Plan plan;
-  build_plan(batch, num_slots(), &plan);
+  std::lock_guard<std::mutex> lock(g_plan_mutex);
+  const Plan& plan = cached_plan(batch);
   const int64_t n = (int64_t)plan.items.size();
   for (int64_t i = 0; i < n && i < capacity; ++i) items[i] = plan.items[i];
   return n;
@@ -167,6 +205,13 @@ int efim_set_tuning(int key, int value) {
     default:
       return EFIM_ERR_INVALID_ARG;
   }
+}
+
+int efim_set_kernel_events(void* start, void* stop) {
+  if ((start == nullptr) != (stop == nullptr)) return EFIM_ERR_INVALID_ARG;
+  tuning().ev_start = static_cast<hipEvent_t>(start);
+  tuning().ev_stop = static_cast<hipEvent_t>(stop);
+  return EFIM_OK;
 }
 
 const char* efim_status_string(int status) {

@@ -38,6 +38,8 @@ struct MergeItem {
 };
 
 struct Tuning {
+  hipEvent_t ev_start = nullptr;
+  hipEvent_t ev_stop = nullptr;
   int split_kv = -1;
   int xcd_grouping = 1;
   int num_slots = 0;

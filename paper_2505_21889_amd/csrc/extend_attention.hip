@@ -330,12 +330,15 @@ int launch_extend_attention(const efim_batch_t* b, const Plan& plan, const void*
   const MergeItem* merges = reinterpret_cast<const MergeItem*>(ws + plan.off_merges);
 
   const dim3 grid((unsigned)plan.items.size());
+  const Tuning& tn = tuning();
+  if (tn.ev_start) (void)hipEventRecord(tn.ev_start, stream);
   if (b->head_dim == 128) {
     extend_attention_kernel<128><<<grid, kThreads, 2 * Geometry<128>::kStageBytes, stream>>>(p);
   } else {
     extend_attention_kernel<64><<<grid, kThreads, 2 * Geometry<64>::kStageBytes, stream>>>(p);
   }
   hipError_t e = hipGetLastError();
+  if (tn.ev_stop) (void)hipEventRecord(tn.ev_stop, stream);
   if (e != hipSuccess) { set_last_hip_error(e); return EFIM_ERR_LAUNCH; }
   if (!plan.merges.empty()) {
     const dim3 mgrid((unsigned)plan.merges.size());

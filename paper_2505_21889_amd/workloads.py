@@ -143,7 +143,7 @@ def make_block_table(cached_len, new_len, page_size, rng, spare_fraction=0.125):
 
 
 def make_batch(name, seed=None, with_history=True, lengths=None, heads=None,
-               head_dim=None, page_size=None, sigma=None, rope_base=None):
+               head_dim=None, page_size=None, sigma=None, rope_base=None, with_tensors=True):
     """Draw a batch of the named workload.
 
     ``lengths=(cached_len, new_len)`` overrides the drawn lengths (used by the
@@ -166,6 +166,9 @@ def make_batch(name, seed=None, with_history=True, lengths=None, heads=None,
         n = np.asarray(lengths[1], dtype=np.int32)
     table, num_pages = make_block_table(c, n, p, rng)
     t = int(n.sum())
+    if not with_tensors:
+        # lengths and block table only: callers draw the tensors themselves (on the device)
+        return ExtendBatch(name, hq, hkv, d, p, base, sg, c, n, table, num_pages, None, None, None)
     q = gaussian_bf16(rng, (t, hq, d), sg)
     k = gaussian_bf16(rng, (t, hkv, d), sg)
     v = gaussian_bf16(rng, (t, hkv, d), sg)
