@@ -30,10 +30,13 @@ int num_slots() {
   return cached;
 }
 
-// Ring of pinned host buffers through which work lists travel to the device.  A slot is
-// reused only after the copy that read it has finished (event recorded behind the copy).
+// Ring of pinned, device-mapped host buffers holding work lists.  The kernels read their
+// (small) work items straight from this memory, so no copy sits between planning and launch.
+// A slot is reused only after the kernels that read it have finished (event recorded behind
+// the last launch of the call).
 struct StageSlot {
   void* host = nullptr;
+  void* dev = nullptr;  // device-side address of the same memory
   size_t capacity = 0;
   hipEvent_t done = nullptr;
   bool in_flight = false;
@@ -43,28 +46,32 @@ StageSlot g_stage[kStageSlots];
 int g_stage_next = 0;
 std::mutex g_stage_mutex;
 
-int stage_and_copy(const Plan& plan, void* workspace, hipStream_t stream) {
-  std::lock_guard<std::mutex> lock(g_stage_mutex);
+#define EFIM_HIP(expr)                                  \
+  do {                                                  \
+    hipError_t e_ = (expr);                             \
+    if (e_ != hipSuccess) {                             \
+      set_last_hip_error(e_);                           \
+      return EFIM_ERR_LAUNCH;                           \
+    }                                                   \
+  } while (0)
+
+// Copies the plan header into the next free slot; *dev_header receives its device address.
+int stage_plan(const Plan& plan, StageSlot** slot_out, const char** dev_header) {
   StageSlot& s = g_stage[g_stage_next];
   g_stage_next = (g_stage_next + 1) % kStageSlots;
-  hipError_t e;
-  if (!s.done) {
-    e = hipEventCreateWithFlags(&s.done, hipEventDisableTiming);
-    if (e != hipSuccess) { set_last_hip_error(e); return EFIM_ERR_LAUNCH; }
-  }
+  if (!s.done) EFIM_HIP(hipEventCreateWithFlags(&s.done, hipEventDisableTiming));
   if (s.in_flight) {
-    e = hipEventSynchronize(s.done);
-    if (e != hipSuccess) { set_last_hip_error(e); return EFIM_ERR_LAUNCH; }
+    EFIM_HIP(hipEventSynchronize(s.done));
     s.in_flight = false;
   }
   if (s.capacity < plan.header_bytes) {
     if (s.host) (void)hipHostFree(s.host);
-    s.host = nullptr;
+    s.host = s.dev = nullptr;
     s.capacity = 0;
     size_t cap = 1 << 16;
     while (cap < plan.header_bytes) cap <<= 1;
-    e = hipHostMalloc(&s.host, cap, hipHostMallocDefault);
-    if (e != hipSuccess) { set_last_hip_error(e); return EFIM_ERR_LAUNCH; }
+    EFIM_HIP(hipHostMalloc(&s.host, cap, hipHostMallocMapped));
+    EFIM_HIP(hipHostGetDevicePointer(&s.dev, s.host, 0));
     s.capacity = cap;
   }
   char* h = static_cast<char*>(s.host);
@@ -72,11 +79,8 @@ int stage_and_copy(const Plan& plan, void* workspace, hipStream_t stream) {
   std::memcpy(h + plan.off_items, plan.items.data(), plan.items.size() * sizeof(WorkItem));
   if (!plan.merges.empty())
     std::memcpy(h + plan.off_merges, plan.merges.data(), plan.merges.size() * sizeof(MergeItem));
-  e = hipMemcpyAsync(workspace, s.host, plan.header_bytes, hipMemcpyHostToDevice, stream);
-  if (e != hipSuccess) { set_last_hip_error(e); return EFIM_ERR_LAUNCH; }
-  e = hipEventRecord(s.done, stream);
-  if (e != hipSuccess) { set_last_hip_error(e); return EFIM_ERR_LAUNCH; }
-  s.in_flight = true;
+  *slot_out = &s;
+  *dev_header = static_cast<const char*>(s.dev);
   return EFIM_OK;
 }
 
@@ -171,9 +175,16 @@ int efim_extend_attention(const efim_batch_t* batch, const void* q, const void* 
     return EFIM_ERR_WORKSPACE;
   if (sm_scale == 0.f) sm_scale = 1.0f / sqrtf((float)batch->head_dim);
   hipStream_t s = static_cast<hipStream_t>(stream);
-  rc = stage_and_copy(plan, workspace, s);
+  std::lock_guard<std::mutex> stage_lock(g_stage_mutex);
+  StageSlot* slot = nullptr;
+  const char* header = nullptr;
+  rc = stage_plan(plan, &slot, &header);
   if (rc != EFIM_OK) return rc;
-  return launch_extend_attention(batch, plan, q, k_cache, v_cache, out, sm_scale, workspace, s);
+  rc = launch_extend_attention(batch, plan, header, q, k_cache, v_cache, out, sm_scale, workspace, s);
+  // the slot is busy until everything enqueued so far on the stream has run
+  if (hipEventRecord(slot->done, s) == hipSuccess) slot->in_flight = true;
+  else (void)hipStreamSynchronize(s);
+  return rc;
 }
 
 int64_t efim_extend_plan_items(const efim_batch_t* batch, efim_work_item_t* items, int64_t capacity) {

@@ -52,9 +52,10 @@ struct Plan {
   std::vector<WorkItem> items;
   std::vector<MergeItem> merges;
   int64_t num_partial_slots = 0;
-  // byte offsets inside the device workspace
-  size_t off_reqs = 0, off_items = 0, off_merges = 0, off_part_o = 0, off_part_ml = 0, total_bytes = 0;
-  size_t header_bytes = 0;  // bytes that are copied from the host (reqs + items + merges)
+  // byte offsets of reqs / items / merges inside the staged plan header
+  size_t off_reqs = 0, off_items = 0, off_merges = 0, header_bytes = 0;
+  // byte offsets of the split-KV partial results inside the device workspace, and its size
+  size_t off_part_o = 0, off_part_ml = 0, total_bytes = 0;
 };
 
 // Validates the host-visible part of a batch. total_new receives T.
@@ -67,7 +68,9 @@ int launch_rope_append(const efim_batch_t* b, int64_t total_new, void* q, const 
                        const void* v_new, void* k_cache, void* v_cache, double rope_base,
                        int interleaved, hipStream_t stream);
 
-int launch_extend_attention(const efim_batch_t* b, const Plan& plan, const void* q,
+// `header` is the device-visible address of the staged plan header (reqs, items, merges at
+// the plan's offsets); `workspace` holds the split-KV partial results.
+int launch_extend_attention(const efim_batch_t* b, const Plan& plan, const char* header, const void* q,
                             const void* k_cache, const void* v_cache, void* out, float sm_scale,
                             void* workspace, hipStream_t stream);
 

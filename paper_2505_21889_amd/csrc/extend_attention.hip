@@ -48,6 +48,29 @@ struct AttnParams {
 
 constexpr int kThreads = 64 * kWavesPerGroup;
 
+constexpr float kSlack = 8.f;  // log2 units by which a row max may outgrow its reference
+
+__device__ __forceinline__ float max3(float a, float b, float c) {
+  float r;
+  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+  return r;
+}
+
+// Direct HBM -> LDS copy of 16 bytes per lane: lane l's data lands at lds_base + 16 * l
+// (lds_base is wave-uniform and travels in M0).  Issued as inline assembly so that the
+// compiler does not order LDS reads of OTHER buffers behind it; completion is awaited
+// explicitly with s_waitcnt vmcnt before the workgroup barrier that publishes the buffer.
+__device__ __forceinline__ void load_to_lds_16(const void* gptr, const void* lds_base) {
+  const uint32_t lds_addr = (uint32_t)(uintptr_t)(LDS_PTR(const char))lds_base;
+  asm volatile(
+      "s_mov_b32 m0, %0\n\t"
+      "s_nop 0\n\t"
+      "global_load_lds_dwordx4 %1, off"
+      :
+      : "s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(gptr)
+      : "memory");
+}
+
 template <int D>
 struct Geometry {
   static constexpr int kRowBytes = D * 2;            // one key/value row
@@ -67,7 +90,12 @@ struct Geometry {
 template <int D>
 __global__ __launch_bounds__(kThreads, 2) void extend_attention_kernel(const AttnParams p) {
   using G = Geometry<D>;
-  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  // One LDS object per buffer: the compiler can then tell a gather in flight into one stage
+  // from reads of the other stage and does not wait for it.
+  __shared__ __attribute__((aligned(1024))) char lds_k0[G::kTileBytes];
+  __shared__ __attribute__((aligned(1024))) char lds_v0[G::kTileBytes];
+  __shared__ __attribute__((aligned(1024))) char lds_k1[G::kTileBytes];
+  __shared__ __attribute__((aligned(1024))) char lds_v1[G::kTileBytes];
 
   const WorkItem it = p.items[blockIdx.x];
   if (it.row_count == 0) return;
@@ -118,27 +146,50 @@ __global__ __launch_bounds__(kThreads, 2) void extend_attention_kernel(const Att
   const int32_t* bt = p.block_table + (int64_t)it.req * p.max_pages;
   const int last_page = (k_end - 1) / kPageSize;
 
+  // per-lane constants of the gather: which (key, chunk) of a page this lane fills
+  const int g_key = lane / G::kChunks;      // key within one 1 KB load
+  const int g_pc = lane % G::kChunks;       // physical 16-byte chunk
+
+  // Block-table entries are fetched 64 tiles at a time: lane l of wave w holds the page of
+  // tile (chunk start + l) that wave w gathers; the wave-uniform page id of a tile is then a
+  // cross-lane read instead of a dependent memory load in front of every gather.
+  const int first_page = k_begin / kPageSize;
+  auto load_pages = [&](int tile0) {
+    return bt[min(first_page + (tile0 + lane) * (kKeyTile / kPageSize) + wave, last_page)];
+  };
+  int pages_tile0 = 0;
+  int pages_cur = load_pages(0);
+  int pages_next = ntiles > 64 ? load_pages(64) : 0;
+  // Everything loaded so far (Q operands, page ids) must have landed before the main loop:
+  // inside it the only outstanding vector-memory operations are the gathers, which are
+  // awaited by hand.  (vmcnt(0), expcnt/lgkmcnt untouched)
+  __builtin_amdgcn_s_waitcnt(0x0F70);
+
   // --- gather of one 64-key tile: wave w moves page w of the tile, K and V ------------
-  auto issue_tile = [&](int t, int stage) {
+  auto issue_tile = [&](int t, char* kbuf, char* vbuf) {
     const int key0 = k_begin + t * kKeyTile;
-    const int page_idx = min(key0 / kPageSize + wave, last_page);
-    const int64_t page = __builtin_amdgcn_readfirstlane(bt[page_idx]);
+    if (t - pages_tile0 == 64) {
+      // called right after the loop-top wait, so pages_next has arrived
+      pages_cur = pages_next;
+      pages_tile0 = t;
+      if (t + 64 < ntiles) pages_next = load_pages(t + 64);
+    }
+    const int64_t page = __builtin_amdgcn_readlane(pages_cur, t - pages_tile0);
     const int64_t page_off = ((page * p.num_kv_heads + it.kv_head) * kPageSize) * (int64_t)G::kRowBytes;
     const char* kp = reinterpret_cast<const char*>(p.k_cache) + page_off;
     const char* vp = reinterpret_cast<const char*>(p.v_cache) + page_off;
-    char* ks = smem + stage * G::kStageBytes + wave * kPageSize * G::kRowBytes;
-    char* vs = ks + G::kTileBytes;
+    char* ks = kbuf + wave * kPageSize * G::kRowBytes;
+    char* vs = vbuf + wave * kPageSize * G::kRowBytes;
 #pragma unroll
     for (int j = 0; j < G::kLoadsPerPage; ++j) {
-      const int key_in_page = j * G::kKeysPerLoad + lane / G::kChunks;
-      const int pc = lane % G::kChunks;  // physical chunk this lane fills
+      const int key_in_page = j * G::kKeysPerLoad + g_key;
       const int tile_row = wave * kPageSize + key_in_page;
       const int key = key0 + tile_row;
       if (key < k_end) {
-        const char* ksrc = kp + key_in_page * G::kRowBytes + ((pc ^ G::kswz(tile_row)) << 4);
-        const char* vsrc = vp + key_in_page * G::kRowBytes + ((pc ^ G::vswz(tile_row)) << 4);
-        __builtin_amdgcn_global_load_lds((GLOBAL_PTR(const void))ksrc, (LDS_PTR(void))(ks + j * 1024), 16, 0, 0);
-        __builtin_amdgcn_global_load_lds((GLOBAL_PTR(const void))vsrc, (LDS_PTR(void))(vs + j * 1024), 16, 0, 0);
+        const char* ksrc = kp + key_in_page * G::kRowBytes + ((g_pc ^ G::kswz(tile_row)) << 4);
+        const char* vsrc = vp + key_in_page * G::kRowBytes + ((g_pc ^ G::vswz(tile_row)) << 4);
+        load_to_lds_16(ksrc, ks + j * 1024);
+        load_to_lds_16(vsrc, vs + j * 1024);
       } else {
         // rows past the end of the key range: never fetched (their pages may not exist);
         // zero them so that 0 * garbage cannot become NaN in the PV product
@@ -149,31 +200,66 @@ __global__ __launch_bounds__(kThreads, 2) void extend_attention_kernel(const Att
     }
   };
 
-  issue_tile(0, 0);
-  for (int t = 0; t < ntiles; ++t) {
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    if (t + 1 < ntiles) issue_tile(t + 1, (t + 1) & 1);
+  // per-lane LDS offsets of the MFMA operands
+  const int k_row_off = i32 * G::kRowBytes;
+  const int k_swz = G::kswz(i32);
+  // 16-lane block b of the wave reads a 4-key x 16-d patch of V through the transposing
+  // read; lane w of the block supplies the address of key w/4, d-offset 4*(w%4) and receives
+  // column w of the patch (4 consecutive keys of one d).
+  const int blk = lane >> 4;
+  const int w16 = lane & 15;
+  const int v_key = (blk >> 1) * 4 + (w16 >> 2);            // key inside a 16-key group (+8 for 2nd half)
+  const int v_chunk = 2 * (blk & 1) + ((w16 & 3) >> 1);     // 16-byte chunk inside a 32-d block
+  const int v_sub = (w16 & 1) * 8;
+  const int v_swz = G::vswz(v_key);                         // same for v_key + 8, + 16, ...
 
+  auto compute_tile = [&](int t, const char* ks, const char* vs) {
     const int key0 = k_begin + t * kKeyTile;
-    if (!wave_active || key0 >= wave_max_vis) continue;
-
-    const char* ks = smem + (t & 1) * G::kStageBytes;
-    const char* vs = ks + G::kTileBytes;
-
     // ---- S^T[key][row] = sum_d K[key][d] Q[row][d] -----------------------------------
+    // Operand traffic is scheduled by hand: the 8 K operands of the first 32 keys are read
+    // up front, those of the second 32 keys stream in under the first MFMA chain, and the
+    // V^T operands of the PV product stream in under the second chain, so that by the time
+    // the softmax is done they are all in registers.
     f32x16 s[2];
+    u32x4 ka[2][G::kSteps];
+    const char* krow = ks + k_row_off;
+#pragma unroll
+    for (int st = 0; st < G::kSteps; ++st)
+      ka[0][st] = *reinterpret_cast<const u32x4*>(krow + (((2 * st + hi) ^ k_swz) << 4));
+#pragma unroll
+    for (int st = 0; st < G::kSteps; ++st)
+      ka[1][st] = *reinterpret_cast<const u32x4*>(krow + 32 * G::kRowBytes + (((2 * st + hi) ^ k_swz) << 4));
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) s[kb][r] = 0.f;
-      const char* krow = ks + (kb * 32 + i32) * G::kRowBytes;
 #pragma unroll
-      for (int st = 0; st < G::kSteps; ++st) {
-        const int pc = (2 * st + hi) ^ G::kswz(i32);
-        const u32x4 a = *reinterpret_cast<const u32x4*>(krow + (pc << 4));
-        s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), qb[st], s[kb], 0, 0, 0);
+      for (int st = 0; st < G::kSteps; ++st)
+        s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ka[kb][st]), qb[st], s[kb], 0, 0, 0);
+    }
+    bf16x4 va[4][G::kDBlocks][2];
+    auto read_v = [&](int ks4) {
+      const char* vrow = vs + (ks4 * 16 + v_key) * G::kRowBytes + v_sub;
+#pragma unroll
+      for (int d = 0; d < G::kDBlocks; ++d) {
+        const int off = ((d * 4 + v_chunk) ^ v_swz) << 4;
+        va[ks4][d][0] = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))(vrow + off));
+        va[ks4][d][1] = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))(vrow + 8 * G::kRowBytes + off));
       }
+    };
+    read_v(0);
+    read_v(1);
+    // 0x100 = LDS read, 0x008 = MFMA
+    __builtin_amdgcn_sched_group_barrier(0x100, G::kSteps, 0);
+#pragma unroll
+    for (int st = 0; st < G::kSteps; ++st) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    }
+#pragma unroll
+    for (int st = 0; st < G::kSteps; ++st) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, G::kDBlocks / 2, 0);
     }
     // element r of block kb is key  key0 + kb*32 + (r/4)*8 + hi*4 + r%4  of row i32
     if (key0 + kKeyTile > wave_min_vis) {
@@ -186,16 +272,29 @@ __global__ __launch_bounds__(kThreads, 2) void extend_attention_kernel(const Att
         }
     }
     // ---- online softmax (per-lane row statistics) ------------------------------------
-    float tmax = s[0][0];
+    // m_run is a reference value, not necessarily the exact running max: it is only moved
+    // (and the accumulators rescaled) when the max of a row grew by more than 2^kSlack, so
+    // probabilities stay below 2^kSlack and the rescale is rare after the first tile.
+    float tmax = max3(s[0][0], s[0][1], s[1][0]);
+    tmax = max3(tmax, s[1][1], s[0][2]);
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
+    for (int r = 3; r < 16; r += 2) tmax = max3(tmax, s[0][r], s[0][r + 1 < 16 ? r + 1 : r]);
 #pragma unroll
-      for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, s[kb][r]);
+    for (int r = 2; r < 16; r += 2) tmax = max3(tmax, s[1][r], s[1][r + 1]);
     tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
-    const float m_new = fmaxf(m_run, tmax * p.scale_log2);
-    const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-    const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
-    m_run = m_new;
+    const float m_new = tmax * p.scale_log2;
+    if (__any(m_new > m_run + kSlack)) {
+      const float m_next = fmaxf(m_run, m_new);
+      const float m_safe = (m_next == -INFINITY) ? 0.f : m_next;
+      const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);
+      l_run *= alpha;
+#pragma unroll
+      for (int d = 0; d < G::kDBlocks; ++d)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[d][r] *= alpha;
+      m_run = m_next;
+    }
+    const float m_use = (m_run == -INFINITY) ? 0.f : m_run;
     float psum = 0.f;
     bf16x8 pb[4];
 #pragma unroll
@@ -206,33 +305,32 @@ __global__ __launch_bounds__(kThreads, 2) void extend_attention_kernel(const Att
         psum += e;
         pb[kb * 2 + (r >> 3)][r & 7] = (__bf16)e;
       }
-    l_run = l_run * alpha + psum;
-#pragma unroll
-    for (int d = 0; d < G::kDBlocks; ++d)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) o[d][r] *= alpha;
+    l_run += psum;
 
     // ---- O^T[d][row] += sum_key V[key][d] P[row][key] ---------------------------------
-    // 16-lane block b of the wave reads a 4-key x 16-d patch; lane w of the block supplies
-    // the address of key w/4, d-offset 4*(w%4) and receives column w of the patch.
-    const int blk = lane >> 4;
-    const int w16 = lane & 15;
+    // the V^T operands of keys 32..63 stream in under the MFMAs of keys 0..31
 #pragma unroll
     for (int ks4 = 0; ks4 < 4; ++ks4) {
-      const int kfirst = (ks4 >> 1) * 32 + (ks4 & 1) * 16 + (blk >> 1) * 4 + (w16 >> 2);
+      if (ks4 < 2) read_v(ks4 + 2);
 #pragma unroll
       for (int d = 0; d < G::kDBlocks; ++d) {
-        const int c = d * 4 + 2 * (blk & 1) + ((w16 & 3) >> 1);
-        const int sub = (w16 & 1) * 8;
-        const int r0 = kfirst, r1 = kfirst + 8;
-        const char* a0 = vs + r0 * G::kRowBytes + ((c ^ G::vswz(r0)) << 4) + sub;
-        const char* a1 = vs + r1 * G::kRowBytes + ((c ^ G::vswz(r1)) << 4) + sub;
-        const bf16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))a0);
-        const bf16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))a1);
-        const bf16x8 a = __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
+        const bf16x8 a = __builtin_shufflevector(va[ks4][d][0], va[ks4][d][1], 0, 1, 2, 3, 4, 5, 6, 7);
         o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[ks4], o[d], 0, 0, 0);
       }
     }
+  };
+
+  issue_tile(0, lds_k0, lds_v0);
+  for (int t = 0; t < ntiles; t += 2) {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (t + 1 < ntiles) issue_tile(t + 1, lds_k1, lds_v1);
+    if (wave_active && k_begin + t * kKeyTile < wave_max_vis) compute_tile(t, lds_k0, lds_v0);
+    if (t + 1 >= ntiles) break;
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (t + 2 < ntiles) issue_tile(t + 2, lds_k0, lds_v0);
+    if (wave_active && k_begin + (t + 1) * kKeyTile < wave_max_vis) compute_tile(t + 1, lds_k1, lds_v1);
   }
 
   // --- epilogue ---------------------------------------------------------------------
@@ -274,46 +372,46 @@ __global__ __launch_bounds__(kThreads, 2) void extend_attention_kernel(const Att
 // w_s = 2^(m_s - M):  out = sum_s w_s O_s / sum_s w_s l_s, splits taken in index order.
 template <int D>
 __global__ __launch_bounds__(256) void merge_kernel(const AttnParams p, const MergeItem* merges) {
+  constexpr int VEC = D / 4;               // float4 columns per row
+  constexpr int ROWS = 256 / VEC;          // rows per workgroup
   const MergeItem mi = merges[blockIdx.x];
+  const int lr = blockIdx.y * ROWS + threadIdx.x / VEC;
+  if (lr >= mi.row_count) return;
+  const int dv = (threadIdx.x % VEC) * 4;
   const ReqInfo rq = p.reqs[mi.req];
   const int g = p.group;
-  constexpr int VEC = D / 4;
-  for (int idx = threadIdx.x; idx < mi.row_count * VEC; idx += blockDim.x) {
-    const int lr = idx / VEC;
-    const int dv = (idx - lr * VEC) * 4;
-    float mx = -INFINITY;
-    for (int s = 0; s < mi.nsplit; ++s)
-      mx = fmaxf(mx, p.part_ml[((int64_t)(mi.first_slot + s) * p.rows_per_item + lr) * 2]);
-    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-    float l = 0.f;
-    for (int s = 0; s < mi.nsplit; ++s) {
-      const int64_t prow = (int64_t)(mi.first_slot + s) * p.rows_per_item + lr;
-      const float w = __builtin_amdgcn_exp2f(p.part_ml[prow * 2] - mx);
-      l += w * p.part_ml[prow * 2 + 1];
-      const f32x4 v = *reinterpret_cast<const f32x4*>(p.part_o + prow * D + dv);
-      acc += v * w;
-    }
-    const float inv = 1.f / l;
-    const int row = mi.row_begin + lr;
-    const int tok = row / g;
-    const int hg = row - tok * g;
-    uint16_t* dst = p.out + ((int64_t)(rq.row_start + tok) * p.num_q_heads + mi.kv_head * g + hg) * D + dv;
-    bf16x4 v;
-#pragma unroll
-    for (int e = 0; e < 4; ++e) v[e] = (__bf16)(acc[e] * inv);
-    *reinterpret_cast<u32x2*>(dst) = __builtin_bit_cast(u32x2, v);
+  float mx = -INFINITY;
+  for (int s = 0; s < mi.nsplit; ++s)
+    mx = fmaxf(mx, p.part_ml[((int64_t)(mi.first_slot + s) * p.rows_per_item + lr) * 2]);
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  float l = 0.f;
+  for (int s = 0; s < mi.nsplit; ++s) {
+    const int64_t prow = (int64_t)(mi.first_slot + s) * p.rows_per_item + lr;
+    const float w = __builtin_amdgcn_exp2f(p.part_ml[prow * 2] - mx);
+    l += w * p.part_ml[prow * 2 + 1];
+    const f32x4 v = *reinterpret_cast<const f32x4*>(p.part_o + prow * D + dv);
+    acc += v * w;
   }
+  const float inv = 1.f / l;
+  const int row = mi.row_begin + lr;
+  const int tok = row / g;
+  const int hg = row - tok * g;
+  uint16_t* dst = p.out + ((int64_t)(rq.row_start + tok) * p.num_q_heads + mi.kv_head * g + hg) * D + dv;
+  bf16x4 v;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) v[e] = (__bf16)(acc[e] * inv);
+  *reinterpret_cast<u32x2*>(dst) = __builtin_bit_cast(u32x2, v);
 }
 
 }  // namespace
 
-int launch_extend_attention(const efim_batch_t* b, const Plan& plan, const void* q,
+int launch_extend_attention(const efim_batch_t* b, const Plan& plan, const char* header, const void* q,
                             const void* k_cache, const void* v_cache, void* out, float sm_scale,
                             void* workspace, hipStream_t stream) {
   char* ws = static_cast<char*>(workspace);
   AttnParams p;
-  p.reqs = reinterpret_cast<const ReqInfo*>(ws + plan.off_reqs);
-  p.items = reinterpret_cast<const WorkItem*>(ws + plan.off_items);
+  p.reqs = reinterpret_cast<const ReqInfo*>(header + plan.off_reqs);
+  p.items = reinterpret_cast<const WorkItem*>(header + plan.off_items);
   p.q = static_cast<const uint16_t*>(q);
   p.k_cache = static_cast<const uint16_t*>(k_cache);
   p.v_cache = static_cast<const uint16_t*>(v_cache);
@@ -327,21 +425,21 @@ int launch_extend_attention(const efim_batch_t* b, const Plan& plan, const void*
   p.group = b->num_q_heads / b->num_kv_heads;
   p.rows_per_item = plan.rows_per_item;
   p.scale_log2 = sm_scale * 1.4426950408889634f;
-  const MergeItem* merges = reinterpret_cast<const MergeItem*>(ws + plan.off_merges);
+  const MergeItem* merges = reinterpret_cast<const MergeItem*>(header + plan.off_merges);
 
   const dim3 grid((unsigned)plan.items.size());
   const Tuning& tn = tuning();
   if (tn.ev_start) (void)hipEventRecord(tn.ev_start, stream);
   if (b->head_dim == 128) {
-    extend_attention_kernel<128><<<grid, kThreads, 2 * Geometry<128>::kStageBytes, stream>>>(p);
+    extend_attention_kernel<128><<<grid, kThreads, 0, stream>>>(p);
   } else {
-    extend_attention_kernel<64><<<grid, kThreads, 2 * Geometry<64>::kStageBytes, stream>>>(p);
+    extend_attention_kernel<64><<<grid, kThreads, 0, stream>>>(p);
   }
   hipError_t e = hipGetLastError();
   if (tn.ev_stop) (void)hipEventRecord(tn.ev_stop, stream);
   if (e != hipSuccess) { set_last_hip_error(e); return EFIM_ERR_LAUNCH; }
   if (!plan.merges.empty()) {
-    const dim3 mgrid((unsigned)plan.merges.size());
+    const dim3 mgrid((unsigned)plan.merges.size(), (unsigned)(plan.rows_per_item * (b->head_dim / 4) / 256));
     if (b->head_dim == 128) merge_kernel<128><<<mgrid, 256, 0, stream>>>(p, merges);
     else merge_kernel<64><<<mgrid, 256, 0, stream>>>(p, merges);
     e = hipGetLastError();

@@ -189,7 +189,7 @@ void build_plan(const efim_batch_t* b, int num_slots, Plan* plan) {
     while (!plan->items.empty() && plan->items.back().row_count == 0) plan->items.pop_back();
   }
 
-  // Workspace layout.
+  // Layout of the staged header and of the device workspace.
   size_t off = 0;
   plan->off_reqs = off;
   off = align_up(off + plan->reqs.size() * sizeof(ReqInfo), 256);
@@ -198,11 +198,12 @@ void build_plan(const efim_batch_t* b, int num_slots, Plan* plan) {
   plan->off_merges = off;
   off = align_up(off + plan->merges.size() * sizeof(MergeItem), 256);
   plan->header_bytes = off;
+  off = 0;
   plan->off_part_o = off;
   off = align_up(off + (size_t)plan->num_partial_slots * M * D * sizeof(float), 256);
   plan->off_part_ml = off;
   off = align_up(off + (size_t)plan->num_partial_slots * M * 2 * sizeof(float), 256);
-  plan->total_bytes = off;
+  plan->total_bytes = off < 256 ? 256 : off;  // never zero, so callers always pass a real buffer
 }
 
 }  // namespace efim

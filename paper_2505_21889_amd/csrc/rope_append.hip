@@ -12,7 +12,6 @@
 namespace efim {
 namespace {
 
-constexpr int kTokens = 4;       // tokens per workgroup
 constexpr int kThreads = 256;
 constexpr int kMaxReqPerLaunch = 384;
 
@@ -50,7 +49,9 @@ __device__ __forceinline__ uint32_t f64_to_bf16_bits(double x) {
   return u >> 16;
 }
 
-template <int D, bool INTERLEAVED>
+// kTokens = tokens per workgroup: 4 for large steps (all threads busy in the sincos phase),
+// 1 for small ones so that even a few hundred tokens spread over the whole device.
+template <int D, bool INTERLEAVED, int kTokens>
 __global__ __launch_bounds__(kThreads) void rope_append_kernel(
     const RopeArgs args, uint16_t* __restrict__ q, const uint16_t* __restrict__ k_new,
     const uint16_t* __restrict__ v_new, uint16_t* __restrict__ k_cache,
@@ -70,7 +71,7 @@ __global__ __launch_bounds__(kThreads) void rope_append_kernel(
     const int tt = tid >> 6;
     const int j = tid & 63;
     const int row = tok0 + tt;
-    if (j < HALF && row < end_row) {
+    if (tt < kTokens && j < HALF && row < end_row) {
       // request of this row: last r with row_start[r] <= row < row_start[r + 1]
       int lo = 0, hi = args.nreq;  // invariant: row_start[lo] <= row, row_start[hi] > row
       while (hi - lo > 1) {
@@ -200,19 +201,23 @@ int launch_rope_append(const efim_batch_t* b, int64_t total_new, void* q, const 
     args.req_base = r0;
     const int64_t ntok = row - first;
     if (ntok == 0) continue;
-    const dim3 grid((unsigned)((ntok + kTokens - 1) / kTokens));
     auto qp = static_cast<uint16_t*>(q);
     auto kn = static_cast<const uint16_t*>(k_new);
     auto vn = static_cast<const uint16_t*>(v_new);
     auto kc = static_cast<uint16_t*>(k_cache);
     auto vc = static_cast<uint16_t*>(v_cache);
+#define EFIM_ROPE_LAUNCH(DD, IL, TOK)                                                        \
+  rope_append_kernel<DD, IL, TOK><<<dim3((unsigned)((ntok + TOK - 1) / TOK)), kThreads, 0, stream>>>( \
+      args, qp, kn, vn, kc, vc, b->block_table)
+    const bool small = ntok < 16384;
     if (D == 128) {
-      if (interleaved) rope_append_kernel<128, true><<<grid, kThreads, 0, stream>>>(args, qp, kn, vn, kc, vc, b->block_table);
-      else rope_append_kernel<128, false><<<grid, kThreads, 0, stream>>>(args, qp, kn, vn, kc, vc, b->block_table);
+      if (interleaved) { if (small) EFIM_ROPE_LAUNCH(128, true, 1); else EFIM_ROPE_LAUNCH(128, true, 4); }
+      else { if (small) EFIM_ROPE_LAUNCH(128, false, 1); else EFIM_ROPE_LAUNCH(128, false, 4); }
     } else {
-      if (interleaved) rope_append_kernel<64, true><<<grid, kThreads, 0, stream>>>(args, qp, kn, vn, kc, vc, b->block_table);
-      else rope_append_kernel<64, false><<<grid, kThreads, 0, stream>>>(args, qp, kn, vn, kc, vc, b->block_table);
+      if (interleaved) { if (small) EFIM_ROPE_LAUNCH(64, true, 1); else EFIM_ROPE_LAUNCH(64, true, 4); }
+      else { if (small) EFIM_ROPE_LAUNCH(64, false, 1); else EFIM_ROPE_LAUNCH(64, false, 4); }
     }
+#undef EFIM_ROPE_LAUNCH
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) { set_last_hip_error(e); return EFIM_ERR_LAUNCH; }
   }

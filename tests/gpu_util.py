@@ -70,8 +70,13 @@ def errors(got_bits, ref):
     return max_abs, rel_l2
 
 
-def assert_close(got_bits, ref, what=""):
+def assert_close(got_bits, ref, what="", scale_abs_with_output=False):
+    """max abs <= 1e-2 and relative L2 <= 5e-3.  The absolute bound is stated for outputs of
+    order one (N(0,1) values averaged by a softmax at the default scale).  A test that sharpens
+    the softmax on purpose gets outputs of magnitude up to ~4, whose bf16 rounding alone is up
+    to 2^-7 = 7.8e-3; such a test sets scale_abs_with_output and the bound scales with max|ref|."""
     assert np.all(np.isfinite(O.bf16_to_f64(got_bits))), what + ": non-finite output"
     max_abs, rel_l2 = errors(got_bits, ref)
-    assert max_abs <= MAX_ABS_TOL and rel_l2 <= REL_L2_TOL, "%s: max_abs %.3e rel_l2 %.3e" % (what, max_abs, rel_l2)
+    abs_tol = MAX_ABS_TOL * (max(1.0, float(np.abs(ref).max())) if scale_abs_with_output else 1.0)
+    assert max_abs <= abs_tol and rel_l2 <= REL_L2_TOL, "%s: max_abs %.3e rel_l2 %.3e" % (what, max_abs, rel_l2)
     return max_abs, rel_l2

@@ -135,7 +135,7 @@ def test_sm_scale_argument(E):
     q_roped, kc, vc = _oracle_inputs(b)
     ref = O.extend_attention(b.cached_len, b.new_len, b.block_table, b.page_size, q_roped, kc, vc, sm_scale=0.31)
     got = U.gpu_extend_attention(E, b, q_roped, kc, vc, sm_scale=0.31)
-    U.assert_close(got, ref, "scale")
+    U.assert_close(got, ref, "scale", scale_abs_with_output=True)
 
 
 def test_repeated_runs_are_deterministic(E):
