@@ -153,7 +153,8 @@ int64_t efim_extend_plan_items(const efim_batch_t* batch, efim_work_item_t* item
 typedef enum efim_tuning_key {
   EFIM_TUNE_SPLIT_KV = 0,   /* -1 automatic (default), 0 never split, n > 0 split into chunks of n keys (multiple of 64) */
   EFIM_TUNE_XCD_GROUPING = 1, /* 1 (default): items sharing K/V are placed on one XCD; 0: plain cost order */
-  EFIM_TUNE_NUM_SLOTS = 2   /* concurrent workgroup slots assumed by the planner; 0 = query the device */
+  EFIM_TUNE_NUM_SLOTS = 2,  /* concurrent workgroup slots assumed by the planner; 0 = query the device */
+  EFIM_TUNE_ROW_TILE = 3    /* query rows per workgroup: 0 automatic (default), 128 or 256 */
 } efim_tuning_key_t;
 
 int efim_set_tuning(int key, int value);

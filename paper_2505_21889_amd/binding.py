@@ -23,6 +23,7 @@ EFIM_ERR_LAUNCH = -4
 EFIM_TUNE_SPLIT_KV = 0
 EFIM_TUNE_XCD_GROUPING = 1
 EFIM_TUNE_NUM_SLOTS = 2
+EFIM_TUNE_ROW_TILE = 3
 
 
 class EfimBatch(ctypes.Structure):
@@ -58,9 +59,11 @@ class EfimError(RuntimeError):
 
 
 def _load():
-    path = _build.LIB_PATH
-    if not os.path.exists(path):
-        _build.build_library()
+    path = os.environ.get("EFIM_LIBRARY")  # explicit path to an already built libefim.so
+    if not path:
+        path = _build.LIB_PATH
+        if not os.path.exists(path):
+            _build.build_library()
     lib = ctypes.CDLL(path)
     vp, i32, i64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64
     bp = ctypes.POINTER(EfimBatch)
@@ -86,7 +89,7 @@ def _load():
 
 
 _lib = _load()
-LIBRARY_PATH = _build.LIB_PATH
+LIBRARY_PATH = os.environ.get("EFIM_LIBRARY") or _build.LIB_PATH
 EXPORTED_SYMBOLS = (
     "efim_rope_append", "efim_extend_workspace_bytes", "efim_extend_attention",
     "efim_extend_plan_items", "efim_set_tuning", "efim_set_kernel_events", "efim_status_string",

@@ -105,6 +105,7 @@ void plan_key(const efim_batch_t* b, int slots, std::vector<int32_t>* key) {
   key->push_back(slots);
   key->push_back(t.split_kv);
   key->push_back(t.xcd_grouping);
+  key->push_back(t.row_tile);
   key->insert(key->end(), b->cached_len, b->cached_len + b->batch);
   key->insert(key->end(), b->new_len, b->new_len + b->batch);
 }
@@ -212,6 +213,10 @@ int efim_set_tuning(int key, int value) {
     case EFIM_TUNE_NUM_SLOTS:
       if (value < 0) return EFIM_ERR_INVALID_ARG;
       tuning().num_slots = value;
+      return EFIM_OK;
+    case EFIM_TUNE_ROW_TILE:
+      if (value != 0 && value != 128 && value != 256) return EFIM_ERR_INVALID_ARG;
+      tuning().row_tile = value;
       return EFIM_OK;
     default:
       return EFIM_ERR_INVALID_ARG;

@@ -43,6 +43,7 @@ struct Tuning {
   int split_kv = -1;
   int xcd_grouping = 1;
   int num_slots = 0;
+  int row_tile = 0;  // 0 automatic, 128 or 256 forced
 };
 Tuning& tuning();
 

@@ -46,7 +46,6 @@ struct AttnParams {
   float scale_log2;       // sm_scale * log2(e)
 };
 
-constexpr int kThreads = 64 * kWavesPerGroup;
 
 constexpr float kSlack = 8.f;  // log2 units by which a row max may outgrow its reference
 
@@ -78,24 +77,33 @@ struct Geometry {
   static constexpr int kSteps = D / 16;              // MFMA k-steps over the head dimension
   static constexpr int kDBlocks = D / 32;            // 32-wide blocks of the head dimension
   static constexpr int kTileBytes = kKeyTile * kRowBytes;
-  static constexpr int kStageBytes = 2 * kTileBytes; // K tile then V tile
-  static constexpr int kLoadsPerPage = kPageSize * kRowBytes / 1024;
-  static constexpr int kKeysPerLoad = 1024 / kRowBytes;
+  static constexpr int kKeysPerLoad = 1024 / kRowBytes;      // keys moved by one 1 KB wave load
+  static constexpr int kLoadsPerMatrix = kTileBytes / 1024;  // wave loads per K (or V) tile
   // chunk swizzles (XOR masks) that spread the K rows read by ds_read_b128 and the V rows
   // read by the transposing read over the LDS banks
   __device__ static int kswz(int row) { return row & (kChunks - 1); }
   __device__ static int vswz(int row) { return (row & (kChunks / 4 - 1)) << 2; }
 };
 
-template <int D>
-__global__ __launch_bounds__(kThreads, 2) void extend_attention_kernel(const AttnParams p) {
+// WAVES wavefronts per workgroup, 32 query rows each; STAGES LDS buffers of one 64-key K/V
+// tile each.  Two configurations are launched:
+//   <4 waves, 2 stages>  128 rows, 64 KB LDS, two workgroups per compute unit -- steps bound
+//                        by HBM, where many small independent gathers in flight matter;
+//   <8 waves, 3 stages>  256 rows, 96 KB LDS, one workgroup per compute unit -- compute-heavy
+//                        steps, where each gathered K/V byte is used by twice as many rows and
+//                        the gather runs two tiles ahead.
+template <int D, int WAVES, int STAGES>
+__global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const AttnParams p) {
   using G = Geometry<D>;
-  // One LDS object per buffer: the compiler can then tell a gather in flight into one stage
-  // from reads of the other stage and does not wait for it.
+  static_assert(STAGES == 2 || STAGES == 3, "two or three LDS stages");
+  // One LDS object per buffer: the compiler can then tell reads of one stage from anything
+  // else and does not serialise them.
   __shared__ __attribute__((aligned(1024))) char lds_k0[G::kTileBytes];
   __shared__ __attribute__((aligned(1024))) char lds_v0[G::kTileBytes];
   __shared__ __attribute__((aligned(1024))) char lds_k1[G::kTileBytes];
   __shared__ __attribute__((aligned(1024))) char lds_v1[G::kTileBytes];
+  __shared__ __attribute__((aligned(1024))) char lds_k2[STAGES == 3 ? G::kTileBytes : 16];
+  __shared__ __attribute__((aligned(1024))) char lds_v2[STAGES == 3 ? G::kTileBytes : 16];
 
   const WorkItem it = p.items[blockIdx.x];
   if (it.row_count == 0) return;
@@ -137,7 +145,7 @@ __global__ __launch_bounds__(kThreads, 2) void extend_attention_kernel(const Att
   for (int d = 0; d < G::kDBlocks; ++d)
 #pragma unroll
     for (int r = 0; r < 16; ++r) o[d][r] = 0.f;
-  float m_run = -INFINITY;  // running max of scaled scores (log2 units)
+  float m_run = -INFINITY;  // reference max of the scaled scores (log2 units)
   float l_run = 0.f;        // this lane's share of the running sum
 
   const int k_begin = it.key_begin;
@@ -146,57 +154,57 @@ __global__ __launch_bounds__(kThreads, 2) void extend_attention_kernel(const Att
   const int32_t* bt = p.block_table + (int64_t)it.req * p.max_pages;
   const int last_page = (k_end - 1) / kPageSize;
 
-  // per-lane constants of the gather: which (key, chunk) of a page this lane fills
-  const int g_key = lane / G::kChunks;      // key within one 1 KB load
-  const int g_pc = lane % G::kChunks;       // physical 16-byte chunk
-
-  // Block-table entries are fetched 64 tiles at a time: lane l of wave w holds the page of
-  // tile (chunk start + l) that wave w gathers; the wave-uniform page id of a tile is then a
-  // cross-lane read instead of a dependent memory load in front of every gather.
+  // Block-table entries are fetched 64 pages (16 tiles) at a time: lane l holds the page id
+  // of page (chunk start + l); the wave-uniform page id of a load is then a cross-lane read
+  // instead of a dependent memory load in front of every gather.
+  constexpr int kPagesPerTile = kKeyTile / kPageSize;
+  constexpr int kTilesPerChunk = 64 / kPagesPerTile;
   const int first_page = k_begin / kPageSize;
-  auto load_pages = [&](int tile0) {
-    return bt[min(first_page + (tile0 + lane) * (kKeyTile / kPageSize) + wave, last_page)];
-  };
+  auto load_pages = [&](int tile0) { return bt[min(first_page + tile0 * kPagesPerTile + lane, last_page)]; };
   int pages_tile0 = 0;
   int pages_cur = load_pages(0);
-  int pages_next = ntiles > 64 ? load_pages(64) : 0;
+  int pages_next = ntiles > kTilesPerChunk ? load_pages(kTilesPerChunk) : 0;
+  const int64_t page_bytes = (int64_t)p.num_kv_heads * kPageSize * G::kRowBytes;
+  const int64_t head_bytes = (int64_t)it.kv_head * kPageSize * G::kRowBytes;
+  // Rows of a tile past the end of the key range are fetched from the last key of the range
+  // instead: every tile then issues the same number of loads, pages that may not exist are
+  // never touched, and LDS only ever holds finite data (the scores of those rows are masked).
+  const int64_t last_off =
+      (int64_t)bt[last_page] * page_bytes + head_bytes + ((k_end - 1) % kPageSize) * G::kRowBytes;
   // Everything loaded so far (Q operands, page ids) must have landed before the main loop:
   // inside it the only outstanding vector-memory operations are the gathers, which are
   // awaited by hand.  (vmcnt(0), expcnt/lgkmcnt untouched)
   __builtin_amdgcn_s_waitcnt(0x0F70);
 
-  // --- gather of one 64-key tile: wave w moves page w of the tile, K and V ------------
+  // --- gather of one 64-key tile: the 2 * kLoadsPerMatrix 1 KB loads are dealt to the waves
+  constexpr int kLoadsPerWave = 2 * G::kLoadsPerMatrix / WAVES;
+  static_assert(kLoadsPerWave * WAVES == 2 * G::kLoadsPerMatrix, "loads must divide evenly");
+  const int g_key = lane / G::kChunks;  // key within one 1 KB load
+  const int g_pc = lane % G::kChunks;   // physical 16-byte chunk this lane fills
   auto issue_tile = [&](int t, char* kbuf, char* vbuf) {
     const int key0 = k_begin + t * kKeyTile;
-    if (t - pages_tile0 == 64) {
+    if (t - pages_tile0 == kTilesPerChunk) {
       // called right after the loop-top wait, so pages_next has arrived
       pages_cur = pages_next;
       pages_tile0 = t;
-      if (t + 64 < ntiles) pages_next = load_pages(t + 64);
+      if (t + kTilesPerChunk < ntiles) pages_next = load_pages(t + kTilesPerChunk);
     }
-    const int64_t page = __builtin_amdgcn_readlane(pages_cur, t - pages_tile0);
-    const int64_t page_off = ((page * p.num_kv_heads + it.kv_head) * kPageSize) * (int64_t)G::kRowBytes;
-    const char* kp = reinterpret_cast<const char*>(p.k_cache) + page_off;
-    const char* vp = reinterpret_cast<const char*>(p.v_cache) + page_off;
-    char* ks = kbuf + wave * kPageSize * G::kRowBytes;
-    char* vs = vbuf + wave * kPageSize * G::kRowBytes;
+    const char* kc = reinterpret_cast<const char*>(p.k_cache);
+    const char* vc = reinterpret_cast<const char*>(p.v_cache);
 #pragma unroll
-    for (int j = 0; j < G::kLoadsPerPage; ++j) {
-      const int key_in_page = j * G::kKeysPerLoad + g_key;
-      const int tile_row = wave * kPageSize + key_in_page;
-      const int key = key0 + tile_row;
-      if (key < k_end) {
-        const char* ksrc = kp + key_in_page * G::kRowBytes + ((g_pc ^ G::kswz(tile_row)) << 4);
-        const char* vsrc = vp + key_in_page * G::kRowBytes + ((g_pc ^ G::vswz(tile_row)) << 4);
-        load_to_lds_16(ksrc, ks + j * 1024);
-        load_to_lds_16(vsrc, vs + j * 1024);
-      } else {
-        // rows past the end of the key range: never fetched (their pages may not exist);
-        // zero them so that 0 * garbage cannot become NaN in the PV product
-        const u32x4 z = {0u, 0u, 0u, 0u};
-        *reinterpret_cast<u32x4*>(ks + j * 1024 + lane * 16) = z;
-        *reinterpret_cast<u32x4*>(vs + j * 1024 + lane * 16) = z;
-      }
+    for (int j = 0; j < kLoadsPerWave; ++j) {
+      const int load = wave * kLoadsPerWave + j;              // 0 .. 2*kLoadsPerMatrix-1
+      const bool is_v = load >= G::kLoadsPerMatrix;           // wave-uniform
+      const int idx = is_v ? load - G::kLoadsPerMatrix : load;
+      const int row0 = idx * G::kKeysPerLoad;                  // first tile row of this load
+      const int tile_row = row0 + g_key;
+      const int64_t page =
+          __builtin_amdgcn_readlane(pages_cur, (t - pages_tile0) * kPagesPerTile + row0 / kPageSize);
+      const int64_t in_off = page * page_bytes + head_bytes + (tile_row % kPageSize) * G::kRowBytes;
+      const int64_t row_off = (key0 + tile_row < k_end) ? in_off : last_off;
+      const int swz = is_v ? G::vswz(tile_row) : G::kswz(tile_row);
+      const char* src = (is_v ? vc : kc) + row_off + ((g_pc ^ swz) << 4);
+      load_to_lds_16(src, (is_v ? vbuf : kbuf) + idx * 1024);
     }
   };
 
@@ -320,17 +328,45 @@ __global__ __launch_bounds__(kThreads, 2) void extend_attention_kernel(const Att
     }
   };
 
-  issue_tile(0, lds_k0, lds_v0);
-  for (int t = 0; t < ntiles; t += 2) {
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  auto step = [&](int t, const char* ks, const char* vs) {
+    if (wave_active && k_begin + t * kKeyTile < wave_max_vis) compute_tile(t, ks, vs);
+  };
+  // Loop top for tile t.  With three stages the gather of tile t + 1 (this wave's newest
+  // kLoadsPerWave loads) may stay in flight; everything older must have landed.  The barrier
+  // publishes tile t and tells that every wave is done with the buffer about to be refilled.
+  auto wait_tile = [&](int t) {
+    if (STAGES == 3 && t + 1 < ntiles) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kLoadsPerWave) : "memory");
+    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
-    if (t + 1 < ntiles) issue_tile(t + 1, lds_k1, lds_v1);
-    if (wave_active && k_begin + t * kKeyTile < wave_max_vis) compute_tile(t, lds_k0, lds_v0);
-    if (t + 1 >= ntiles) break;
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    if (t + 2 < ntiles) issue_tile(t + 2, lds_k0, lds_v0);
-    if (wave_active && k_begin + (t + 1) * kKeyTile < wave_max_vis) compute_tile(t + 1, lds_k1, lds_v1);
+  };
+
+  if (STAGES == 2) {
+    issue_tile(0, lds_k0, lds_v0);
+    for (int t = 0; t < ntiles; t += 2) {
+      wait_tile(t);
+      if (t + 1 < ntiles) issue_tile(t + 1, lds_k1, lds_v1);
+      step(t, lds_k0, lds_v0);
+      if (t + 1 >= ntiles) break;
+      wait_tile(t + 1);
+      if (t + 2 < ntiles) issue_tile(t + 2, lds_k0, lds_v0);
+      step(t + 1, lds_k1, lds_v1);
+    }
+  } else {
+    issue_tile(0, lds_k0, lds_v0);
+    if (ntiles > 1) issue_tile(1, lds_k1, lds_v1);
+    for (int t = 0; t < ntiles; t += 3) {
+      wait_tile(t);
+      if (t + 2 < ntiles) issue_tile(t + 2, lds_k2, lds_v2);
+      step(t, lds_k0, lds_v0);
+      if (t + 1 >= ntiles) break;
+      wait_tile(t + 1);
+      if (t + 3 < ntiles) issue_tile(t + 3, lds_k0, lds_v0);
+      step(t + 1, lds_k1, lds_v1);
+      if (t + 2 >= ntiles) break;
+      wait_tile(t + 2);
+      if (t + 4 < ntiles) issue_tile(t + 4, lds_k1, lds_v1);
+      step(t + 2, lds_k2, lds_v2);
+    }
   }
 
   // --- epilogue ---------------------------------------------------------------------
@@ -430,10 +466,14 @@ int launch_extend_attention(const efim_batch_t* b, const Plan& plan, const char*
   const dim3 grid((unsigned)plan.items.size());
   const Tuning& tn = tuning();
   if (tn.ev_start) (void)hipEventRecord(tn.ev_start, stream);
-  if (b->head_dim == 128) {
-    extend_attention_kernel<128><<<grid, kThreads, 0, stream>>>(p);
+  if (b->head_dim == 128 && plan.rows_per_item == 256) {
+    extend_attention_kernel<128, 8, 3><<<grid, 512, 0, stream>>>(p);
+  } else if (b->head_dim == 128) {
+    extend_attention_kernel<128, 4, 2><<<grid, 256, 0, stream>>>(p);
+  } else if (plan.rows_per_item == 256) {
+    extend_attention_kernel<64, 8, 3><<<grid, 512, 0, stream>>>(p);
   } else {
-    extend_attention_kernel<64><<<grid, kThreads, 0, stream>>>(p);
+    extend_attention_kernel<64, 4, 2><<<grid, 256, 0, stream>>>(p);
   }
   hipError_t e = hipGetLastError();
   if (tn.ev_stop) (void)hipEventRecord(tn.ev_stop, stream);

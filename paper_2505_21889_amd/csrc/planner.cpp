@@ -74,8 +74,12 @@ void build_plan(const efim_batch_t* b, int num_slots, Plan* plan) {
     row += b->new_len[r];
     max_rows = std::max<int64_t>(max_rows, (int64_t)g * b->new_len[r]);
   }
-  // Query-row tile of a workgroup: each of the 4 waves owns 32 rows.
-  const int M = 128;
+  // Query-row tile of a workgroup: 128 rows (each of the 4 waves owns 32; two workgroups per
+  // compute unit, suits steps bound by HBM) or, when some kv head has more rows than that and
+  // the step is therefore compute-heavy, 256 rows (8 waves of 32; one workgroup per unit).
+  const Tuning& tn0 = tuning();
+  int M = 128;
+  if (tn0.row_tile == 256 || (tn0.row_tile == 0 && max_rows > 128)) M = 256;
   plan->rows_per_item = M;
 
   std::vector<Tile> tiles;

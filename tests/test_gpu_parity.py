@@ -88,6 +88,22 @@ def test_extend_attention_ragged_small(E, heads, d):
     U.assert_close(got, ref, "ragged")
 
 
+@pytest.mark.parametrize("row_tile", [128, 256])
+@pytest.mark.parametrize("heads,d", [((4, 4), 64), ((8, 2), 128)])
+def test_extend_attention_both_row_tiles(E, row_tile, heads, d):
+    # the 128-row (4 waves, 2 LDS stages) and 256-row (8 waves, 3 stages) configurations on
+    # the same ragged batch: long enough for the 3-stage ring to wrap several times
+    b = _ragged(93 + d, [700, 0, 129, 5], [100, 333, 64, 1], heads=heads, head_dim=d)
+    q_roped, kc, vc = _oracle_inputs(b)
+    ref = O.extend_attention(b.cached_len, b.new_len, b.block_table, b.page_size, q_roped, kc, vc)
+    E.efim_set_tuning(E.EFIM_TUNE_ROW_TILE, row_tile)
+    try:
+        got = U.gpu_extend_attention(E, b, q_roped, kc, vc)
+    finally:
+        E.efim_set_tuning(E.EFIM_TUNE_ROW_TILE, 0)
+    U.assert_close(got, ref, "row tile %d" % row_tile)
+
+
 @pytest.mark.parametrize("split", [0, 64, 256])
 def test_extend_attention_split_kv_agrees(E, split):
     b = _ragged(95, [700, 0, 300], [40, 300, 2], heads=(4, 2), head_dim=128)
