@@ -82,18 +82,6 @@ __device__ __forceinline__ void load_to_lds_16(const void* gptr, const void* lds
       : "memory");
 }
 
-// Same copy with a wave-uniform 64-bit base (SGPR pair) and a 32-bit per-lane byte offset.
-__device__ __forceinline__ void load_to_lds_16(const void* uniform_base, uint32_t lane_off, const void* lds_base) {
-  const uint32_t lds_addr = (uint32_t)(uintptr_t)(LDS_PTR(const char))lds_base;
-  asm volatile(
-      "s_mov_b32 m0, %0\n\t"
-      "s_nop 0\n\t"
-      "global_load_lds_dwordx4 %1, %2"
-      :
-      : "s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(lane_off), "s"(uniform_base)
-      : "memory");
-}
-
 template <int D>
 struct Geometry {
   static constexpr int kRowBytes = D * 2;            // one key/value row
@@ -313,7 +301,7 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
     for (int r = 3; r < 16; r += 2) tmax = max3(tmax, s[0][r], s[0][r + 1 < 16 ? r + 1 : r]);
 #pragma unroll
     for (int r = 2; r < 16; r += 2) tmax = max3(tmax, s[1][r], s[1][r + 1]);
-    tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+    tmax = cross_half_max(tmax);
     const float m_new = tmax * p.scale_log2;
     if (__any(m_new > m_run + kSlack)) {
       const float m_next = fmaxf(m_run, m_new);
@@ -391,422 +379,6 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
       if (t + 4 < ntiles) issue_tile(t + 4, lds_k1, lds_v1);
       step(t + 2, lds_k2, lds_v2);
     }
-  }
-
-  // --- epilogue ---------------------------------------------------------------------
-  if (!wave_active) return;
-  const float l_tot = l_run + __shfl_xor(l_run, 32);
-  if (!row_ok) return;
-  if (it.partial_slot < 0) {
-    const float inv = 1.f / l_tot;
-    uint16_t* dst = p.out + q_off;
-#pragma unroll
-    for (int d = 0; d < G::kDBlocks; ++d)
-#pragma unroll
-      for (int rr = 0; rr < 4; ++rr) {
-        bf16x4 v;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] = (__bf16)(o[d][rr * 4 + e] * inv);
-        *reinterpret_cast<u32x2*>(dst + d * 32 + rr * 8 + hi * 4) = __builtin_bit_cast(u32x2, v);
-      }
-  } else {
-    const int64_t prow = (int64_t)it.partial_slot * p.rows_per_item + local_row;
-    float* dst = p.part_o + prow * D;
-#pragma unroll
-    for (int d = 0; d < G::kDBlocks; ++d)
-#pragma unroll
-      for (int rr = 0; rr < 4; ++rr) {
-        f32x4 v;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] = o[d][rr * 4 + e];
-        *reinterpret_cast<f32x4*>(dst + d * 32 + rr * 8 + hi * 4) = v;
-      }
-    if (hi == 0) {
-      p.part_ml[prow * 2] = m_run;
-      p.part_ml[prow * 2 + 1] = l_tot;
-    }
-  }
-}
-
-// ------------------------------------------------------------------------------------------
-// Software-pipelined variant for compute-heavy steps: 8 waves x 32 rows = 256 query rows per
-// workgroup, one workgroup per compute unit, four LDS stages.
-//
-// On this hardware a wave's MFMAs overlap with its OWN vector ALU work almost perfectly, while
-// an MFMA-heavy wave and an ALU-heavy wave sharing a SIMD slow each other down.  So the two
-// kinds of work are interleaved inside every wave, across tiles: in iteration t a wave issues
-//   QK(t+1)        16 MFMA   under   exp of the first 32 keys of tile t
-//   PV(t, 0..31)    8 MFMA   under   exp of the last 32 keys of tile t
-//   PV(t, 32..63)   8 MFMA   under   row max of tile t+1
-// S(t+1) is therefore computed one iteration before it is consumed, which needs K of tile
-// t+1 and V of tile t in LDS at the same time: four stages, the gather two tiles ahead.
-template <int D>
-__global__ __launch_bounds__(512, 2) void extend_attention_pipelined_kernel(const AttnParams p) {
-  using G = Geometry<D>;
-  constexpr int WAVES = 8;
-  // K tiles of the four stages in the lower half of the buffer, V tiles in the upper half:
-  // all K (resp. V) operand reads then share their per-lane address registers and differ only
-  // in the immediate offset.
-  constexpr int kStages = 4;
-  __shared__ __attribute__((aligned(1024))) char lds[2 * kStages * G::kTileBytes];
-  char* const lds_k0 = lds;
-  char* const lds_k1 = lds + G::kTileBytes;
-  char* const lds_k2 = lds + 2 * G::kTileBytes;
-  char* const lds_k3 = lds + 3 * G::kTileBytes;
-  char* const lds_v0 = lds + kStages * G::kTileBytes;
-  char* const lds_v1 = lds_v0 + G::kTileBytes;
-  char* const lds_v2 = lds_v0 + 2 * G::kTileBytes;
-  char* const lds_v3 = lds_v0 + 3 * G::kTileBytes;
-
-  const WorkItem it = p.items[blockIdx.x];
-  if (it.row_count == 0) return;
-  const ReqInfo rq = p.reqs[it.req];
-
-  const int tid = threadIdx.x;
-  const int lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int i32 = lane & 31;
-  const int hi = lane >> 5;
-  const int g = p.group;
-
-  const int local_row = wave * 32 + i32;
-  const bool row_ok = local_row < it.row_count;
-  const int row = it.row_begin + local_row;
-  const int tok = row / g;
-  const int head_in_group = row - tok * g;
-  const int n_vis = row_ok ? rq.cached + tok + 1 : 0;
-  const int64_t q_off =
-      ((int64_t)(rq.row_start + tok) * p.num_q_heads + it.kv_head * g + head_in_group) * D;
-
-  const bool wave_active = wave * 32 < it.row_count;
-  const int wave_first_row = it.row_begin + wave * 32;
-  const int wave_last_row = it.row_begin + min(it.row_count, wave * 32 + 32) - 1;
-  const int wave_min_vis = rq.cached + wave_first_row / g + 1;
-  const int wave_max_vis = rq.cached + wave_last_row / g + 1;
-
-  bf16x8 qb[G::kSteps];
-#pragma unroll
-  for (int s = 0; s < G::kSteps; ++s) {
-    u32x4 v = {0u, 0u, 0u, 0u};
-    if (row_ok) v = *reinterpret_cast<const u32x4*>(p.q + q_off + 16 * s + 8 * hi);
-    qb[s] = __builtin_bit_cast(bf16x8, v);
-  }
-
-  f32x16 o[G::kDBlocks];
-#pragma unroll
-  for (int d = 0; d < G::kDBlocks; ++d)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) o[d][r] = 0.f;
-  float m_run = -INFINITY;
-  float l_run = 0.f;
-
-  const int k_begin = it.key_begin;
-  const int k_end = it.key_end;
-  const int ntiles = (k_end - k_begin + kKeyTile - 1) / kKeyTile;
-  // tiles this wave computes on: those that hold a key visible to one of its rows
-  const int my_tiles = wave_active ? min(ntiles, (wave_max_vis - k_begin + kKeyTile - 1) / kKeyTile) : 0;
-  const int32_t* bt = p.block_table + (int64_t)it.req * p.max_pages;
-  const int last_page = (k_end - 1) / kPageSize;
-
-  // Block-table entries are fetched 256 pages (64 tiles) at a time into four registers: lane
-  // l of register c holds the id of page (chunk start + 64 c + l); the wave-uniform page id of
-  // a load is then a cross-lane read.  The refill is synchronous (once per 4096 keys): a load
-  // left pending across iterations would make the compiler wait for ALL vector-memory
-  // operations, the gathers in flight included, in every iteration.
-  constexpr int kPagesPerTile = kKeyTile / kPageSize;
-  constexpr int kTilesPerChunk = 256 / kPagesPerTile;
-  const int first_page = k_begin / kPageSize;
-  int pages[4];
-  int pages_tile0 = 0;
-  auto load_pages = [&](int tile0) {
-#pragma unroll
-    for (int c = 0; c < 4; ++c) pages[c] = bt[min(first_page + tile0 * kPagesPerTile + 64 * c + lane, last_page)];
-  };
-  load_pages(0);
-  auto page_of = [&](int rel_page) -> int {  // rel_page is wave-uniform, 0..255
-    const int c = rel_page >> 6;
-    const int l = rel_page & 63;
-    int r = __builtin_amdgcn_readlane(pages[0], l);
-    if (c == 1) r = __builtin_amdgcn_readlane(pages[1], l);
-    if (c == 2) r = __builtin_amdgcn_readlane(pages[2], l);
-    if (c == 3) r = __builtin_amdgcn_readlane(pages[3], l);
-    return r;
-  };
-  const int64_t page_bytes = (int64_t)p.num_kv_heads * kPageSize * G::kRowBytes;
-  const int64_t head_bytes = (int64_t)it.kv_head * kPageSize * G::kRowBytes;
-  const int64_t last_off =
-      (int64_t)bt[last_page] * page_bytes + head_bytes + ((k_end - 1) % kPageSize) * G::kRowBytes;
-  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): Q operands and page ids have landed
-
-  // Gather of one 64-key tile: the 2 * kLoadsPerMatrix 1 KB loads are dealt to the waves.
-  // A load covers kKeysPerLoad consecutive keys of one page, so its source is a wave-uniform
-  // base (page, kv head) plus a per-lane offset that does not depend on the tile.
-  constexpr int kLoadsPerWave = 2 * G::kLoadsPerMatrix / WAVES;
-  const int g_key = lane / G::kChunks;
-  const int g_pc = lane % G::kChunks;
-  uint32_t lane_off[kLoadsPerWave];
-#pragma unroll
-  for (int j = 0; j < kLoadsPerWave; ++j) {
-    const int load = wave * kLoadsPerWave + j;
-    const bool is_v = load >= G::kLoadsPerMatrix;
-    const int tile_row = (is_v ? load - G::kLoadsPerMatrix : load) * G::kKeysPerLoad + g_key;
-    const int swz = is_v ? G::vswz(tile_row) : G::kswz(tile_row);
-    lane_off[j] = (tile_row % kPageSize) * G::kRowBytes + ((g_pc ^ swz) << 4);
-  }
-  // page-id refill for the tile about to be gathered (rare, synchronous)
-  auto refill_pages = [&](int t) {
-    if (t - pages_tile0 == kTilesPerChunk) {
-      pages_tile0 = t;
-      load_pages(t);
-      __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
-    }
-  };
-  // load j (of kLoadsPerWave) of this wave's share of tile t
-  auto issue_load = [&](int t, int j, char* kbuf, char* vbuf) {
-    const int key0 = k_begin + t * kKeyTile;
-    const char* kc = reinterpret_cast<const char*>(p.k_cache);
-    const char* vc = reinterpret_cast<const char*>(p.v_cache);
-    const bool full = key0 + kKeyTile <= k_end;  // wave-uniform
-    const int load = wave * kLoadsPerWave + j;
-    const bool is_v = load >= G::kLoadsPerMatrix;
-    const int idx = is_v ? load - G::kLoadsPerMatrix : load;
-    const int row0 = idx * G::kKeysPerLoad;
-    const int64_t page = page_of((t - pages_tile0) * kPagesPerTile + row0 / kPageSize);
-    const char* base = (is_v ? vc : kc) + page * page_bytes + head_bytes;
-    char* dst = (is_v ? vbuf : kbuf) + idx * 1024;
-    if (full) {
-      load_to_lds_16(base, lane_off[j], dst);
-    } else {
-      // last tile of the range: rows past its end are fetched from the last key instead
-      const int tile_row = row0 + g_key;
-      const int swz = is_v ? G::vswz(tile_row) : G::kswz(tile_row);
-      const char* src = (key0 + tile_row < k_end)
-                            ? base + lane_off[j]
-                            : (is_v ? vc : kc) + last_off + ((g_pc ^ swz) << 4);
-      load_to_lds_16(src, dst);
-    }
-  };
-  auto issue_tile = [&](int t, char* kbuf, char* vbuf) {
-    refill_pages(t);
-#pragma unroll
-    for (int j = 0; j < kLoadsPerWave; ++j) issue_load(t, j, kbuf, vbuf);
-  };
-
-  const int k_row_off = i32 * G::kRowBytes;
-  const int k_swz = G::kswz(i32);
-  const int blk = lane >> 4;
-  const int w16 = lane & 15;
-  const int v_key = (blk >> 1) * 4 + (w16 >> 2);
-  const int v_chunk = 2 * (blk & 1) + ((w16 & 3) >> 1);
-  const int v_sub = (w16 & 1) * 8;
-  const int v_swz = G::vswz(v_key);
-
-  f32x16 s_cur[2];   // S^T of the tile whose softmax / PV run in the current iteration
-  float m_use = 0.f; // reference max used for that tile
-
-  // S^T of one tile into `s`
-  auto qk = [&](f32x16 (&s)[2], const char* ks) {
-    const char* krow = ks + k_row_off;
-    u32x4 ka[2][G::kSteps];
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int st = 0; st < G::kSteps; ++st)
-        ka[kb][st] = *reinterpret_cast<const u32x4*>(krow + kb * 32 * G::kRowBytes + (((2 * st + hi) ^ k_swz) << 4));
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
-#pragma unroll
-      for (int r = 0; r < 16; ++r) s[kb][r] = 0.f;
-#pragma unroll
-      for (int st = 0; st < G::kSteps; ++st)
-        s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ka[kb][st]), qb[st], s[kb], 0, 0, 0);
-    }
-  };
-  auto apply_mask = [&](f32x16 (&s)[2], int key0) {
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int key = key0 + kb * 32 + (r >> 2) * 8 + hi * 4 + (r & 3);
-        if (key >= n_vis) s[kb][r] = -INFINITY;
-      }
-  };
-  auto tile_max = [&](const f32x16 (&s)[2]) -> float {
-    float tmax = max3(s[0][0], s[0][1], s[1][0]);
-    tmax = max3(tmax, s[1][1], s[0][2]);
-#pragma unroll
-    for (int r = 3; r < 16; r += 2) tmax = max3(tmax, s[0][r], s[0][r + 1 < 16 ? r + 1 : r]);
-#pragma unroll
-    for (int r = 2; r < 16; r += 2) tmax = max3(tmax, s[1][r], s[1][r + 1]);
-    return cross_half_max(tmax) * p.scale_log2;
-  };
-  // moves the reference max when a row outgrew it by more than 2^kSlack (rare after tile 0)
-  auto settle_max = [&](float m_new) {
-    if (__any(m_new > m_run + kSlack)) {
-      const float m_next = fmaxf(m_run, m_new);
-      const float m_safe = (m_next == -INFINITY) ? 0.f : m_next;
-      const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);
-      l_run *= alpha;
-#pragma unroll
-      for (int d = 0; d < G::kDBlocks; ++d)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) o[d][r] *= alpha;
-      m_run = m_next;
-    }
-    m_use = (m_run == -INFINITY) ? 0.f : m_run;
-  };
-
-  // One pipelined iteration: softmax + PV of tile t (S^T already in s_cur) and QK of tile
-  // t + 1.  `vs` = V of tile t, `ks_next` = K of tile t + 1.
-  auto body = [&](int t, const char* vs, const char* ks_next, int t_load, char* kload, char* vload) {
-    // The waves of a workgroup run in lockstep between barriers; if they all issued their
-    // gathers at the same point they would queue up behind each other in the vector-memory
-    // unit.  So the two waves of SIMD pair (w & 3) issue theirs at their own point of the
-    // iteration: before phase A, or after phase A, B or C.
-    const bool do_load = t_load < ntiles;
-    const int load_slot = (wave & 3) - 1;
-    auto issue_all = [&](int tl, char* kl, char* vl) {
-#pragma unroll
-      for (int j = 0; j < kLoadsPerWave; ++j) issue_load(tl, j, kl, vl);
-    };
-    if (do_load && load_slot < 0) issue_all(t_load, kload, vload);
-    __builtin_amdgcn_sched_barrier(0);
-    f32x16 s_nxt[2];
-    bf16x8 pb[4];
-    bf16x4 va[4][G::kDBlocks][2];
-    auto read_v = [&](int ks4) {
-      const char* vrow = vs + (ks4 * 16 + v_key) * G::kRowBytes + v_sub;
-#pragma unroll
-      for (int d = 0; d < G::kDBlocks; ++d) {
-        const int off = ((d * 4 + v_chunk) ^ v_swz) << 4;
-        va[ks4][d][0] = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))(vrow + off));
-        va[ks4][d][1] = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))(vrow + 8 * G::kRowBytes + off));
-      }
-    };
-    auto exp_half = [&](int kb) {
-      float psum = 0.f;
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const float e = __builtin_amdgcn_exp2f(s_cur[kb][r] * p.scale_log2 - m_use);
-        psum += e;
-        pb[kb * 2 + (r >> 3)][r & 7] = (__bf16)e;
-      }
-      l_run += psum;
-    };
-    auto pv_half = [&](int kb) {
-#pragma unroll
-      for (int ks4 = 2 * kb; ks4 < 2 * kb + 2; ++ks4)
-#pragma unroll
-        for (int d = 0; d < G::kDBlocks; ++d) {
-          const bf16x8 a = __builtin_shufflevector(va[ks4][d][0], va[ks4][d][1], 0, 1, 2, 3, 4, 5, 6, 7);
-          o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[ks4], o[d], 0, 0, 0);
-        }
-    };
-    // --- A: QK(t+1) under exp of keys 0..31 of tile t.  K operands stream in four ahead of
-    // their MFMA; the V operands of the first 16 keys follow under the last MFMAs.  This
-    // wave's share of the gather of tile t_load is issued in four pieces between the phases so
-    // that the vector-memory queue never holds up the MFMA stream.
-    qk(s_nxt, ks_next);
-    exp_half(0);
-    read_v(0);
-    __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
-#pragma unroll
-    for (int i = 0; i < 2 * G::kSteps - 4; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                // 1 MFMA
-      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                // 1 K operand
-      __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);                // VALU
-      __builtin_amdgcn_sched_group_barrier(0x400, 1, 0);                // transcendental
-    }
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x100, 2 * G::kDBlocks / 4, 0);  // V operands, keys 0..15
-      __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);
-      __builtin_amdgcn_sched_group_barrier(0x400, 1, 0);
-    }
-    __builtin_amdgcn_sched_barrier(0);
-    if (do_load && load_slot == 0) issue_all(t_load, kload, vload);
-    __builtin_amdgcn_sched_barrier(0);
-    // --- B: PV of keys 0..31 under exp of keys 32..63
-    read_v(1);
-    pv_half(0);
-    exp_half(1);
-    read_v(2);
-#pragma unroll
-    for (int i = 0; i < 2 * G::kDBlocks; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x100, 2 * G::kDBlocks / 4, 0);
-      __builtin_amdgcn_sched_group_barrier(0x002, 6, 0);
-      __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);
-    }
-    __builtin_amdgcn_sched_barrier(0);
-    if (do_load && load_slot == 1) issue_all(t_load, kload, vload);
-    __builtin_amdgcn_sched_barrier(0);
-    // --- C: PV of keys 32..63 under the row max of tile t+1
-    read_v(3);
-    pv_half(1);
-    const int key0_next = k_begin + (t + 1) * kKeyTile;
-    if (key0_next + kKeyTile > wave_min_vis) apply_mask(s_nxt, key0_next);
-    const float m_new = tile_max(s_nxt);
-#pragma unroll
-    for (int i = 0; i < G::kDBlocks; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x100, 2 * G::kDBlocks / 4, 0);
-      __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);
-    }
-#pragma unroll
-    for (int i = 0; i < G::kDBlocks; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);
-    }
-    __builtin_amdgcn_sched_barrier(0);
-    if (do_load && load_slot == 2) issue_all(t_load, kload, vload);
-    __builtin_amdgcn_sched_barrier(0);
-    if (t + 1 < my_tiles) settle_max(m_new);
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb) s_cur[kb] = s_nxt[kb];
-  };
-
-  // Top of iteration t: tile t + 1 must have landed (its K is read now), tile t + 2 may stay
-  // in flight.  The barrier also tells that every wave is done with tile t - 1, whose buffer
-  // is refilled next.
-  auto wait_next = [&](int t) {
-    if (t + 2 < ntiles) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kLoadsPerWave) : "memory");
-    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-  };
-
-  issue_tile(0, lds_k0, lds_v0);
-  if (ntiles > 1) issue_tile(1, lds_k1, lds_v1);
-  if (ntiles > 2) issue_tile(2, lds_k2, lds_v2);
-  // prologue: S^T of tile 0
-  if (ntiles > 2) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * kLoadsPerWave) : "memory");
-  else if (ntiles > 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kLoadsPerWave) : "memory");
-  else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  __syncthreads();
-  if (my_tiles > 0) {
-    qk(s_cur, lds_k0);
-    if (k_begin + kKeyTile > wave_min_vis) apply_mask(s_cur, k_begin);
-    settle_max(tile_max(s_cur));
-  }
-  // iteration t: gather tile t + 3 into the buffer of tile t - 1, compute on tiles t, t + 1
-  auto iteration = [&](int t, const char* vs, const char* ks_next, char* kload, char* vload) {
-    wait_next(t);
-    if (t + 3 < ntiles) refill_pages(t + 3);
-    if (t < my_tiles) body(t, vs, ks_next, t + 3, kload, vload);
-    else if (t + 3 < ntiles) {
-#pragma unroll
-      for (int j = 0; j < kLoadsPerWave; ++j) issue_load(t + 3, j, kload, vload);
-    }
-  };
-  for (int t = 0; t < ntiles; t += 4) {
-    iteration(t, lds_v0, lds_k1, lds_k3, lds_v3);
-    if (t + 1 >= ntiles) break;
-    iteration(t + 1, lds_v1, lds_k2, lds_k0, lds_v0);
-    if (t + 2 >= ntiles) break;
-    iteration(t + 2, lds_v2, lds_k3, lds_k1, lds_v1);
-    if (t + 3 >= ntiles) break;
-    iteration(t + 3, lds_v3, lds_k0, lds_k2, lds_v2);
   }
 
   // --- epilogue ---------------------------------------------------------------------
@@ -907,7 +479,7 @@ int launch_extend_attention(const efim_batch_t* b, const Plan& plan, const char*
   const Tuning& tn = tuning();
   if (tn.ev_start) (void)hipEventRecord(tn.ev_start, stream);
   if (b->head_dim == 128 && plan.rows_per_item == 256) {
-    extend_attention_pipelined_kernel<128><<<grid, 512, 0, stream>>>(p);
+    extend_attention_kernel<128, 8, 3><<<grid, 512, 0, stream>>>(p);
   } else if (b->head_dim == 128) {
     extend_attention_kernel<128, 4, 2><<<grid, 256, 0, stream>>>(p);
   } else if (plan.rows_per_item == 256) {

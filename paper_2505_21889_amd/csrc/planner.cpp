@@ -81,6 +81,7 @@ void build_plan(const efim_batch_t* b, int num_slots, Plan* plan) {
   int M = 128;
   if (tn0.row_tile == 256 || (tn0.row_tile == 0 && max_rows > 128)) M = 256;
   plan->rows_per_item = M;
+  if (M == 256) num_slots = std::max(1, num_slots / 2);  // 8-wave workgroups: one per compute unit
 
   std::vector<Tile> tiles;
   int64_t total_cost = 0;
