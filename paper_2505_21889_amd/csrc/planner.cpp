@@ -77,9 +77,18 @@ void build_plan(const efim_batch_t* b, int num_slots, Plan* plan) {
   // Query-row tile of a workgroup: 128 rows (each of the 4 waves owns 32; two workgroups per
   // compute unit, suits steps bound by HBM) or, when some kv head has more rows than that and
   // the step is therefore compute-heavy, 256 rows (8 waves of 32; one workgroup per unit).
+  // "Compute-heavy" = arithmetic intensity (flop per K/V/Q/O byte) above the machine balance
+  // of about 315 flop/byte (2.5 PFLOP/s over 8 TB/s).
   const Tuning& tn0 = tuning();
+  double flops = 0.0, bytes = 0.0;
+  for (int r = 0; r < b->batch; ++r) {
+    const double n = b->new_len[r], c = b->cached_len[r];
+    if (n == 0) continue;
+    flops += 4.0 * D * b->num_q_heads * n * (c + 0.5 * (n + 1));
+    bytes += 4.0 * D * ((c + n) * b->num_kv_heads + n * b->num_q_heads);
+  }
   int M = 128;
-  if (tn0.row_tile == 256 || (tn0.row_tile == 0 && max_rows > 128)) M = 256;
+  if (tn0.row_tile == 256 || (tn0.row_tile == 0 && max_rows > 128 && flops > 315.0 * bytes)) M = 256;
   plan->rows_per_item = M;
   if (M == 256) num_slots = std::max(1, num_slots / 2);  // 8-wave workgroups: one per compute unit
 
@@ -180,11 +189,31 @@ void build_plan(const efim_batch_t* b, int num_slots, Plan* plan) {
       gx[gi] = best;
       load[best] += gcost[gi];
     }
+    // When a (request, kv head) pair has many query tiles (long new sequences), inside one XCD
+    // the items run group after group (heaviest group first, and inside a group
+    // heaviest item first): the workgroups resident at any time then read the K/V of only one
+    // or two (request, kv head) pairs, which fits the 4 MB L2, instead of a slice of all of them.
+    // With few query tiles per pair there is little to share and plain heaviest-first order
+    // balances better.
+    int64_t live_groups = 0;
+    for (int64_t gi = 0; gi < ngroups; ++gi) live_groups += gcost[gi] > 0;
+    const bool group_major = (int64_t)tiles.size() >= 4 * std::max<int64_t>(1, live_groups);
     std::vector<Pending> per[kXcds];
     for (auto& p : pend) per[gx[p.group]].push_back(p);
     size_t longest = 0;
     for (int x = 0; x < kXcds; ++x) {
-      std::stable_sort(per[x].begin(), per[x].end(), by_cost);
+      if (!group_major) {
+        std::stable_sort(per[x].begin(), per[x].end(), by_cost);
+        longest = std::max(longest, per[x].size());
+        continue;
+      }
+      std::stable_sort(per[x].begin(), per[x].end(), [&](const Pending& a, const Pending& c) {
+        if (a.group != c.group) {
+          if (gcost[a.group] != gcost[c.group]) return gcost[a.group] > gcost[c.group];
+          return a.group < c.group;
+        }
+        return a.cost > c.cost;
+      });
       longest = std::max(longest, per[x].size());
     }
     plan->items.reserve(longest * kXcds);
