@@ -48,7 +48,7 @@ struct Tuning {
 Tuning& tuning();
 
 struct Plan {
-  int rows_per_item = 128;  // query rows per workgroup tile (32 per wave and row block)
+  int rows_per_item = 128;  // query rows per workgroup tile (32 per wave)
   std::vector<ReqInfo> reqs;
   std::vector<WorkItem> items;
   std::vector<MergeItem> merges;

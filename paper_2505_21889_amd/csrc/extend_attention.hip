@@ -107,15 +107,10 @@ struct Geometry {
 template <int D, int WAVES, int STAGES>
 __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const AttnParams p) {
   using G = Geometry<D>;
-  static_assert(STAGES == 2 || STAGES == 3, "two or three LDS stages");
-  // One LDS object per buffer: the compiler can then tell reads of one stage from anything
-  // else and does not serialise them.
-  __shared__ __attribute__((aligned(1024))) char lds_k0[G::kTileBytes];
-  __shared__ __attribute__((aligned(1024))) char lds_v0[G::kTileBytes];
-  __shared__ __attribute__((aligned(1024))) char lds_k1[G::kTileBytes];
-  __shared__ __attribute__((aligned(1024))) char lds_v1[G::kTileBytes];
-  __shared__ __attribute__((aligned(1024))) char lds_k2[STAGES == 3 ? G::kTileBytes : 16];
-  __shared__ __attribute__((aligned(1024))) char lds_v2[STAGES == 3 ? G::kTileBytes : 16];
+  static_assert(STAGES >= 2 && STAGES * 2 * G::kTileBytes <= 160 * 1024, "stages must fit the 160 KB LDS");
+  // stage s: K tile at s * kStageBytes, V tile right behind it
+  constexpr int kStageBytes = 2 * G::kTileBytes;
+  __shared__ __attribute__((aligned(1024))) char lds[STAGES * kStageBytes];
 
   const WorkItem it = p.items[blockIdx.x];
   if (it.row_count == 0) return;
@@ -343,41 +338,33 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
   auto step = [&](int t, const char* ks, const char* vs) {
     if (wave_active && k_begin + t * kKeyTile < wave_max_vis) compute_tile(t, ks, vs);
   };
-  // Loop top for tile t.  With three stages the gather of tile t + 1 (this wave's newest
-  // kLoadsPerWave loads) may stay in flight; everything older must have landed.  The barrier
-  // publishes tile t and tells that every wave is done with the buffer about to be refilled.
+  // Loop top for tile t: the gathers of up to STAGES - 2 later tiles (this wave's newest
+  // loads) may stay in flight; everything older must have landed.  The barrier publishes tile
+  // t and tells that every wave is done with the buffer about to be refilled.
   auto wait_tile = [&](int t) {
-    if (STAGES == 3 && t + 1 < ntiles) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kLoadsPerWave) : "memory");
+    const int later = min(STAGES - 2, ntiles - 1 - t);  // tiles issued after t so far
+    if (STAGES >= 5 && later == 3) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(3 * kLoadsPerWave) : "memory");
+    else if (STAGES >= 4 && later == 2) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * kLoadsPerWave) : "memory");
+    else if (STAGES >= 3 && later == 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kLoadsPerWave) : "memory");
     else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
   };
+  static_assert(STAGES <= 5, "wait_tile handles up to three tiles in flight");
 
-  if (STAGES == 2) {
-    issue_tile(0, lds_k0, lds_v0);
-    for (int t = 0; t < ntiles; t += 2) {
-      wait_tile(t);
-      if (t + 1 < ntiles) issue_tile(t + 1, lds_k1, lds_v1);
-      step(t, lds_k0, lds_v0);
-      if (t + 1 >= ntiles) break;
-      wait_tile(t + 1);
-      if (t + 2 < ntiles) issue_tile(t + 2, lds_k0, lds_v0);
-      step(t + 1, lds_k1, lds_v1);
-    }
-  } else {
-    issue_tile(0, lds_k0, lds_v0);
-    if (ntiles > 1) issue_tile(1, lds_k1, lds_v1);
-    for (int t = 0; t < ntiles; t += 3) {
-      wait_tile(t);
-      if (t + 2 < ntiles) issue_tile(t + 2, lds_k2, lds_v2);
-      step(t, lds_k0, lds_v0);
-      if (t + 1 >= ntiles) break;
-      wait_tile(t + 1);
-      if (t + 3 < ntiles) issue_tile(t + 3, lds_k0, lds_v0);
-      step(t + 1, lds_k1, lds_v1);
-      if (t + 2 >= ntiles) break;
-      wait_tile(t + 2);
-      if (t + 4 < ntiles) issue_tile(t + 4, lds_k1, lds_v1);
-      step(t + 2, lds_k2, lds_v2);
+#pragma unroll
+  for (int s0 = 0; s0 < STAGES - 1; ++s0)
+    if (s0 < ntiles) issue_tile(s0, lds + s0 * kStageBytes, lds + s0 * kStageBytes + G::kTileBytes);
+  for (int t0 = 0; t0 < ntiles; t0 += STAGES) {
+#pragma unroll
+    for (int s0 = 0; s0 < STAGES; ++s0) {
+      const int t = t0 + s0;
+      if (t < ntiles) {
+        wait_tile(t);
+        constexpr int kAhead = STAGES - 1;
+        const int sl = (s0 + kAhead) % STAGES;  // static after unrolling
+        if (t + kAhead < ntiles) issue_tile(t + kAhead, lds + sl * kStageBytes, lds + sl * kStageBytes + G::kTileBytes);
+        step(t, lds + s0 * kStageBytes, lds + s0 * kStageBytes + G::kTileBytes);
+      }
     }
   }
 
@@ -478,14 +465,13 @@ int launch_extend_attention(const efim_batch_t* b, const Plan& plan, const char*
   const dim3 grid((unsigned)plan.items.size());
   const Tuning& tn = tuning();
   if (tn.ev_start) (void)hipEventRecord(tn.ev_start, stream);
-  if (b->head_dim == 128 && plan.rows_per_item == 256) {
-    extend_attention_kernel<128, 8, 3><<<grid, 512, 0, stream>>>(p);
-  } else if (b->head_dim == 128) {
-    extend_attention_kernel<128, 4, 2><<<grid, 256, 0, stream>>>(p);
-  } else if (plan.rows_per_item == 256) {
-    extend_attention_kernel<64, 8, 3><<<grid, 512, 0, stream>>>(p);
+  const bool wide = plan.rows_per_item == 256;
+  if (b->head_dim == 128) {
+    if (wide) extend_attention_kernel<128, 8, 3><<<grid, 512, 0, stream>>>(p);
+    else extend_attention_kernel<128, 4, 2><<<grid, 256, 0, stream>>>(p);
   } else {
-    extend_attention_kernel<64, 4, 2><<<grid, 256, 0, stream>>>(p);
+    if (wide) extend_attention_kernel<64, 8, 3><<<grid, 512, 0, stream>>>(p);
+    else extend_attention_kernel<64, 4, 2><<<grid, 256, 0, stream>>>(p);
   }
   hipError_t e = hipGetLastError();
   if (tn.ev_stop) (void)hipEventRecord(tn.ev_stop, stream);
