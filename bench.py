@@ -32,7 +32,7 @@ if ROOT not in sys.path:
 # on: the digest of extend_attention.hip is recorded with it and checked at run time.
 MEASURED_TRAFFIC = {
     # workload: (bytes per launch, sha256 of csrc/extend_attention.hip when measured)
-    "c5": (2558269077, "9f82a22687831524d7a5d62eb42da4cf57b9444f5823dc8d1f46cf9120c8ee2f"),
+    "c5": (2560415317, "398e7c7e05c7eb3bb5ab496662987b37cceb5bbbf84f3ffbc5b9e45b835e02ae"),
 }
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak
