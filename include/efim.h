@@ -170,6 +170,70 @@ const char* efim_status_string(int status);
 int efim_last_hip_error(void); /* hipError_t of the most recent EFIM_ERR_LAUNCH on this thread */
 int efim_version(void);        /* major * 10000 + minor * 100 + patch */
 
+/* ---------------------------------------------------------------------------------------
+ * Session pool: the FIM -> EFIM prompt rewrite in front of the engine (Sec. 3.1, steps 1-5
+ * of the prompt transformation figure).  Host code only; no device is touched.
+ *
+ * A pool maps a user id to that user's session: the prefix and suffix of the previous
+ * request as they were laid out in the prompt, and the prompt itself.  For a new request
+ * (prefix, suffix), both sequences of token ids that contain none of the three marker ids:
+ *   step 1/2  no session: PSM order  <P> prefix <S> suffix <M>; the session is created;
+ *   step 3/4  same suffix and the prefix extends the session's: EFIM order
+ *             <P> common <S> suffix <M> inc  with common = the session's prefix; the session
+ *             keeps (common, suffix), so the next EFIM prompt extends this one;
+ *   step 5    anything else (the paper names growth at the head of the suffix): PSM order with
+ *             the new prefix and suffix, which replace the session.  A request identical to
+ *             the session keeps its previous layout.
+ * What a prefix-matching paged KV cache then reuses is reported alongside: cached_len is the
+ * longest common token prefix of this prompt and the user's previous one, rounded down to
+ * reuse_granularity tokens and at most prompt_len - 1; new_len = prompt_len - cached_len.
+ * These are the C_r and N_r of efim_batch_t for this request.
+ * ------------------------------------------------------------------------------------- */
+typedef struct efim_session_pool efim_session_pool_t;
+
+enum { EFIM_ORDER_PSM = 0, EFIM_ORDER_EFIM = 1 };
+
+typedef struct {
+  int32_t order;       /* EFIM_ORDER_PSM or EFIM_ORDER_EFIM                           */
+  int32_t reserved;
+  int64_t common_len;  /* tokens between <P> and <S>                                  */
+  int64_t inc_len;     /* tokens behind <M> (0 in PSM order)                          */
+  int64_t suffix_len;
+  int64_t prompt_len;  /* common_len + suffix_len + inc_len + 3                       */
+  int64_t cached_len;  /* reusable leading tokens (see above)                         */
+  int64_t new_len;     /* prompt_len - cached_len >= 1                                */
+} efim_prompt_info_t;
+
+/* Creates an empty pool.  tok_p/tok_s/tok_m are the ids of <P>, <S>, <M> (pairwise
+ * different); reuse_granularity >= 1 (16 for a cache with 16-token pages, 1 for exact
+ * token reuse); always_psm != 0 switches steps 4 off (PSM order with cache reuse: the
+ * "FIM" scheme of Sec. 4.2).  Returns NULL on invalid arguments or allocation failure.
+ * The caller owns the pool and releases it with efim_session_pool_destroy (NULL is ok).
+ * A pool may be used from several threads; calls on one pool are serialised. */
+efim_session_pool_t* efim_session_pool_create(int32_t tok_p, int32_t tok_s, int32_t tok_m,
+                                              int32_t reuse_granularity, int32_t always_psm);
+void efim_session_pool_destroy(efim_session_pool_t* pool);
+
+/* Steps 1-5 for one request.  prefix/suffix: HOST arrays of n_prefix/n_suffix token ids
+ * (may be NULL when the length is 0), read before the call returns.  Fills *info and stores
+ * the prompt in the session.  EFIM_ERR_INVALID_ARG for NULL pool/info, negative lengths, a
+ * NULL array with a positive length, or a marker id inside prefix or suffix (the session is
+ * left untouched). */
+int efim_session_transform(efim_session_pool_t* pool, uint64_t user, const int32_t* prefix,
+                           int64_t n_prefix, const int32_t* suffix, int64_t n_suffix,
+                           efim_prompt_info_t* info);
+
+/* Copies the prompt last built for `user` into dst (HOST, capacity tokens; at most capacity
+ * are written, dst may be NULL when capacity is 0) and returns its full length, 0 if the
+ * user has no session, or EFIM_ERR_INVALID_ARG. */
+int64_t efim_session_prompt(efim_session_pool_t* pool, uint64_t user, int32_t* dst, int64_t capacity);
+
+/* Forgets one user's session (returns 1 if there was one, 0 if not) / counts the sessions.
+ * Both return EFIM_ERR_INVALID_ARG for a NULL pool. */
+int efim_session_drop(efim_session_pool_t* pool, uint64_t user);
+int64_t efim_session_count(efim_session_pool_t* pool);
+
+
 #ifdef __cplusplus
 }
 #endif

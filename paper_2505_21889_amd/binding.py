@@ -58,6 +58,13 @@ class EfimError(RuntimeError):
         super().__init__("%s: %s" % (where, msg))
 
 
+class EfimPromptInfo(ctypes.Structure):
+    """efim_prompt_info_t"""
+    _fields_ = [("order", ctypes.c_int32), ("reserved", ctypes.c_int32), ("common_len", ctypes.c_int64),
+                ("inc_len", ctypes.c_int64), ("suffix_len", ctypes.c_int64), ("prompt_len", ctypes.c_int64),
+                ("cached_len", ctypes.c_int64), ("new_len", ctypes.c_int64)]
+
+
 def _load():
     path = os.environ.get("EFIM_LIBRARY")  # explicit path to an already built libefim.so
     if not path:
@@ -85,6 +92,19 @@ def _load():
     lib.efim_last_hip_error.restype = i32
     lib.efim_version.argtypes = []
     lib.efim_version.restype = i32
+    ip = ctypes.POINTER(ctypes.c_int32)
+    lib.efim_session_pool_create.argtypes = [i32, i32, i32, i32, i32]
+    lib.efim_session_pool_create.restype = vp
+    lib.efim_session_pool_destroy.argtypes = [vp]
+    lib.efim_session_pool_destroy.restype = None
+    lib.efim_session_transform.argtypes = [vp, ctypes.c_uint64, ip, i64, ip, i64, ctypes.POINTER(EfimPromptInfo)]
+    lib.efim_session_transform.restype = i32
+    lib.efim_session_prompt.argtypes = [vp, ctypes.c_uint64, ip, i64]
+    lib.efim_session_prompt.restype = i64
+    lib.efim_session_drop.argtypes = [vp, ctypes.c_uint64]
+    lib.efim_session_drop.restype = i32
+    lib.efim_session_count.argtypes = [vp]
+    lib.efim_session_count.restype = i64
     return lib
 
 
@@ -94,6 +114,8 @@ EXPORTED_SYMBOLS = (
     "efim_rope_append", "efim_extend_workspace_bytes", "efim_extend_attention",
     "efim_extend_plan_items", "efim_set_tuning", "efim_set_kernel_events", "efim_status_string",
     "efim_last_hip_error", "efim_version",
+    "efim_session_pool_create", "efim_session_pool_destroy", "efim_session_transform", "efim_session_prompt",
+    "efim_session_drop", "efim_session_count",
 )
 
 
@@ -239,3 +261,59 @@ class HipEvent:
         if rc != 0:
             raise RuntimeError("hipEventElapsedTime failed: %d" % rc)
         return float(ms.value)
+
+
+EFIM_ORDER_PSM, EFIM_ORDER_EFIM = 0, 1
+
+
+def _tokens(seq):
+    arr = np.ascontiguousarray(np.asarray(seq, dtype=np.int32).reshape(-1))
+    return arr, arr.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)), int(arr.size)
+
+
+class SessionPool:
+    """Owner of an efim_session_pool_t; the methods are the C calls of the same names."""
+
+    def __init__(self, tok_p, tok_s, tok_m, reuse_granularity=1, always_psm=False):
+        self.handle = _lib.efim_session_pool_create(int(tok_p), int(tok_s), int(tok_m), int(reuse_granularity),
+                                                    int(bool(always_psm)))
+        if not self.handle:
+            raise EfimError(EFIM_ERR_INVALID_ARG, "efim_session_pool_create")
+
+    def close(self):
+        if self.handle:
+            _lib.efim_session_pool_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        self.close()
+
+    def efim_session_transform(self, user, prefix, suffix):
+        pre, pre_p, n_pre = _tokens(prefix)
+        suf, suf_p, n_suf = _tokens(suffix)
+        info = EfimPromptInfo()
+        _check(_lib.efim_session_transform(self.handle, int(user), pre_p, n_pre, suf_p, n_suf, ctypes.byref(info)),
+               "efim_session_transform")
+        return {name: int(getattr(info, name)) for name, _ in EfimPromptInfo._fields_ if name != "reserved"}
+
+    def efim_session_prompt(self, user):
+        n = _lib.efim_session_prompt(self.handle, int(user), None, 0)
+        if n < 0:
+            raise EfimError(int(n), "efim_session_prompt")
+        out = np.zeros(int(n), dtype=np.int32)
+        if n:
+            m = _lib.efim_session_prompt(self.handle, int(user), out.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)), int(n))
+            assert m == n
+        return out
+
+    def efim_session_drop(self, user):
+        rc = _lib.efim_session_drop(self.handle, int(user))
+        if rc < 0:
+            raise EfimError(int(rc), "efim_session_drop")
+        return bool(rc)
+
+    def efim_session_count(self):
+        n = _lib.efim_session_count(self.handle)
+        if n < 0:
+            raise EfimError(int(n), "efim_session_count")
+        return int(n)

@@ -10,7 +10,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB_DIR = os.path.join(PKG, "lib")
 LIB_PATH = os.path.join(LIB_DIR, "libefim.so")
-SOURCES = ["api.hip", "planner.cpp", "rope_append.hip", "extend_attention.hip"]
+SOURCES = ["api.hip", "planner.cpp", "session_pool.cpp", "rope_append.hip", "extend_attention.hip"]
 
 
 def hipcc_path():
