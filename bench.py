@@ -153,6 +153,58 @@ def summarize(db, parts):
     }
 
 
+def replay_lengths(E, W, scheme, docs):
+    """(cached_len, new_len) of every round of the service replay under one scheme: 'baseline'
+    recomputes every prompt, 'fim' sends PSM prompts to a prefix-matching cache with 16-token
+    pages, 'efim' puts the session pool's rewrite in front of the same cache (EFIM Sec. 4.2)."""
+    pool = None if scheme == "baseline" else E.SessionPool(*W.REPLAY_MARKERS, reuse_granularity=16,
+                                                           always_psm=(scheme == "fim"))
+    rounds = []
+    for docs_round in docs:
+        c, n = [], []
+        for user, (prefix, suffix) in enumerate(docs_round):
+            if pool is None:
+                c.append(0)
+                n.append(len(prefix) + len(suffix) + 3)
+            else:
+                info = pool.efim_session_transform(user, prefix, suffix)
+                c.append(info["cached_len"])
+                n.append(info["new_len"])
+        rounds.append((np.asarray(c, dtype=np.int32), np.asarray(n, dtype=np.int32)))
+    if pool is not None:
+        pool.close()
+    return rounds
+
+
+def replay(torch, E, W, iters):
+    """Kernel-level replay of the 16-user, 5-round service of EFIM Sec. 4.2: per head layout and
+    scheme, the device time of one attention layer's step (rope_append + extend_attention) in
+    every round, the share of prompt tokens served from the cache, and prompt tokens per
+    second of that one layer."""
+    out = {}
+    docs = W.replay_documents()
+    for spec in ("replay", "replay_mha"):
+        per_scheme = {}
+        for scheme in ("baseline", "fim", "efim"):
+            round_us, cached, total = [], 0, 0
+            for c, n in replay_lengths(E, W, scheme, docs):
+                d = DeviceBatch(torch, E, W, spec, lengths=(c, n), copies=2)
+                parts = time_parts(torch, E, d, iters=iters, warmup=10)
+                round_us.append(round(parts["rope_us"] + parts["attn_call_us"], 2))
+                cached += int(c.sum())
+                total += int(c.sum() + n.sum())
+                del d
+                torch.cuda.empty_cache()
+            per_scheme[scheme] = {"round_us": round_us, "total_us": round(sum(round_us), 2),
+                                  "reuse_rate": round(cached / total, 4),
+                                  "prompt_tokens_per_s": round(total / (sum(round_us) * 1e-6), 1)}
+        base = per_scheme["baseline"]["total_us"]
+        for scheme in per_scheme:
+            per_scheme[scheme]["time_vs_baseline"] = round(per_scheme[scheme]["total_us"] / base, 4)
+        out[spec] = per_scheme
+    return out
+
+
 def recorded_traffic(name):
     import hashlib
     rec = MEASURED_TRAFFIC.get(name)
@@ -287,6 +339,7 @@ def main():
             del d
             torch.cuda.empty_cache()
         result["workloads"] = extra
+        result["service_replay"] = replay(torch, E, W, iters=max(5, args.extra_iters // 3))
 
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(W, name)

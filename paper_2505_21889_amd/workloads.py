@@ -48,7 +48,41 @@ SPECS = {
     "c5": WorkloadSpec("c5", 64, 32, 8, 128, 16, 1.0e6, 1.0, 1004,
                        "mixed serving step: 64 requests, 32/8 heads, d128; half hits "
                        "(cached U[512,8192], inc U[1,256]), half misses (cached 0, new U[1024,4096])"),
+    # one round of the multi-user infilling service of EFIM Sec. 4.2 (lengths come from
+    # replay_documents and a session pool, never from draw_lengths); the two head layouts are
+    # those of the two models the paper serves
+    "replay": WorkloadSpec("replay", 16, 32, 8, 128, 16, 5.0e5, 1.0, 1005,
+                           "service replay, GQA 32/8, d128: 16 users x 5 rounds, prompts of ~2355 tokens"),
+    "replay_mha": WorkloadSpec("replay_mha", 16, 32, 32, 128, 16, 1.0e5, 1.0, 1006,
+                               "service replay, MHA 32/32, d128: 16 users x 5 rounds, prompts of ~2355 tokens"),
 }
+
+REPLAY_USERS = 16
+REPLAY_ROUNDS = 5
+REPLAY_VOCAB = 32000            # content token ids are drawn below this; markers sit above it
+REPLAY_MARKERS = (32001, 32002, 32003)
+
+
+def replay_documents(seed=1005, users=REPLAY_USERS, rounds=REPLAY_ROUNDS):
+    """Token sequences of the closed-loop service of EFIM Sec. 4.2: ``rounds`` lists of
+    ``users`` (prefix, suffix) pairs.  Every user starts from a document split at the
+    insertion point (prefix and suffix each U[600,1480] tokens) and in every later round has
+    typed U[16,256] more tokens at the tail of the prefix; the suffix never changes.  With the
+    three markers the prompts average 2355 tokens over the five rounds, the paper's figure."""
+    rng = np.random.default_rng(seed)
+    docs = []
+    for _ in range(users):
+        prefix = rng.integers(0, REPLAY_VOCAB, int(rng.integers(600, 1481))).astype(np.int32)
+        suffix = rng.integers(0, REPLAY_VOCAB, int(rng.integers(600, 1481))).astype(np.int32)
+        docs.append((prefix, suffix))
+    out = [list(docs)]
+    for _ in range(1, rounds):
+        nxt = []
+        for prefix, suffix in out[-1]:
+            typed = rng.integers(0, REPLAY_VOCAB, int(rng.integers(16, 257))).astype(np.int32)
+            nxt.append((np.concatenate([prefix, typed]), suffix))
+        out.append(nxt)
+    return out
 
 
 def draw_lengths(name, rng):

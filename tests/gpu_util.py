@@ -80,3 +80,44 @@ def assert_close(got_bits, ref, what="", scale_abs_with_output=False):
     abs_tol = MAX_ABS_TOL * (max(1.0, float(np.abs(ref).max())) if scale_abs_with_output else 1.0)
     assert max_abs <= abs_tol and rel_l2 <= REL_L2_TOL, "%s: max_abs %.3e rel_l2 %.3e" % (what, max_abs, rel_l2)
     return max_abs, rel_l2
+
+
+def oracle_inputs(b):
+    """Oracle-side inputs of the attention step: roped queries and the caches after the append."""
+    kc, vc = oracle_cache(b)
+    q_roped, _ = O.rope_append(b.cached_len, b.new_len, b.block_table, b.page_size, b.q_new, b.k_new,
+                               b.v_new, kc, vc, b.rope_base)
+    return q_roped, kc, vc
+
+
+def sampled_check(E, b, heads_per_req, rows_per_head, seed):
+    """Library output of the whole batch against oracle rows computed one by one: for every
+    request a sample of (kv head, query head, row) triples, first, middle and last row always."""
+    q_roped, kc, vc = oracle_inputs(b)
+    got_bits = gpu_extend_attention(E, b, q_roped, kc, vc)
+    got = O.bf16_to_f64(got_bits)
+    assert np.all(np.isfinite(got)), "a row was left unwritten or is not finite"
+    rng = np.random.default_rng(seed)
+    g = b.num_q_heads // b.num_kv_heads
+    num = den = 0.0
+    worst = 0.0
+    start = 0
+    for r in range(b.batch):
+        n = int(b.new_len[r])
+        if n == 0:
+            continue
+        kv_heads = rng.choice(b.num_kv_heads, size=min(heads_per_req, b.num_kv_heads), replace=False)
+        for h in kv_heads:
+            a = int(h) * g + int(rng.integers(0, g))
+            rows = {0, n - 1, n // 2} | set(int(x) for x in rng.integers(0, n, size=min(rows_per_head, n)))
+            rows = sorted(rows)
+            ref = O.extend_attention_rows(r, a, b.cached_len, b.new_len, b.block_table, b.page_size,
+                                          q_roped, kc, vc, rows=rows)
+            d = got[start + np.array(rows), a, :] - ref
+            worst = max(worst, float(np.abs(d).max()))
+            num += float((d * d).sum())
+            den += float((ref * ref).sum())
+        start += n
+    rel = (num / den) ** 0.5
+    assert worst <= MAX_ABS_TOL and rel <= REL_L2_TOL, "max_abs %.3e rel_l2 %.3e" % (worst, rel)
+    return worst, rel

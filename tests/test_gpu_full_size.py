@@ -22,63 +22,25 @@ def E():
     return binding
 
 
-def _inputs(b):
-    kc, vc = U.oracle_cache(b)
-    q_roped, _ = O.rope_append(b.cached_len, b.new_len, b.block_table, b.page_size, b.q_new, b.k_new,
-                               b.v_new, kc, vc, b.rope_base)
-    return q_roped, kc, vc
-
-
 @pytest.mark.parametrize("name", ["c2", "c3"])
 def test_full_output_matches_oracle(E, name):
     b = W.make_batch(name)
-    q_roped, kc, vc = _inputs(b)
+    q_roped, kc, vc = U.oracle_inputs(b)
     got = U.gpu_extend_attention(E, b, q_roped, kc, vc)
     ref = O.extend_attention(b.cached_len, b.new_len, b.block_table, b.page_size, q_roped, kc, vc)
     max_abs, rel = U.assert_close(got, ref, name)
     print("%s: max_abs %.3e rel_l2 %.3e" % (name, max_abs, rel))
 
 
-def _sampled_check(E, b, heads_per_req, rows_per_head, seed):
-    q_roped, kc, vc = _inputs(b)
-    got_bits = U.gpu_extend_attention(E, b, q_roped, kc, vc)
-    got = O.bf16_to_f64(got_bits)
-    assert np.all(np.isfinite(got)), "a row was left unwritten or is not finite"
-    rng = np.random.default_rng(seed)
-    g = b.num_q_heads // b.num_kv_heads
-    num = den = 0.0
-    worst = 0.0
-    start = 0
-    for r in range(b.batch):
-        n = int(b.new_len[r])
-        if n == 0:
-            continue
-        kv_heads = rng.choice(b.num_kv_heads, size=min(heads_per_req, b.num_kv_heads), replace=False)
-        for h in kv_heads:
-            a = int(h) * g + int(rng.integers(0, g))
-            rows = {0, n - 1, n // 2} | set(int(x) for x in rng.integers(0, n, size=min(rows_per_head, n)))
-            rows = sorted(rows)
-            ref = O.extend_attention_rows(r, a, b.cached_len, b.new_len, b.block_table, b.page_size,
-                                          q_roped, kc, vc, rows=rows)
-            d = got[start + np.array(rows), a, :] - ref
-            worst = max(worst, float(np.abs(d).max()))
-            num += float((d * d).sum())
-            den += float((ref * ref).sum())
-        start += n
-    rel = (num / den) ** 0.5
-    assert worst <= U.MAX_ABS_TOL and rel <= U.REL_L2_TOL, "max_abs %.3e rel_l2 %.3e" % (worst, rel)
-    return worst, rel
-
-
 def test_c4_sampled_outputs_match_oracle(E):
     b = W.make_batch("c4")
-    worst, rel = _sampled_check(E, b, heads_per_req=4, rows_per_head=40, seed=7)
+    worst, rel = U.sampled_check(E, b, heads_per_req=4, rows_per_head=40, seed=7)
     print("c4 sampled: max_abs %.3e rel_l2 %.3e" % (worst, rel))
 
 
 def test_c5_sampled_outputs_match_oracle(E):
     b = W.make_batch("c5")
-    worst, rel = _sampled_check(E, b, heads_per_req=2, rows_per_head=24, seed=8)
+    worst, rel = U.sampled_check(E, b, heads_per_req=2, rows_per_head=24, seed=8)
     print("c5 sampled: max_abs %.3e rel_l2 %.3e" % (worst, rel))
 
 

@@ -102,3 +102,34 @@ def test_large_user_ids_and_long_documents():
         r = ref.transform(user, pre, suf)
         assert {k: r[k] for k in KEYS} == got.efim_session_transform(user, pre, suf)
     got.close()
+
+
+def test_replay_lengths_follow_the_three_reuse_levels():
+    """The benchmark's service replay: the library pool gives the oracle pool's lengths, and in
+    rounds >= 1 they are the closed forms of the three reuse levels of EFIM Sec. 4.2 (none /
+    prefix / prefix + suffix), with 16-token pages."""
+    import bench as B
+    from paper_2505_21889_amd import workloads as W
+    docs = W.replay_documents()
+    assert len(docs) == W.REPLAY_ROUNDS and all(len(r) == W.REPLAY_USERS for r in docs)
+    mean_len = np.mean([[len(p) + len(s) + 3 for p, s in r] for r in docs])
+    assert abs(mean_len - 2355) < 40          # the paper's average input length
+    got = {sch: B.replay_lengths(E, W, sch, docs) for sch in ("baseline", "fim", "efim")}
+    for sch, psm in (("fim", True), ("efim", False)):
+        ref = SO.SessionPool(*W.REPLAY_MARKERS, granularity=16, always_psm=psm)
+        for k, round_docs in enumerate(docs):
+            for u, (p, s) in enumerate(round_docs):
+                r = ref.transform(u, p.tolist(), s.tolist())
+                assert (got[sch][k][0][u], got[sch][k][1][u]) == (r["cached_len"], r["new_len"])
+    for k, round_docs in enumerate(docs):
+        for u, (p, s) in enumerate(round_docs):
+            total = len(p) + len(s) + 3
+            assert (got["baseline"][k][0][u], got["baseline"][k][1][u]) == (0, total)
+            if k == 0:
+                assert got["fim"][k][0][u] == got["efim"][k][0][u] == 0
+                continue
+            old_p = len(docs[k - 1][u][0])
+            assert got["fim"][k][0][u] == (1 + old_p) // 16 * 16                      # <P> + old prefix
+            assert got["efim"][k][0][u] == (old_p + len(s) + 3) // 16 * 16            # everything before the new inc
+            assert got["fim"][k][0][u] + got["fim"][k][1][u] == total
+            assert got["efim"][k][0][u] + got["efim"][k][1][u] == total
