@@ -171,6 +171,31 @@ int efim_last_hip_error(void); /* hipError_t of the most recent EFIM_ERR_LAUNCH 
 int efim_version(void);        /* major * 10000 + minor * 100 + patch */
 
 /* ---------------------------------------------------------------------------------------
+ * Decode step in one launch.  After the prompt, the engine generates the answer one token per
+ * request and step (Sec. 2.2, the prefill / decode breakdown; Sec. 4.2: 128 output tokens per
+ * request).  For such a batch -- new_len[r] == 1 for every r, num_q_heads / num_kv_heads <= 32 --
+ * efim_decode_step computes what
+ *     efim_rope_append(batch, q, k_new, v_new, k_cache, v_cache, rope_base, rope_interleaved)
+ *     efim_extend_attention(batch, q, k_cache, v_cache, out, sm_scale, ...)
+ * compute, with one kernel: same cache contents bit for bit, same `out`.  The one difference:
+ * q is read only -- it is rotated on the fly and NOT rewritten in place.
+ *
+ * workspace: DEVICE, 256-byte aligned, at least efim_decode_workspace_bytes(batch) bytes.  Its
+ * first 64 KiB hold arrival counters of split key ranges: they must be zero when a workspace
+ * is used for the first time (zero-fill it once after allocating), and every call that returns
+ * EFIM_OK leaves them zero again once its kernel has run.  Calls sharing a workspace must be
+ * ordered on one stream.
+ * Errors: as efim_extend_attention / efim_rope_append; EFIM_ERR_UNSUPPORTED if some
+ * new_len[r] != 1, if there are more than 32 query heads per kv head, or if the planner was
+ * forced to 256-row tiles (EFIM_TUNE_ROW_TILE).
+ * efim_decode_workspace_bytes returns 0 for a batch efim_decode_step would reject.
+ * ------------------------------------------------------------------------------------- */
+size_t efim_decode_workspace_bytes(const efim_batch_t* batch);
+int efim_decode_step(const efim_batch_t* batch, const void* q, const void* k_new, const void* v_new,
+                     void* k_cache, void* v_cache, void* out, double rope_base, int rope_interleaved,
+                     float sm_scale, void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------
  * Session pool: the FIM -> EFIM prompt rewrite in front of the engine (Sec. 3.1, steps 1-5
  * of the prompt transformation figure).  Host code only; no device is touched.
  *

@@ -188,6 +188,64 @@ int efim_extend_attention(const efim_batch_t* batch, const void* q, const void* 
   return rc;
 }
 
+namespace {
+
+// The fused decode step takes batches in which every request has exactly one new token and
+// whose query heads per kv head fit one wavefront's rows.
+int validate_decode_batch(const efim_batch_t* batch, int64_t* total) {
+  int rc = validate_batch(batch, total);
+  if (rc != EFIM_OK) return rc;
+  for (int r = 0; r < batch->batch; ++r)
+    if (batch->new_len[r] != 1) return EFIM_ERR_UNSUPPORTED;
+  if (batch->num_q_heads / batch->num_kv_heads > kDecodeMaxGroup) return EFIM_ERR_UNSUPPORTED;
+  return EFIM_OK;
+}
+
+}  // namespace
+
+size_t efim_decode_workspace_bytes(const efim_batch_t* batch) {
+  int64_t total = 0;
+  if (validate_decode_batch(batch, &total) != EFIM_OK) return 0;
+  std::lock_guard<std::mutex> lock(g_plan_mutex);
+  const Plan& plan = cached_plan(batch);
+  return kDecodeTicketBytes + (plan.total_bytes < 256 ? 256 : plan.total_bytes);
+}
+
+int efim_decode_step(const efim_batch_t* batch, const void* q, const void* k_new, const void* v_new,
+                     void* k_cache, void* v_cache, void* out, double rope_base, int rope_interleaved,
+                     float sm_scale, void* workspace, size_t workspace_bytes, void* stream) {
+  int64_t total = 0;
+  int rc = validate_decode_batch(batch, &total);
+  if (rc != EFIM_OK) return rc;
+  if (!(sm_scale >= 0.f) || !(rope_base > 0.0) || (rope_interleaved != 0 && rope_interleaved != 1))
+    return EFIM_ERR_INVALID_ARG;
+  if (total == 0) return EFIM_OK;
+  if (!q || !k_new || !v_new || !k_cache || !v_cache || !out || q == out || out == k_cache || out == v_cache)
+    return EFIM_ERR_INVALID_ARG;
+  if (!aligned16(q) || !aligned16(k_new) || !aligned16(v_new) || !aligned16(k_cache) ||
+      !aligned16(v_cache) || !aligned16(out) || (reinterpret_cast<uintptr_t>(batch->block_table) & 3u))
+    return EFIM_ERR_INVALID_ARG;
+  std::lock_guard<std::mutex> lock(g_plan_mutex);
+  const Plan& plan = cached_plan(batch);
+  if (plan.rows_per_item != 128 || plan.merges.size() * sizeof(int32_t) > kDecodeTicketBytes)
+    return EFIM_ERR_UNSUPPORTED;
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) ||
+      workspace_bytes < kDecodeTicketBytes + plan.total_bytes)
+    return EFIM_ERR_WORKSPACE;
+  if (sm_scale == 0.f) sm_scale = 1.0f / sqrtf((float)batch->head_dim);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  std::lock_guard<std::mutex> stage_lock(g_stage_mutex);
+  StageSlot* slot = nullptr;
+  const char* header = nullptr;
+  rc = stage_plan(plan, &slot, &header);
+  if (rc != EFIM_OK) return rc;
+  rc = launch_decode_step(batch, plan, header, q, k_new, v_new, k_cache, v_cache, out, rope_base,
+                          rope_interleaved, sm_scale, workspace, s);
+  if (hipEventRecord(slot->done, s) == hipSuccess) slot->in_flight = true;
+  else (void)hipStreamSynchronize(s);
+  return rc;
+}
+
 int64_t efim_extend_plan_items(const efim_batch_t* batch, efim_work_item_t* items, int64_t capacity) {
   int64_t total = 0;
   int rc = validate_batch(batch, &total);

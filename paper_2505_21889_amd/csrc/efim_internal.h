@@ -75,6 +75,17 @@ int launch_extend_attention(const efim_batch_t* b, const Plan& plan, const char*
                             const void* k_cache, const void* v_cache, void* out, float sm_scale,
                             void* workspace, hipStream_t stream);
 
+// Fused decode step (every request has exactly one new token): one launch does the rotary
+// embedding, the cache append, the attention and the merge of split key ranges.  The first
+// kDecodeTicketBytes of `workspace` are arrival counters (zero between launches), the partial
+// results follow.
+constexpr size_t kDecodeTicketBytes = 64 * 1024;
+constexpr int kDecodeMaxGroup = 32;  // query heads per kv head the fused kernel handles
+int launch_decode_step(const efim_batch_t* b, const Plan& plan, const char* header, const void* q,
+                       const void* k_new, const void* v_new, void* k_cache, void* v_cache, void* out,
+                       double rope_base, int interleaved, float sm_scale, void* workspace,
+                       hipStream_t stream);
+
 void set_last_hip_error(hipError_t e);
 
 }  // namespace efim

@@ -14,6 +14,7 @@
 //     V^T operands come from the row-major V tile through the transposing LDS read.
 // Accumulation is fp32; partial results of split key ranges are merged by a second kernel.
 #include "efim_internal.h"
+#include "rope_math.h"
 
 namespace efim {
 namespace {
@@ -44,6 +45,15 @@ struct AttnParams {
   int32_t group;          // Hq / Hkv
   int32_t rows_per_item;
   float scale_log2;       // sm_scale * log2(e)
+  // --- fused decode step only (one new token per request) ---
+  const uint16_t* k_new;  // [B, Hkv, D] raw keys of the new tokens
+  const uint16_t* v_new;  // [B, Hkv, D]
+  uint16_t* k_cache_w;    // the caches again, writable: the new token's K/V are appended
+  uint16_t* v_cache_w;
+  int32_t* tickets;       // one arrival counter per split query tile, zero between launches
+  const MergeItem* merges;
+  int32_t interleaved;    // rotary pairing
+  double inv_freq[64];    // base^(-2j/D)
 };
 
 
@@ -97,6 +107,42 @@ struct Geometry {
   __device__ static int vswz(int row) { return (row & (kChunks / 4 - 1)) << 2; }
 };
 
+// Combines the partial results of a split key range: with M = max_s m_s and
+// w_s = 2^(m_s - M):  out = sum_s w_s O_s / sum_s w_s l_s, splits taken in index order.
+// nthreads threads (thread index t) share rows [row_lo, row_hi) of the tile, D/4 threads per row.
+template <int D>
+__device__ __forceinline__ void merge_rows(const AttnParams& p, const MergeItem& mi, int t, int nthreads,
+                                           int row_lo = 0, int row_hi = 1 << 30) {
+  constexpr int VEC = D / 4;  // float4 columns per row
+  const int dv = (t % VEC) * 4;
+  const ReqInfo rq = p.reqs[mi.req];
+  const int g = p.group;
+  row_hi = min(row_hi, mi.row_count);
+  for (int lr = row_lo + t / VEC; lr < row_hi; lr += nthreads / VEC) {
+    float mx = -INFINITY;
+    for (int s = 0; s < mi.nsplit; ++s)
+      mx = fmaxf(mx, p.part_ml[((int64_t)(mi.first_slot + s) * p.rows_per_item + lr) * 2]);
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    float l = 0.f;
+    for (int s = 0; s < mi.nsplit; ++s) {
+      const int64_t prow = (int64_t)(mi.first_slot + s) * p.rows_per_item + lr;
+      const float w = __builtin_amdgcn_exp2f(p.part_ml[prow * 2] - mx);
+      l += w * p.part_ml[prow * 2 + 1];
+      const f32x4 v = *reinterpret_cast<const f32x4*>(p.part_o + prow * D + dv);
+      acc += v * w;
+    }
+    const float inv = 1.f / l;
+    const int row = mi.row_begin + lr;
+    const int tok = row / g;
+    const int hg = row - tok * g;
+    uint16_t* dst = p.out + ((int64_t)(rq.row_start + tok) * p.num_q_heads + mi.kv_head * g + hg) * D + dv;
+    bf16x4 v;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) v[e] = (__bf16)(acc[e] * inv);
+    *reinterpret_cast<u32x2*>(dst) = __builtin_bit_cast(u32x2, v);
+  }
+}
+
 // WAVES wavefronts per workgroup, 32 query rows each; STAGES LDS buffers of one 64-key K/V
 // tile each.  Two configurations are launched:
 //   <4 waves, 2 stages>  128 rows, 64 KB LDS, two workgroups per compute unit -- steps bound
@@ -104,13 +150,26 @@ struct Geometry {
 //   <8 waves, 3 stages>  256 rows, 96 KB LDS, one workgroup per compute unit -- compute-heavy
 //                        steps, where each gathered K/V byte is used by twice as many rows and
 //                        the gather runs two tiles ahead.
-template <int D, int WAVES, int STAGES>
+//
+// FUSED (decode step, one new token per request, at most 32 query heads per kv head): the
+// kernel also does what efim_rope_append does for that token -- q is rotated on the way in
+// (global q stays raw), the workgroup whose key range ends with the new token rotates its key,
+// stores key and value into the paged cache and patches them into its LDS tile -- and the
+// workgroup that finishes a split query tile last combines the partial results itself.
+template <int D, int WAVES, int STAGES, bool FUSED>
 __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const AttnParams p) {
   using G = Geometry<D>;
   static_assert(STAGES >= 2 && STAGES * 2 * G::kTileBytes <= 160 * 1024, "stages must fit the 160 KB LDS");
   // stage s: K tile at s * kStageBytes, V tile right behind it
   constexpr int kStageBytes = 2 * G::kTileBytes;
   __shared__ __attribute__((aligned(1024))) char lds[STAGES * kStageBytes];
+  // fused decode step: the rotated query rows of the tile, the new token's rotated key and its
+  // value, cos/sin of the token's position, and the "this workgroup merges" flag
+  constexpr int kFusedRows = 32;
+  __shared__ __attribute__((aligned(16))) uint16_t s_q[FUSED ? kFusedRows * D : 8];
+  __shared__ __attribute__((aligned(16))) uint16_t s_kv[FUSED ? 2 * D : 8];
+  __shared__ double s_cs[FUSED ? 128 : 1];
+  __shared__ int s_last;
 
   const WorkItem it = p.items[blockIdx.x];
   if (it.row_count == 0) return;
@@ -139,11 +198,48 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
   const int wave_min_vis = rq.cached + wave_first_row / g + 1;
   const int wave_max_vis = rq.cached + wave_last_row / g + 1;
 
+  if constexpr (FUSED) {
+    // rotary embedding of the tile's query rows and of the new token's key at position C_r
+    // (the request's only new token is packed row rq.row_start), same arithmetic as the
+    // stand-alone append kernel
+    const int pos = rq.cached;
+    if (tid < D / 2) {
+      double sn, cs;
+      sincos((double)pos * p.inv_freq[tid], &sn, &cs);
+      s_cs[tid] = cs;
+      s_cs[64 + tid] = sn;
+    }
+    __syncthreads();
+    const int64_t kv_row = ((int64_t)rq.row_start * p.num_kv_heads + it.kv_head) * D;
+    for (int idx = tid; idx < (it.row_count + 1) * (D / 2); idx += 64 * WAVES) {
+      const int r = idx / (D / 2), j = idx - r * (D / 2);
+      const int e1 = p.interleaved ? 2 * j : j;
+      const int e2 = p.interleaved ? 2 * j + 1 : j + D / 2;
+      const uint16_t* src = p.k_new + kv_row;
+      uint16_t* dst = s_kv;
+      if (r < it.row_count) {
+        const int rr = it.row_begin + r;
+        const int t_ = rr / g;
+        src = p.q + ((int64_t)(rq.row_start + t_) * p.num_q_heads + it.kv_head * g + (rr - t_ * g)) * D;
+        dst = s_q + r * D;
+      }
+      uint32_t y1, y2;
+      rotate_pair_bf16(src[e1], src[e2], s_cs[j], s_cs[64 + j], &y1, &y2);
+      dst[e1] = (uint16_t)y1;
+      dst[e2] = (uint16_t)y2;
+    }
+    for (int e = tid; e < D; e += 64 * WAVES) s_kv[D + e] = p.v_new[kv_row + e];
+    __syncthreads();
+  }
   bf16x8 qb[G::kSteps];
 #pragma unroll
   for (int s = 0; s < G::kSteps; ++s) {
     u32x4 v = {0u, 0u, 0u, 0u};
-    if (row_ok) v = *reinterpret_cast<const u32x4*>(p.q + q_off + 16 * s + 8 * hi);
+    if constexpr (FUSED) {
+      if (row_ok) v = *reinterpret_cast<const u32x4*>(s_q + local_row * D + 16 * s + 8 * hi);
+    } else {
+      if (row_ok) v = *reinterpret_cast<const u32x4*>(p.q + q_off + 16 * s + 8 * hi);
+    }
     qb[s] = __builtin_bit_cast(bf16x8, v);
   }
 
@@ -363,79 +459,131 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
         constexpr int kAhead = STAGES - 1;
         const int sl = (s0 + kAhead) % STAGES;  // static after unrolling
         if (t + kAhead < ntiles) issue_tile(t + kAhead, lds + sl * kStageBytes, lds + sl * kStageBytes + G::kTileBytes);
+        if constexpr (FUSED) {
+          // The key range that ends with the new token: the cache slot of that token has not
+          // been written yet, so its row of the landed tile and the rows behind it (which the
+          // gather fetched from that same slot) are replaced by the rotated key / the value;
+          // the token is also appended to the paged cache.
+          if (k_end == rq.cached + 1 && t == ntiles - 1) {
+            const int pos = rq.cached;
+            const int prow = pos - (k_begin + t * kKeyTile);
+            constexpr int kPerRow = 2 * G::kChunks;  // 16-byte chunks of a key row and a value row
+            for (int u = tid; u < (kKeyTile - prow) * kPerRow; u += 64 * WAVES) {
+              const int row = prow + u / kPerRow;
+              const int w = u % kPerRow;
+              const bool is_v = w >= G::kChunks;
+              const int c = is_v ? w - G::kChunks : w;
+              const u32x4 val = *reinterpret_cast<const u32x4*>(s_kv + (is_v ? D : 0) + c * 8);
+              const int swz = is_v ? G::vswz(row) : G::kswz(row);
+              char* tile = lds + s0 * kStageBytes + (is_v ? G::kTileBytes : 0);
+              *reinterpret_cast<u32x4*>(tile + row * G::kRowBytes + ((c ^ swz) << 4)) = val;
+              if (row == prow) {
+                const int64_t page = bt[pos / kPageSize];
+                uint16_t* cache = is_v ? p.v_cache_w : p.k_cache_w;
+                *reinterpret_cast<u32x4*>(cache + ((page * p.num_kv_heads + it.kv_head) * kPageSize + pos % kPageSize) * D + c * 8) = val;
+              }
+            }
+            __syncthreads();
+          }
+        }
         step(t, lds + s0 * kStageBytes, lds + s0 * kStageBytes + G::kTileBytes);
       }
     }
   }
 
   // --- epilogue ---------------------------------------------------------------------
-  if (!wave_active) return;
-  const float l_tot = cross_half_sum(l_run);
-  if (!row_ok) return;
-  if (it.partial_slot < 0) {
-    const float inv = 1.f / l_tot;
-    uint16_t* dst = p.out + q_off;
+  if (wave_active) {
+    const float l_tot = cross_half_sum(l_run);
+    if (row_ok) {
+      if (it.partial_slot < 0) {
+        const float inv = 1.f / l_tot;
+        uint16_t* dst = p.out + q_off;
 #pragma unroll
-    for (int d = 0; d < G::kDBlocks; ++d)
+        for (int d = 0; d < G::kDBlocks; ++d)
 #pragma unroll
-      for (int rr = 0; rr < 4; ++rr) {
-        bf16x4 v;
+          for (int rr = 0; rr < 4; ++rr) {
+            bf16x4 v;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] = (__bf16)(o[d][rr * 4 + e] * inv);
-        *reinterpret_cast<u32x2*>(dst + d * 32 + rr * 8 + hi * 4) = __builtin_bit_cast(u32x2, v);
+            for (int e = 0; e < 4; ++e) v[e] = (__bf16)(o[d][rr * 4 + e] * inv);
+            *reinterpret_cast<u32x2*>(dst + d * 32 + rr * 8 + hi * 4) = __builtin_bit_cast(u32x2, v);
+          }
+      } else {
+        const int64_t prow = (int64_t)it.partial_slot * p.rows_per_item + local_row;
+        float* dst = p.part_o + prow * D;
+#pragma unroll
+        for (int d = 0; d < G::kDBlocks; ++d)
+#pragma unroll
+          for (int rr = 0; rr < 4; ++rr) {
+            f32x4 v;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] = o[d][rr * 4 + e];
+            *reinterpret_cast<f32x4*>(dst + d * 32 + rr * 8 + hi * 4) = v;
+          }
+        if (hi == 0) {
+          p.part_ml[prow * 2] = m_run;
+          p.part_ml[prow * 2 + 1] = l_tot;
+        }
       }
-  } else {
-    const int64_t prow = (int64_t)it.partial_slot * p.rows_per_item + local_row;
-    float* dst = p.part_o + prow * D;
-#pragma unroll
-    for (int d = 0; d < G::kDBlocks; ++d)
-#pragma unroll
-      for (int rr = 0; rr < 4; ++rr) {
-        f32x4 v;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] = o[d][rr * 4 + e];
-        *reinterpret_cast<f32x4*>(dst + d * 32 + rr * 8 + hi * 4) = v;
+    }
+  }
+  if constexpr (FUSED) {
+    // Split query tile: every workgroup publishes its partial result and takes a ticket; the
+    // one that draws the last ticket finds all partial results visible, combines them and
+    // puts the counter back to zero for the next launch.
+    if (it.partial_slot >= 0) {
+      const MergeItem mi = p.merges[it.merge_id];
+      __threadfence();
+      __syncthreads();
+      if (tid == 0) s_last = atomicAdd(p.tickets + it.merge_id, 1) == mi.nsplit - 1;
+      __syncthreads();
+      if (s_last) {
+        __threadfence();
+        merge_rows<D>(p, mi, tid, 64 * WAVES);
+        if (tid == 0) p.tickets[it.merge_id] = 0;
       }
-    if (hi == 0) {
-      p.part_ml[prow * 2] = m_run;
-      p.part_ml[prow * 2 + 1] = l_tot;
     }
   }
 }
 
-// Combines the partial results of a split key range: with M = max_s m_s and
-// w_s = 2^(m_s - M):  out = sum_s w_s O_s / sum_s w_s l_s, splits taken in index order.
 template <int D>
 __global__ __launch_bounds__(256) void merge_kernel(const AttnParams p, const MergeItem* merges) {
-  constexpr int VEC = D / 4;               // float4 columns per row
-  constexpr int ROWS = 256 / VEC;          // rows per workgroup
-  const MergeItem mi = merges[blockIdx.x];
-  const int lr = blockIdx.y * ROWS + threadIdx.x / VEC;
-  if (lr >= mi.row_count) return;
-  const int dv = (threadIdx.x % VEC) * 4;
-  const ReqInfo rq = p.reqs[mi.req];
-  const int g = p.group;
-  float mx = -INFINITY;
-  for (int s = 0; s < mi.nsplit; ++s)
-    mx = fmaxf(mx, p.part_ml[((int64_t)(mi.first_slot + s) * p.rows_per_item + lr) * 2]);
-  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-  float l = 0.f;
-  for (int s = 0; s < mi.nsplit; ++s) {
-    const int64_t prow = (int64_t)(mi.first_slot + s) * p.rows_per_item + lr;
-    const float w = __builtin_amdgcn_exp2f(p.part_ml[prow * 2] - mx);
-    l += w * p.part_ml[prow * 2 + 1];
-    const f32x4 v = *reinterpret_cast<const f32x4*>(p.part_o + prow * D + dv);
-    acc += v * w;
-  }
-  const float inv = 1.f / l;
-  const int row = mi.row_begin + lr;
-  const int tok = row / g;
-  const int hg = row - tok * g;
-  uint16_t* dst = p.out + ((int64_t)(rq.row_start + tok) * p.num_q_heads + mi.kv_head * g + hg) * D + dv;
-  bf16x4 v;
-#pragma unroll
-  for (int e = 0; e < 4; ++e) v[e] = (__bf16)(acc[e] * inv);
-  *reinterpret_cast<u32x2*>(dst) = __builtin_bit_cast(u32x2, v);
+  constexpr int ROWS = 256 / (D / 4);  // rows per workgroup
+  MergeItem mi = merges[blockIdx.x];
+  // this workgroup's slice of the rows
+  const int first = blockIdx.y * ROWS;
+  if (first >= mi.row_count) return;
+  merge_rows<D>(p, mi, threadIdx.x, 256, first, min(mi.row_count, first + ROWS));
+}
+
+}  // namespace
+
+namespace {
+
+void fill_params(AttnParams* p, const efim_batch_t* b, const Plan& plan, const char* header, const void* q,
+                 const void* k_cache, const void* v_cache, void* out, float sm_scale, char* partials) {
+  p->reqs = reinterpret_cast<const ReqInfo*>(header + plan.off_reqs);
+  p->items = reinterpret_cast<const WorkItem*>(header + plan.off_items);
+  p->q = static_cast<const uint16_t*>(q);
+  p->k_cache = static_cast<const uint16_t*>(k_cache);
+  p->v_cache = static_cast<const uint16_t*>(v_cache);
+  p->out = static_cast<uint16_t*>(out);
+  p->part_o = reinterpret_cast<float*>(partials + plan.off_part_o);
+  p->part_ml = reinterpret_cast<float*>(partials + plan.off_part_ml);
+  p->block_table = b->block_table;
+  p->max_pages = b->max_pages_per_req;
+  p->num_q_heads = b->num_q_heads;
+  p->num_kv_heads = b->num_kv_heads;
+  p->group = b->num_q_heads / b->num_kv_heads;
+  p->rows_per_item = plan.rows_per_item;
+  p->scale_log2 = sm_scale * 1.4426950408889634f;
+  p->k_new = nullptr;
+  p->v_new = nullptr;
+  p->k_cache_w = nullptr;
+  p->v_cache_w = nullptr;
+  p->tickets = nullptr;
+  p->merges = reinterpret_cast<const MergeItem*>(header + plan.off_merges);
+  p->interleaved = 0;
+  for (double& f : p->inv_freq) f = 0.0;
 }
 
 }  // namespace
@@ -443,35 +591,20 @@ __global__ __launch_bounds__(256) void merge_kernel(const AttnParams p, const Me
 int launch_extend_attention(const efim_batch_t* b, const Plan& plan, const char* header, const void* q,
                             const void* k_cache, const void* v_cache, void* out, float sm_scale,
                             void* workspace, hipStream_t stream) {
-  char* ws = static_cast<char*>(workspace);
   AttnParams p;
-  p.reqs = reinterpret_cast<const ReqInfo*>(header + plan.off_reqs);
-  p.items = reinterpret_cast<const WorkItem*>(header + plan.off_items);
-  p.q = static_cast<const uint16_t*>(q);
-  p.k_cache = static_cast<const uint16_t*>(k_cache);
-  p.v_cache = static_cast<const uint16_t*>(v_cache);
-  p.out = static_cast<uint16_t*>(out);
-  p.part_o = reinterpret_cast<float*>(ws + plan.off_part_o);
-  p.part_ml = reinterpret_cast<float*>(ws + plan.off_part_ml);
-  p.block_table = b->block_table;
-  p.max_pages = b->max_pages_per_req;
-  p.num_q_heads = b->num_q_heads;
-  p.num_kv_heads = b->num_kv_heads;
-  p.group = b->num_q_heads / b->num_kv_heads;
-  p.rows_per_item = plan.rows_per_item;
-  p.scale_log2 = sm_scale * 1.4426950408889634f;
-  const MergeItem* merges = reinterpret_cast<const MergeItem*>(header + plan.off_merges);
+  fill_params(&p, b, plan, header, q, k_cache, v_cache, out, sm_scale, static_cast<char*>(workspace));
+  const MergeItem* merges = p.merges;
 
   const dim3 grid((unsigned)plan.items.size());
   const Tuning& tn = tuning();
   if (tn.ev_start) (void)hipEventRecord(tn.ev_start, stream);
   const bool wide = plan.rows_per_item == 256;
   if (b->head_dim == 128) {
-    if (wide) extend_attention_kernel<128, 8, 3><<<grid, 512, 0, stream>>>(p);
-    else extend_attention_kernel<128, 4, 2><<<grid, 256, 0, stream>>>(p);
+    if (wide) extend_attention_kernel<128, 8, 3, false><<<grid, 512, 0, stream>>>(p);
+    else extend_attention_kernel<128, 4, 2, false><<<grid, 256, 0, stream>>>(p);
   } else {
-    if (wide) extend_attention_kernel<64, 8, 3><<<grid, 512, 0, stream>>>(p);
-    else extend_attention_kernel<64, 4, 2><<<grid, 256, 0, stream>>>(p);
+    if (wide) extend_attention_kernel<64, 8, 3, false><<<grid, 512, 0, stream>>>(p);
+    else extend_attention_kernel<64, 4, 2, false><<<grid, 256, 0, stream>>>(p);
   }
   hipError_t e = hipGetLastError();
   if (tn.ev_stop) (void)hipEventRecord(tn.ev_stop, stream);
@@ -483,6 +616,34 @@ int launch_extend_attention(const efim_batch_t* b, const Plan& plan, const char*
     e = hipGetLastError();
     if (e != hipSuccess) { set_last_hip_error(e); return EFIM_ERR_LAUNCH; }
   }
+  return EFIM_OK;
+}
+
+int launch_decode_step(const efim_batch_t* b, const Plan& plan, const char* header, const void* q,
+                       const void* k_new, const void* v_new, void* k_cache, void* v_cache, void* out,
+                       double rope_base, int interleaved, float sm_scale, void* workspace,
+                       hipStream_t stream) {
+  // workspace: the ticket counters first (kDecodeTicketBytes), the partial results behind them
+  AttnParams p;
+  fill_params(&p, b, plan, header, q, k_cache, v_cache, out, sm_scale,
+              static_cast<char*>(workspace) + kDecodeTicketBytes);
+  p.k_new = static_cast<const uint16_t*>(k_new);
+  p.v_new = static_cast<const uint16_t*>(v_new);
+  p.k_cache_w = static_cast<uint16_t*>(k_cache);
+  p.v_cache_w = static_cast<uint16_t*>(v_cache);
+  p.tickets = static_cast<int32_t*>(workspace);
+  p.interleaved = interleaved;
+  const int D = b->head_dim;
+  for (int j = 0; j < D / 2; ++j) p.inv_freq[j] = pow(rope_base, -2.0 * j / D);
+
+  const dim3 grid((unsigned)plan.items.size());
+  const Tuning& tn = tuning();
+  if (tn.ev_start) (void)hipEventRecord(tn.ev_start, stream);
+  if (D == 128) extend_attention_kernel<128, 4, 2, true><<<grid, 256, 0, stream>>>(p);
+  else extend_attention_kernel<64, 4, 2, true><<<grid, 256, 0, stream>>>(p);
+  hipError_t e = hipGetLastError();
+  if (tn.ev_stop) (void)hipEventRecord(tn.ev_stop, stream);
+  if (e != hipSuccess) { set_last_hip_error(e); return EFIM_ERR_LAUNCH; }
   return EFIM_OK;
 }
 

@@ -8,6 +8,7 @@
 // first one thread per (token, pair index) evaluates sincos once and parks it in LDS, then
 // all threads stream the (Hq + 2*Hkv) head rows of those tokens with 16-byte accesses.
 #include "efim_internal.h"
+#include "rope_math.h"
 
 namespace efim {
 namespace {
@@ -28,26 +29,6 @@ struct RopeArgs {
 };
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-
-__device__ __forceinline__ double bf16_bits_to_f64(uint32_t bits16) {
-  return (double)__uint_as_float(bits16 << 16);
-}
-
-// fp64 -> bf16, round to nearest even, with a single rounding.  The conversion goes through
-// fp32; the only case where the detour could round twice is an inexact fp32 result sitting
-// exactly on a bf16 midpoint, which is nudged to the side the exact value lies on.
-__device__ __forceinline__ uint32_t f64_to_bf16_bits(double x) {
-  float f = (float)x;
-  uint32_t u = __float_as_uint(f);
-  if ((u & 0xFFFFu) == 0x8000u) {
-    double back = (double)f;
-    if (back != x) u = (fabs(x) > fabs(back)) ? u + 1u : u - 1u;
-  }
-  // round to nearest even on the upper 16 bits (NaN stays NaN: quiet bit is in the upper half)
-  uint32_t lsb = (u >> 16) & 1u;
-  if ((u & 0x7F800000u) != 0x7F800000u) u += 0x7FFFu + lsb;
-  return u >> 16;
-}
 
 // kTokens = tokens per workgroup: 4 for large steps (all threads busy in the sincos phase),
 // 1 for small ones so that even a few hundred tokens spread over the whole device.
@@ -145,9 +126,7 @@ __global__ __launch_bounds__(kThreads) void rope_append_kernel(
         for (int t = 0; t < 8; ++t) {
           const int j = cp * 8 + t;
           const double c = s_cos[tt][j], s = s_sin[tt][j];
-          const double x1 = bf16_bits_to_f64(x[2 * t]), x2 = bf16_bits_to_f64(x[2 * t + 1]);
-          y[2 * t] = f64_to_bf16_bits(x1 * c - x2 * s);
-          y[2 * t + 1] = f64_to_bf16_bits(x2 * c + x1 * s);
+          rotate_pair_bf16(x[2 * t], x[2 * t + 1], c, s, &y[2 * t], &y[2 * t + 1]);
         }
 #pragma unroll
         for (int t = 0; t < 8; ++t) { ya[t] = y[t]; yb[t] = y[8 + t]; }
@@ -156,9 +135,7 @@ __global__ __launch_bounds__(kThreads) void rope_append_kernel(
         for (int t = 0; t < 8; ++t) {
           const int j = cp * 8 + t;
           const double c = s_cos[tt][j], s = s_sin[tt][j];
-          const double x1 = bf16_bits_to_f64(xa[t]), x2 = bf16_bits_to_f64(xb[t]);
-          ya[t] = f64_to_bf16_bits(x1 * c - x2 * s);
-          yb[t] = f64_to_bf16_bits(x2 * c + x1 * s);
+          rotate_pair_bf16(xa[t], xb[t], c, s, &ya[t], &yb[t]);
         }
       }
 #pragma unroll

@@ -1,0 +1,151 @@
+"""The fused decode step (one new token per request) against the oracle's rope_append followed by
+its extend_attention, and against the library's own two-call path: caches bit-exact, q left
+untouched, outputs within the attention tolerance and identical to the two-call path."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import efim_oracle as O
+from paper_2505_21889_amd import workloads as W
+
+import gpu_util as U
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def E():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2505_21889_amd import binding
+    return binding
+
+
+def run_decode(E, b, kc, vc, interleaved=0, ws=None, sm_scale=0.0):
+    table = torch.from_numpy(b.block_table).cuda()
+    desc = U.make_desc(E, b, table)
+    q = U.dev_bits(b.q_new)
+    k_new, v_new = U.dev_bits(b.k_new), U.dev_bits(b.v_new)
+    kcd, vcd = U.dev_bits(kc), U.dev_bits(vc)
+    out = torch.full(q.shape, 0x7FC1, dtype=torch.int16, device="cuda")
+    nbytes = E.efim_decode_workspace_bytes(desc)
+    assert nbytes >= 64 * 1024
+    if ws is None:
+        ws = torch.zeros(nbytes, dtype=torch.uint8, device="cuda")   # zero-filled once, as the header asks
+    assert ws.numel() >= nbytes
+    E.efim_decode_step(desc, q, k_new, v_new, kcd, vcd, out, b.rope_base, interleaved, sm_scale, ws, ws.numel())
+    torch.cuda.synchronize()
+    assert np.array_equal(U.host_bits(q), b.q_new), "q must stay as given"
+    assert not ws[:64 * 1024].any().item(), "arrival counters must be back at zero"
+    return U.host_bits(out), U.host_bits(kcd), U.host_bits(vcd), ws
+
+
+def oracle_step(b, kc, vc, interleaved=False):
+    kc, vc = kc.copy(), vc.copy()
+    q_roped, _ = O.rope_append(b.cached_len, b.new_len, b.block_table, b.page_size, b.q_new, b.k_new, b.v_new,
+                               kc, vc, b.rope_base, interleaved)
+    ref = O.extend_attention(b.cached_len, b.new_len, b.block_table, b.page_size, q_roped, kc, vc)
+    return q_roped, kc, vc, ref
+
+
+def two_call_path(E, b, kc, vc, interleaved=0):
+    table = torch.from_numpy(b.block_table).cuda()
+    desc = U.make_desc(E, b, table)
+    q = U.dev_bits(b.q_new)
+    kcd, vcd = U.dev_bits(kc), U.dev_bits(vc)
+    E.efim_rope_append(desc, q, U.dev_bits(b.k_new), U.dev_bits(b.v_new), kcd, vcd, b.rope_base, interleaved)
+    out = torch.full(q.shape, 0x7FC1, dtype=torch.int16, device="cuda")
+    nbytes = E.efim_extend_workspace_bytes(desc)
+    ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device="cuda")
+    E.efim_extend_attention(desc, q, kcd, vcd, out, 0.0, ws, nbytes)
+    torch.cuda.synchronize()
+    return U.host_bits(out)
+
+
+CASES = [
+    # name,        cached lengths,                           heads,    D,  interleaved
+    ("gqa_ragged", [0, 1, 15, 16, 17, 63, 64, 300, 1000, 2047], (8, 2), 128, 0),
+    ("mha",        [5, 129, 640],                            (4, 4), 128, 0),
+    ("gqa7_d128",  [777, 31, 4096],                          (28, 4), 128, 1),
+    ("d64",        [0, 100, 1025, 48],                       (8, 4), 64, 0),
+    ("d64_il",     [33, 2000],                               (4, 1), 64, 1),
+]
+
+
+@pytest.mark.parametrize("split", [-1, 64, 0])
+@pytest.mark.parametrize("name,cached,heads,d,interleaved", CASES)
+def test_decode_step_matches_oracle_and_two_call_path(E, name, cached, heads, d, interleaved, split):
+    E.efim_set_tuning(E.EFIM_TUNE_SPLIT_KV, split)
+    try:
+        c = np.array(cached, dtype=np.int32)
+        b = W.make_batch("c1", seed=50 + len(cached), lengths=(c, np.ones_like(c)), heads=heads, head_dim=d)
+        kc, vc = U.oracle_cache(b, fill=0x3C00 if name == "mha" else W.POISON_BITS)
+        q_ref, kc_ref, vc_ref, ref = oracle_step(b, kc, vc, bool(interleaved))
+        got, kc_got, vc_got, ws = run_decode(E, b, kc, vc, interleaved)
+        assert np.array_equal(kc_got, kc_ref) and np.array_equal(vc_got, vc_ref), "cache append must be bit-exact"
+        U.assert_close(got, ref, name)
+        assert np.array_equal(got, two_call_path(E, b, kc, vc, interleaved)), "fused and two-call outputs differ"
+        # a second step on the same workspace (counters were left at zero), same result
+        got2, _, _, _ = run_decode(E, b, kc, vc, interleaved, ws=ws)
+        assert np.array_equal(got, got2)
+    finally:
+        E.efim_set_tuning(E.EFIM_TUNE_SPLIT_KV, -1)
+
+
+def test_decode_sequence_grows_the_cache_token_by_token(E):
+    """Eight consecutive decode steps of three requests: the caches after the last step and
+    every step's output equal the oracle's, which appends token by token too."""
+    heads, d = (8, 2), 128
+    c0 = np.array([14, 250, 1023], dtype=np.int32)
+    steps = 8
+    first = W.make_batch("c1", seed=91, lengths=(c0, np.ones_like(c0)), heads=heads, head_dim=d)
+    # a block table with room for all steps, shared by all of them
+    roomy = W.make_batch("c1", seed=91, lengths=(c0, np.full_like(c0, steps)), heads=heads, head_dim=d,
+                         with_history=True)
+    kc, vc = U.oracle_cache(roomy)
+    kc_ref, vc_ref = kc.copy(), vc.copy()
+    kc_dev, vc_dev = kc.copy(), vc.copy()
+    # one workspace for the whole sequence, zero-filled once; the plans of the steps differ
+    ws = torch.zeros(8 << 20, dtype=torch.uint8, device="cuda")
+    for s in range(steps):
+        b = W.make_batch("c1", seed=200 + s, lengths=(c0 + s, np.ones_like(c0)), heads=heads, head_dim=d,
+                         with_history=False)
+        b.block_table, b.num_pages = roomy.block_table, roomy.num_pages
+        q_ref, kc_ref, vc_ref, ref = oracle_step(b, kc_ref, vc_ref)
+        got, kc_dev, vc_dev, ws = run_decode(E, b, kc_dev, vc_dev, ws=ws)
+        assert np.array_equal(kc_dev, kc_ref) and np.array_equal(vc_dev, vc_ref), "step %d" % s
+        U.assert_close(got, ref, "step %d" % s)
+
+
+def test_decode_shapes_of_the_benchmark(E):
+    """Decode at the batch shapes of c2 / c3 (cached lengths as drawn for those workloads)."""
+    for base in ("c2", "c3"):
+        spec = W.make_batch(base, with_history=False, with_tensors=False)
+        b = W.make_batch(base, lengths=(spec.cached_len, np.ones_like(spec.new_len)))
+        kc, vc = U.oracle_cache(b)
+        _, kc_ref, vc_ref, ref = oracle_step(b, kc, vc)
+        got, kc_got, vc_got, _ = run_decode(E, b, kc, vc)
+        assert np.array_equal(kc_got, kc_ref) and np.array_equal(vc_got, vc_ref)
+        max_abs, rel = U.assert_close(got, ref, base)
+        print("%s decode: max_abs %.3e rel_l2 %.3e" % (base, max_abs, rel))
+
+
+def test_decode_step_rejects_other_batches(E):
+    c = np.array([10, 20], dtype=np.int32)
+    b = W.make_batch("c1", lengths=(c, np.array([1, 2], dtype=np.int32)), heads=(4, 4), head_dim=64)
+    table = torch.from_numpy(b.block_table).cuda()
+    desc = U.make_desc(E, b, table)
+    assert E.efim_decode_workspace_bytes(desc) == 0
+    lib = E.raw_library()
+    import ctypes
+    fake = 0x10000
+    rc = lib.efim_decode_step(ctypes.byref(desc.c), fake, fake, fake, fake, fake, fake + 0x1000, 1e4, 0, 0.0, fake, 1 << 20, None)
+    assert rc == E.EFIM_ERR_UNSUPPORTED
+    b1 = W.make_batch("c1", lengths=(c, np.ones_like(c)), heads=(4, 4), head_dim=64)
+    desc1 = U.make_desc(E, b1, torch.from_numpy(b1.block_table).cuda())
+    need = E.efim_decode_workspace_bytes(desc1)
+    assert need > 0
+    rc = lib.efim_decode_step(ctypes.byref(desc1.c), fake, fake, fake, fake, fake, fake + 0x1000, 1e4, 0, 0.0, fake, need - 1, None)
+    assert rc == E.EFIM_ERR_WORKSPACE
+    rc = lib.efim_decode_step(ctypes.byref(desc1.c), fake, fake, fake, fake, fake, fake + 0x1000, 1e4, 2, 0.0, fake, need, None)
+    assert rc == E.EFIM_ERR_INVALID_ARG
