@@ -205,6 +205,50 @@ def replay(torch, E, W, iters):
     return out
 
 
+def decode_steps(torch, E, W, iters):
+    """Decode (one new token per request) at the batch shapes of c2 and c3: device time of the
+    step through the two calls (efim_rope_append + efim_extend_attention) and through the
+    single-launch efim_decode_step, HIP events on the launch stream around the whole step."""
+    out = {}
+    stream = torch.cuda.current_stream()
+    for base in ("c2", "c3"):
+        spec = W.make_batch(base, with_history=False, with_tensors=False)
+        d = DeviceBatch(torch, E, W, base, lengths=(spec.cached_len, np.ones_like(spec.new_len)), copies=3)
+        nbytes = E.efim_decode_workspace_bytes(d.desc)
+        ws = torch.zeros(nbytes, dtype=torch.uint8, device="cuda")
+        e0, e1 = E.HipEvent(), E.HipEvent()
+        two, one = [], []
+        b = d.host
+        for it in range(10 + iters):
+            s = d.sets[it % len(d.sets)]
+            s["q"].copy_(s["q_raw"])
+            e0.record(stream)
+            run_step(E, d, s, stream)
+            e1.record(stream)
+            e1.synchronize()
+            if it >= 10:
+                two.append(e0.elapsed_ms(e1) * 1e3)
+            e0.record(stream)
+            E.efim_decode_step(d.desc, s["q_raw"], s["k_new"], s["v_new"], s["k_cache"], s["v_cache"], s["out"],
+                               b.rope_base, 0, 0.0, ws, nbytes, stream)
+            e1.record(stream)
+            e1.synchronize()
+            if it >= 10:
+                one.append(e0.elapsed_ms(e1) * 1e3)
+        t2, t1 = float(np.median(two)), float(np.median(one))
+        nbytes_step = d.attn_bytes + d.rope_bytes
+        out[base + "_decode"] = {
+            "batch": b.batch, "two_call_us": round(t2, 2), "single_launch_us": round(t1, 2),
+            "speedup": round(t2 / t1, 3),
+            "single_launch_GBps": round(nbytes_step / t1 / 1e3, 1),
+            "single_launch_frac_hbm": round(nbytes_step / t1 / 1e3 / PEAK_HBM_GBPS, 4),
+            "two_call_frac_hbm": round(nbytes_step / t2 / 1e3 / PEAK_HBM_GBPS, 4),
+        }
+        del d, ws
+        torch.cuda.empty_cache()
+    return out
+
+
 def recorded_traffic(name):
     import hashlib
     rec = MEASURED_TRAFFIC.get(name)
@@ -340,6 +384,7 @@ def main():
             torch.cuda.empty_cache()
         result["workloads"] = extra
         result["service_replay"] = replay(torch, E, W, iters=max(5, args.extra_iters // 3))
+        result["decode_step"] = decode_steps(torch, E, W, iters=args.extra_iters)
 
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(W, name)

@@ -107,39 +107,80 @@ struct Geometry {
   __device__ static int vswz(int row) { return (row & (kChunks / 4 - 1)) << 2; }
 };
 
+// Two floats as one 8-byte access that is coherent across the whole device.
+__device__ __forceinline__ void store_coherent(float* at, float a, float b) {
+  const uint64_t bits = (uint64_t)__float_as_uint(a) | ((uint64_t)__float_as_uint(b) << 32);
+  __hip_atomic_store(reinterpret_cast<uint64_t*>(at), bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void load_coherent(const float* at, float* a, float* b) {
+  const uint64_t bits = __hip_atomic_load(reinterpret_cast<const uint64_t*>(at), __ATOMIC_RELAXED,
+                                          __HIP_MEMORY_SCOPE_AGENT);
+  *a = __uint_as_float((uint32_t)bits);
+  *b = __uint_as_float((uint32_t)(bits >> 32));
+}
+
 // Combines the partial results of a split key range: with M = max_s m_s and
 // w_s = 2^(m_s - M):  out = sum_s w_s O_s / sum_s w_s l_s, splits taken in index order.
-// nthreads threads (thread index t) share rows [row_lo, row_hi) of the tile, D/4 threads per row.
-template <int D>
-__device__ __forceinline__ void merge_rows(const AttnParams& p, const MergeItem& mi, int t, int nthreads,
-                                           int row_lo = 0, int row_hi = 1 << 30) {
+// nthreads threads (thread index t) share rows [row_lo, row_hi) of the tile, D/4 threads per
+// row.  The splits are taken eight at a time with all their loads issued together (one memory
+// round trip per group instead of one per split); a later group rescales the running sums.
+// COHERENT: the partial results were written by other workgroups of the same launch.
+template <int D, bool COHERENT = false>
+__device__ __forceinline__ void merge_rows(const AttnParams& p, const MergeItem& mi, const ReqInfo& rq, int t,
+                                           int nthreads, int row_lo = 0, int row_hi = 1 << 30) {
   constexpr int VEC = D / 4;  // float4 columns per row
+  constexpr int GROUP = 8;
   const int dv = (t % VEC) * 4;
-  const ReqInfo rq = p.reqs[mi.req];
   const int g = p.group;
   row_hi = min(row_hi, mi.row_count);
   for (int lr = row_lo + t / VEC; lr < row_hi; lr += nthreads / VEC) {
-    float mx = -INFINITY;
-    for (int s = 0; s < mi.nsplit; ++s)
-      mx = fmaxf(mx, p.part_ml[((int64_t)(mi.first_slot + s) * p.rows_per_item + lr) * 2]);
+    float mx = -INFINITY, l = 0.f;
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-    float l = 0.f;
-    for (int s = 0; s < mi.nsplit; ++s) {
-      const int64_t prow = (int64_t)(mi.first_slot + s) * p.rows_per_item + lr;
-      const float w = __builtin_amdgcn_exp2f(p.part_ml[prow * 2] - mx);
-      l += w * p.part_ml[prow * 2 + 1];
-      const f32x4 v = *reinterpret_cast<const f32x4*>(p.part_o + prow * D + dv);
-      acc += v * w;
+    for (int s0 = 0; s0 < mi.nsplit; s0 += GROUP) {
+      float m[GROUP], ls[GROUP];
+      f32x4 v[GROUP];
+#pragma unroll
+      for (int i = 0; i < GROUP; ++i) {
+        // splits past the end re-read the last one and get weight zero
+        const int s = min(s0 + i, mi.nsplit - 1);
+        const int64_t prow = (int64_t)(mi.first_slot + s) * p.rows_per_item + lr;
+        if constexpr (COHERENT) {
+          float v0, v1, v2, v3;
+          load_coherent(p.part_ml + prow * 2, &m[i], &ls[i]);
+          load_coherent(p.part_o + prow * D + dv, &v0, &v1);
+          load_coherent(p.part_o + prow * D + dv + 2, &v2, &v3);
+          v[i] = f32x4{v0, v1, v2, v3};
+        } else {
+          m[i] = p.part_ml[prow * 2];
+          ls[i] = p.part_ml[prow * 2 + 1];
+          v[i] = *reinterpret_cast<const f32x4*>(p.part_o + prow * D + dv);
+        }
+      }
+      float gmx = mx;
+#pragma unroll
+      for (int i = 0; i < GROUP; ++i) gmx = fmaxf(gmx, m[i]);
+      if (s0 > 0) {
+        const float back = __builtin_amdgcn_exp2f(mx - gmx);
+        l *= back;
+        acc *= back;
+      }
+      mx = gmx;
+#pragma unroll
+      for (int i = 0; i < GROUP; ++i) {
+        const float w = (s0 + i < mi.nsplit) ? __builtin_amdgcn_exp2f(m[i] - mx) : 0.f;
+        l += w * ls[i];
+        acc += v[i] * w;
+      }
     }
     const float inv = 1.f / l;
     const int row = mi.row_begin + lr;
     const int tok = row / g;
     const int hg = row - tok * g;
     uint16_t* dst = p.out + ((int64_t)(rq.row_start + tok) * p.num_q_heads + mi.kv_head * g + hg) * D + dv;
-    bf16x4 v;
+    bf16x4 o4;
 #pragma unroll
-    for (int e = 0; e < 4; ++e) v[e] = (__bf16)(acc[e] * inv);
-    *reinterpret_cast<u32x2*>(dst) = __builtin_bit_cast(u32x2, v);
+    for (int e = 0; e < 4; ++e) o4[e] = (__bf16)(acc[e] * inv);
+    *reinterpret_cast<u32x2*>(dst) = __builtin_bit_cast(u32x2, o4);
   }
 }
 
@@ -198,49 +239,16 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
   const int wave_min_vis = rq.cached + wave_first_row / g + 1;
   const int wave_max_vis = rq.cached + wave_last_row / g + 1;
 
-  if constexpr (FUSED) {
-    // rotary embedding of the tile's query rows and of the new token's key at position C_r
-    // (the request's only new token is packed row rq.row_start), same arithmetic as the
-    // stand-alone append kernel
-    const int pos = rq.cached;
-    if (tid < D / 2) {
-      double sn, cs;
-      sincos((double)pos * p.inv_freq[tid], &sn, &cs);
-      s_cs[tid] = cs;
-      s_cs[64 + tid] = sn;
-    }
-    __syncthreads();
-    const int64_t kv_row = ((int64_t)rq.row_start * p.num_kv_heads + it.kv_head) * D;
-    for (int idx = tid; idx < (it.row_count + 1) * (D / 2); idx += 64 * WAVES) {
-      const int r = idx / (D / 2), j = idx - r * (D / 2);
-      const int e1 = p.interleaved ? 2 * j : j;
-      const int e2 = p.interleaved ? 2 * j + 1 : j + D / 2;
-      const uint16_t* src = p.k_new + kv_row;
-      uint16_t* dst = s_kv;
-      if (r < it.row_count) {
-        const int rr = it.row_begin + r;
-        const int t_ = rr / g;
-        src = p.q + ((int64_t)(rq.row_start + t_) * p.num_q_heads + it.kv_head * g + (rr - t_ * g)) * D;
-        dst = s_q + r * D;
-      }
-      uint32_t y1, y2;
-      rotate_pair_bf16(src[e1], src[e2], s_cs[j], s_cs[64 + j], &y1, &y2);
-      dst[e1] = (uint16_t)y1;
-      dst[e2] = (uint16_t)y2;
-    }
-    for (int e = tid; e < D; e += 64 * WAVES) s_kv[D + e] = p.v_new[kv_row + e];
-    __syncthreads();
-  }
+  // MFMA B operands of this lane's query row: read here for the plain kernel, after the first
+  // gathers have been issued for the fused one (the rotation then overlaps their latency)
   bf16x8 qb[G::kSteps];
+  if constexpr (!FUSED) {
 #pragma unroll
-  for (int s = 0; s < G::kSteps; ++s) {
-    u32x4 v = {0u, 0u, 0u, 0u};
-    if constexpr (FUSED) {
-      if (row_ok) v = *reinterpret_cast<const u32x4*>(s_q + local_row * D + 16 * s + 8 * hi);
-    } else {
+    for (int s = 0; s < G::kSteps; ++s) {
+      u32x4 v = {0u, 0u, 0u, 0u};
       if (row_ok) v = *reinterpret_cast<const u32x4*>(p.q + q_off + 16 * s + 8 * hi);
+      qb[s] = __builtin_bit_cast(bf16x8, v);
     }
-    qb[s] = __builtin_bit_cast(bf16x8, v);
   }
 
   f32x16 o[G::kDBlocks];
@@ -450,6 +458,47 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
 #pragma unroll
   for (int s0 = 0; s0 < STAGES - 1; ++s0)
     if (s0 < ntiles) issue_tile(s0, lds + s0 * kStageBytes, lds + s0 * kStageBytes + G::kTileBytes);
+  if constexpr (FUSED) {
+    // rotary embedding of the tile's query rows and of the new token's key at position C_r
+    // (the request's only new token is packed row rq.row_start), same arithmetic as the
+    // stand-alone append kernel
+    const int pos = rq.cached;
+    if (tid < D / 2) {
+      double sn, cs;
+      sincos((double)pos * p.inv_freq[tid], &sn, &cs);
+      s_cs[tid] = cs;
+      s_cs[64 + tid] = sn;
+    }
+    __syncthreads();
+    const int64_t kv_row = ((int64_t)rq.row_start * p.num_kv_heads + it.kv_head) * D;
+    for (int idx = tid; idx < (it.row_count + 1) * (D / 2); idx += 64 * WAVES) {
+      const int r = idx / (D / 2), j = idx - r * (D / 2);
+      const int e1 = p.interleaved ? 2 * j : j;
+      const int e2 = p.interleaved ? 2 * j + 1 : j + D / 2;
+      const uint16_t* src = p.k_new + kv_row;
+      uint16_t* dst = s_kv;
+      if (r < it.row_count) {
+        const int rr = it.row_begin + r;
+        const int t_ = rr / g;
+        src = p.q + ((int64_t)(rq.row_start + t_) * p.num_q_heads + it.kv_head * g + (rr - t_ * g)) * D;
+        dst = s_q + r * D;
+      }
+      uint32_t y1, y2;
+      rotate_pair_bf16(src[e1], src[e2], s_cs[j], s_cs[64 + j], &y1, &y2);
+      dst[e1] = (uint16_t)y1;
+      dst[e2] = (uint16_t)y2;
+    }
+    for (int e = tid; e < D; e += 64 * WAVES) s_kv[D + e] = p.v_new[kv_row + e];
+    __syncthreads();
+  }
+  if constexpr (FUSED) {
+#pragma unroll
+    for (int s = 0; s < G::kSteps; ++s) {
+      u32x4 v = {0u, 0u, 0u, 0u};
+      if (row_ok) v = *reinterpret_cast<const u32x4*>(s_q + local_row * D + 16 * s + 8 * hi);
+      qb[s] = __builtin_bit_cast(bf16x8, v);
+    }
+  }
   for (int t0 = 0; t0 < ntiles; t0 += STAGES) {
 #pragma unroll
     for (int s0 = 0; s0 < STAGES; ++s0) {
@@ -517,11 +566,22 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
             f32x4 v;
 #pragma unroll
             for (int e = 0; e < 4; ++e) v[e] = o[d][rr * 4 + e];
-            *reinterpret_cast<f32x4*>(dst + d * 32 + rr * 8 + hi * 4) = v;
+            float* at = dst + d * 32 + rr * 8 + hi * 4;
+            if constexpr (FUSED) {
+              // device-coherent stores: the workgroup that merges may sit on another XCD
+              store_coherent(at, v[0], v[1]);
+              store_coherent(at + 2, v[2], v[3]);
+            } else {
+              *reinterpret_cast<f32x4*>(at) = v;
+            }
           }
         if (hi == 0) {
-          p.part_ml[prow * 2] = m_run;
-          p.part_ml[prow * 2 + 1] = l_tot;
+          if constexpr (FUSED) {
+            store_coherent(p.part_ml + prow * 2, m_run, l_tot);
+          } else {
+            p.part_ml[prow * 2] = m_run;
+            p.part_ml[prow * 2 + 1] = l_tot;
+          }
         }
       }
     }
@@ -531,15 +591,19 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
     // one that draws the last ticket finds all partial results visible, combines them and
     // puts the counter back to zero for the next launch.
     if (it.partial_slot >= 0) {
+      // The partial results travel through device-coherent stores and loads (they bypass the
+      // per-XCD caches), so no cache-wide write-back or invalidate is needed: the stores only
+      // have to be complete before the ticket is drawn.
       const MergeItem mi = p.merges[it.merge_id];
-      __threadfence();
+      __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
       __syncthreads();
-      if (tid == 0) s_last = atomicAdd(p.tickets + it.merge_id, 1) == mi.nsplit - 1;
+      if (tid == 0)
+        s_last = __hip_atomic_fetch_add(p.tickets + it.merge_id, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ==
+                 mi.nsplit - 1;
       __syncthreads();
       if (s_last) {
-        __threadfence();
-        merge_rows<D>(p, mi, tid, 64 * WAVES);
-        if (tid == 0) p.tickets[it.merge_id] = 0;
+        merge_rows<D, true>(p, mi, rq, tid, 64 * WAVES);
+        if (tid == 0) __hip_atomic_store(p.tickets + it.merge_id, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       }
     }
   }
@@ -552,7 +616,7 @@ __global__ __launch_bounds__(256) void merge_kernel(const AttnParams p, const Me
   // this workgroup's slice of the rows
   const int first = blockIdx.y * ROWS;
   if (first >= mi.row_count) return;
-  merge_rows<D>(p, mi, threadIdx.x, 256, first, min(mi.row_count, first + ROWS));
+  merge_rows<D>(p, mi, p.reqs[mi.req], threadIdx.x, 256, first, min(mi.row_count, first + ROWS));
 }
 
 }  // namespace

@@ -92,6 +92,27 @@ def test_decode_step_matches_oracle_and_two_call_path(E, name, cached, heads, d,
         E.efim_set_tuning(E.EFIM_TUNE_SPLIT_KV, -1)
 
 
+def test_decode_merge_across_compute_dies(E):
+    """With the planner's XCD grouping off the parts of a split key range land on different
+    dies: the merging workgroup must still see every partial result."""
+    E.efim_set_tuning(E.EFIM_TUNE_XCD_GROUPING, 0)
+    E.efim_set_tuning(E.EFIM_TUNE_SPLIT_KV, 64)
+    try:
+        c = np.array([3000, 4500, 900, 2222, 5000, 64], dtype=np.int32)
+        b = W.make_batch("c1", seed=77, lengths=(c, np.ones_like(c)), heads=(16, 4), head_dim=128)
+        kc, vc = U.oracle_cache(b)
+        _, kc_ref, vc_ref, ref = oracle_step(b, kc, vc)
+        ws = None
+        for rep in range(3):
+            got, kc_got, vc_got, ws = run_decode(E, b, kc, vc, ws=ws)
+            assert np.array_equal(kc_got, kc_ref) and np.array_equal(vc_got, vc_ref)
+            U.assert_close(got, ref, "rep %d" % rep)
+            assert np.array_equal(got, two_call_path(E, b, kc, vc))
+    finally:
+        E.efim_set_tuning(E.EFIM_TUNE_XCD_GROUPING, 1)
+        E.efim_set_tuning(E.EFIM_TUNE_SPLIT_KV, -1)
+
+
 def test_decode_sequence_grows_the_cache_token_by_token(E):
     """Eight consecutive decode steps of three requests: the caches after the last step and
     every step's output equal the oracle's, which appends token by token too."""
