@@ -215,7 +215,7 @@ def decode_steps(torch, E, W, iters):
         spec = W.make_batch(base, with_history=False, with_tensors=False)
         d = DeviceBatch(torch, E, W, base, lengths=(spec.cached_len, np.ones_like(spec.new_len)), copies=3)
         nbytes = E.efim_decode_workspace_bytes(d.desc)
-        ws = torch.zeros(nbytes, dtype=torch.uint8, device="cuda")
+        ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
         e0, e1 = E.HipEvent(), E.HipEvent()
         two, one = [], []
         b = d.host

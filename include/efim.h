@@ -19,8 +19,12 @@
  *  - Every function returns EFIM_OK (0) or a negative efim_status_t.  No exceptions,
  *    no errno, nothing is printed.
  *  - All device buffers are owned by the caller.  The library allocates no device
- *    memory.  It keeps a small ring of pinned host staging buffers (host memory only)
- *    for the work list it sends to the device.
+ *    memory at run time.  It keeps a small ring of pinned host staging buffers (host
+ *    memory only) for the work list it sends to the device, and its code object carries
+ *    256 KiB of arrival counters (static device memory, one block per staging buffer)
+ *    with which the workgroups of a split key range elect the one that combines them.
+ *    If a kernel is killed half-way (device fault, reset) these counters may be left
+ *    non-zero; after such an event the process should not keep using the library.
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
  *    enqueue work and return; they do not wait for the device.
  *  - Host arrays named in efim_batch_t are read before the call returns and may be
@@ -154,7 +158,8 @@ typedef enum efim_tuning_key {
   EFIM_TUNE_SPLIT_KV = 0,   /* -1 automatic (default), 0 never split, n > 0 split into chunks of n keys (multiple of 64) */
   EFIM_TUNE_XCD_GROUPING = 1, /* 1 (default): items sharing K/V are placed on one XCD; 0: plain cost order */
   EFIM_TUNE_NUM_SLOTS = 2,  /* concurrent workgroup slots assumed by the planner; 0 = query the device */
-  EFIM_TUNE_ROW_TILE = 3    /* query rows per workgroup: 0 automatic (default), 128 or 256 */
+  EFIM_TUNE_ROW_TILE = 3,   /* query rows per workgroup: 0 automatic (default), 128 or 256 */
+  EFIM_TUNE_FUSED_MERGE = 4 /* where split key ranges are combined: -1 (default) inside the kernel for efim_decode_step, by a second launch otherwise; 0 always a second launch; 1 always inside the kernel */
 } efim_tuning_key_t;
 
 int efim_set_tuning(int key, int value);
@@ -180,11 +185,8 @@ int efim_version(void);        /* major * 10000 + minor * 100 + patch */
  * compute, with one kernel: same cache contents bit for bit, same `out`.  The one difference:
  * q is read only -- it is rotated on the fly and NOT rewritten in place.
  *
- * workspace: DEVICE, 256-byte aligned, at least efim_decode_workspace_bytes(batch) bytes.  Its
- * first 64 KiB hold arrival counters of split key ranges: they must be zero when a workspace
- * is used for the first time (zero-fill it once after allocating), and every call that returns
- * EFIM_OK leaves them zero again once its kernel has run.  Calls sharing a workspace must be
- * ordered on one stream.
+ * workspace: DEVICE, 256-byte aligned, at least efim_decode_workspace_bytes(batch) bytes,
+ * contents irrelevant (as for efim_extend_attention).
  * Errors: as efim_extend_attention / efim_rope_append; EFIM_ERR_UNSUPPORTED if some
  * new_len[r] != 1, if there are more than 32 query heads per kv head, or if the planner was
  * forced to 256-row tiles (EFIM_TUNE_ROW_TILE).

@@ -41,7 +41,6 @@ struct StageSlot {
   hipEvent_t done = nullptr;
   bool in_flight = false;
 };
-constexpr int kStageSlots = 8;
 StageSlot g_stage[kStageSlots];
 int g_stage_next = 0;
 std::mutex g_stage_mutex;
@@ -181,7 +180,8 @@ int efim_extend_attention(const efim_batch_t* batch, const void* q, const void* 
   const char* header = nullptr;
   rc = stage_plan(plan, &slot, &header);
   if (rc != EFIM_OK) return rc;
-  rc = launch_extend_attention(batch, plan, header, q, k_cache, v_cache, out, sm_scale, workspace, s);
+  rc = launch_extend_attention(batch, plan, header, (int)(slot - g_stage), q, k_cache, v_cache, out, sm_scale,
+                               workspace, s);
   // the slot is busy until everything enqueued so far on the stream has run
   if (hipEventRecord(slot->done, s) == hipSuccess) slot->in_flight = true;
   else (void)hipStreamSynchronize(s);
@@ -208,7 +208,7 @@ size_t efim_decode_workspace_bytes(const efim_batch_t* batch) {
   if (validate_decode_batch(batch, &total) != EFIM_OK) return 0;
   std::lock_guard<std::mutex> lock(g_plan_mutex);
   const Plan& plan = cached_plan(batch);
-  return kDecodeTicketBytes + (plan.total_bytes < 256 ? 256 : plan.total_bytes);
+  return plan.total_bytes < 256 ? 256 : plan.total_bytes;
 }
 
 int efim_decode_step(const efim_batch_t* batch, const void* q, const void* k_new, const void* v_new,
@@ -227,10 +227,8 @@ int efim_decode_step(const efim_batch_t* batch, const void* q, const void* k_new
     return EFIM_ERR_INVALID_ARG;
   std::lock_guard<std::mutex> lock(g_plan_mutex);
   const Plan& plan = cached_plan(batch);
-  if (plan.rows_per_item != 128 || plan.merges.size() * sizeof(int32_t) > kDecodeTicketBytes)
-    return EFIM_ERR_UNSUPPORTED;
-  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) ||
-      workspace_bytes < kDecodeTicketBytes + plan.total_bytes)
+  if (plan.rows_per_item != 128) return EFIM_ERR_UNSUPPORTED;
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) || workspace_bytes < plan.total_bytes)
     return EFIM_ERR_WORKSPACE;
   if (sm_scale == 0.f) sm_scale = 1.0f / sqrtf((float)batch->head_dim);
   hipStream_t s = static_cast<hipStream_t>(stream);
@@ -239,8 +237,8 @@ int efim_decode_step(const efim_batch_t* batch, const void* q, const void* k_new
   const char* header = nullptr;
   rc = stage_plan(plan, &slot, &header);
   if (rc != EFIM_OK) return rc;
-  rc = launch_decode_step(batch, plan, header, q, k_new, v_new, k_cache, v_cache, out, rope_base,
-                          rope_interleaved, sm_scale, workspace, s);
+  rc = launch_decode_step(batch, plan, header, (int)(slot - g_stage), q, k_new, v_new, k_cache, v_cache, out,
+                          rope_base, rope_interleaved, sm_scale, workspace, s);
   if (hipEventRecord(slot->done, s) == hipSuccess) slot->in_flight = true;
   else (void)hipStreamSynchronize(s);
   return rc;
@@ -275,6 +273,10 @@ int efim_set_tuning(int key, int value) {
     case EFIM_TUNE_ROW_TILE:
       if (value != 0 && value != 128 && value != 256) return EFIM_ERR_INVALID_ARG;
       tuning().row_tile = value;
+      return EFIM_OK;
+    case EFIM_TUNE_FUSED_MERGE:
+      if (value < -1 || value > 1) return EFIM_ERR_INVALID_ARG;
+      tuning().fused_merge = value;
       return EFIM_OK;
     default:
       return EFIM_ERR_INVALID_ARG;

@@ -14,6 +14,9 @@ constexpr int kPageSize = 16;         // tokens per KV page
 constexpr int kKeyTile = 64;          // keys staged in LDS per main-loop iteration (4 pages)
 constexpr int kWavesPerGroup = 4;     // wavefronts per attention workgroup
 constexpr int kMaxRowsPerItem = 256;  // largest query-row tile of one workgroup
+constexpr int kStageSlots = 8;        // work lists (= launches) that can be in flight at once
+constexpr int kTicketSlots = kStageSlots;
+constexpr int kTicketsPerSlot = 8192; // split query tiles one launch can combine in-kernel
 
 // Device-side view of one request.
 struct ReqInfo {
@@ -44,6 +47,7 @@ struct Tuning {
   int xcd_grouping = 1;
   int num_slots = 0;
   int row_tile = 0;  // 0 automatic, 128 or 256 forced
+  int fused_merge = -1;  // split key ranges combined inside the main kernel: -1 decode step only, 0 never, 1 always
 };
 Tuning& tuning();
 
@@ -71,19 +75,18 @@ int launch_rope_append(const efim_batch_t* b, int64_t total_new, void* q, const 
 
 // `header` is the device-visible address of the staged plan header (reqs, items, merges at
 // the plan's offsets); `workspace` holds the split-KV partial results.
-int launch_extend_attention(const efim_batch_t* b, const Plan& plan, const char* header, const void* q,
-                            const void* k_cache, const void* v_cache, void* out, float sm_scale,
-                            void* workspace, hipStream_t stream);
+// `stage_slot` is the index of the staging slot that holds the header: it selects the launch's
+// block of arrival counters.
+int launch_extend_attention(const efim_batch_t* b, const Plan& plan, const char* header, int stage_slot,
+                            const void* q, const void* k_cache, const void* v_cache, void* out,
+                            float sm_scale, void* workspace, hipStream_t stream);
 
 // Fused decode step (every request has exactly one new token): one launch does the rotary
-// embedding, the cache append, the attention and the merge of split key ranges.  The first
-// kDecodeTicketBytes of `workspace` are arrival counters (zero between launches), the partial
-// results follow.
-constexpr size_t kDecodeTicketBytes = 64 * 1024;
+// embedding, the cache append, the attention and the merge of split key ranges.
 constexpr int kDecodeMaxGroup = 32;  // query heads per kv head the fused kernel handles
-int launch_decode_step(const efim_batch_t* b, const Plan& plan, const char* header, const void* q,
-                       const void* k_new, const void* v_new, void* k_cache, void* v_cache, void* out,
-                       double rope_base, int interleaved, float sm_scale, void* workspace,
+int launch_decode_step(const efim_batch_t* b, const Plan& plan, const char* header, int stage_slot,
+                       const void* q, const void* k_new, const void* v_new, void* k_cache, void* v_cache,
+                       void* out, double rope_base, int interleaved, float sm_scale, void* workspace,
                        hipStream_t stream);
 
 void set_last_hip_error(hipError_t e);

@@ -19,6 +19,12 @@
 namespace efim {
 namespace {
 
+// Arrival counters of split query tiles: the workgroup that finishes a tile's last part
+// combines the parts.  One block of counters per work-list staging slot, so that launches in
+// flight at the same time never share a counter; all zero whenever no launch is running
+// (zero-initialised with the module, and the merging workgroup puts its counter back).
+__device__ int32_t g_tickets[kTicketSlots * kTicketsPerSlot];
+
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
@@ -50,8 +56,9 @@ struct AttnParams {
   const uint16_t* v_new;  // [B, Hkv, D]
   uint16_t* k_cache_w;    // the caches again, writable: the new token's K/V are appended
   uint16_t* v_cache_w;
-  int32_t* tickets;       // one arrival counter per split query tile, zero between launches
   const MergeItem* merges;
+  int32_t ticket_base;    // first arrival counter of this launch in g_tickets, or -1: the split
+                          // key ranges are combined by merge_kernel in a second launch
   int32_t interleaved;    // rotary pairing
   double inv_freq[64];    // base^(-2j/D)
 };
@@ -195,8 +202,7 @@ __device__ __forceinline__ void merge_rows(const AttnParams& p, const MergeItem&
 // FUSED (decode step, one new token per request, at most 32 query heads per kv head): the
 // kernel also does what efim_rope_append does for that token -- q is rotated on the way in
 // (global q stays raw), the workgroup whose key range ends with the new token rotates its key,
-// stores key and value into the paged cache and patches them into its LDS tile -- and the
-// workgroup that finishes a split query tile last combines the partial results itself.
+// stores key and value into the paged cache and patches them into its LDS tile.
 template <int D, int WAVES, int STAGES, bool FUSED>
 __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const AttnParams p) {
   using G = Geometry<D>;
@@ -567,7 +573,7 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
 #pragma unroll
             for (int e = 0; e < 4; ++e) v[e] = o[d][rr * 4 + e];
             float* at = dst + d * 32 + rr * 8 + hi * 4;
-            if constexpr (FUSED) {
+            if (p.ticket_base >= 0) {
               // device-coherent stores: the workgroup that merges may sit on another XCD
               store_coherent(at, v[0], v[1]);
               store_coherent(at + 2, v[2], v[3]);
@@ -576,7 +582,7 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
             }
           }
         if (hi == 0) {
-          if constexpr (FUSED) {
+          if (p.ticket_base >= 0) {
             store_coherent(p.part_ml + prow * 2, m_run, l_tot);
           } else {
             p.part_ml[prow * 2] = m_run;
@@ -586,25 +592,23 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
       }
     }
   }
-  if constexpr (FUSED) {
-    // Split query tile: every workgroup publishes its partial result and takes a ticket; the
-    // one that draws the last ticket finds all partial results visible, combines them and
-    // puts the counter back to zero for the next launch.
-    if (it.partial_slot >= 0) {
-      // The partial results travel through device-coherent stores and loads (they bypass the
-      // per-XCD caches), so no cache-wide write-back or invalidate is needed: the stores only
-      // have to be complete before the ticket is drawn.
-      const MergeItem mi = p.merges[it.merge_id];
-      __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
-      __syncthreads();
-      if (tid == 0)
-        s_last = __hip_atomic_fetch_add(p.tickets + it.merge_id, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ==
-                 mi.nsplit - 1;
-      __syncthreads();
-      if (s_last) {
-        merge_rows<D, true>(p, mi, rq, tid, 64 * WAVES);
-        if (tid == 0) __hip_atomic_store(p.tickets + it.merge_id, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      }
+  // Split query tile: every workgroup publishes its partial result and takes a ticket; the one
+  // that draws the last ticket finds all partial results visible, combines them and puts the
+  // counter back to zero for the next launch.  The partial results travel through
+  // device-coherent stores and loads (they bypass the per-XCD caches), so no cache-wide
+  // write-back or invalidate is needed: the stores only have to be complete before the ticket
+  // is drawn.
+  if (it.partial_slot >= 0 && p.ticket_base >= 0) {
+    const MergeItem mi = p.merges[it.merge_id];
+    int32_t* ticket = g_tickets + p.ticket_base + it.merge_id;
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+    __syncthreads();
+    if (tid == 0)
+      s_last = __hip_atomic_fetch_add(ticket, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == mi.nsplit - 1;
+    __syncthreads();
+    if (s_last) {
+      merge_rows<D, true>(p, mi, rq, tid, 64 * WAVES);
+      if (tid == 0) __hip_atomic_store(ticket, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
   }
 }
@@ -644,7 +648,7 @@ void fill_params(AttnParams* p, const efim_batch_t* b, const Plan& plan, const c
   p->v_new = nullptr;
   p->k_cache_w = nullptr;
   p->v_cache_w = nullptr;
-  p->tickets = nullptr;
+  p->ticket_base = -1;
   p->merges = reinterpret_cast<const MergeItem*>(header + plan.off_merges);
   p->interleaved = 0;
   for (double& f : p->inv_freq) f = 0.0;
@@ -652,12 +656,35 @@ void fill_params(AttnParams* p, const efim_batch_t* b, const Plan& plan, const c
 
 }  // namespace
 
-int launch_extend_attention(const efim_batch_t* b, const Plan& plan, const char* header, const void* q,
-                            const void* k_cache, const void* v_cache, void* out, float sm_scale,
-                            void* workspace, hipStream_t stream) {
+namespace {
+
+// Split key ranges are combined inside the main kernel or by merge_kernel in a second launch.
+// In-kernel merging sends the partial results through device-coherent (write-through) stores;
+// that pays for the few rows of a decode step, where it saves a launch, and costs more than
+// the launch once a tile has many rows, so by default only the decode step uses it.
+bool use_tickets(const Plan& plan, bool decode) {
+  const int knob = tuning().fused_merge;
+  const bool want = knob < 0 ? decode : knob != 0;
+  return want && !plan.merges.empty() && plan.merges.size() <= (size_t)kTicketsPerSlot;
+}
+
+int launch_merge(const efim_batch_t* b, const Plan& plan, const AttnParams& p, hipStream_t stream) {
+  const dim3 mgrid((unsigned)plan.merges.size(), (unsigned)(plan.rows_per_item * (b->head_dim / 4) / 256));
+  if (b->head_dim == 128) merge_kernel<128><<<mgrid, 256, 0, stream>>>(p, p.merges);
+  else merge_kernel<64><<<mgrid, 256, 0, stream>>>(p, p.merges);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) { set_last_hip_error(e); return EFIM_ERR_LAUNCH; }
+  return EFIM_OK;
+}
+
+}  // namespace
+
+int launch_extend_attention(const efim_batch_t* b, const Plan& plan, const char* header, int stage_slot,
+                            const void* q, const void* k_cache, const void* v_cache, void* out,
+                            float sm_scale, void* workspace, hipStream_t stream) {
   AttnParams p;
   fill_params(&p, b, plan, header, q, k_cache, v_cache, out, sm_scale, static_cast<char*>(workspace));
-  const MergeItem* merges = p.merges;
+  if (use_tickets(plan, false)) p.ticket_base = stage_slot * kTicketsPerSlot;
 
   const dim3 grid((unsigned)plan.items.size());
   const Tuning& tn = tuning();
@@ -673,29 +700,21 @@ int launch_extend_attention(const efim_batch_t* b, const Plan& plan, const char*
   hipError_t e = hipGetLastError();
   if (tn.ev_stop) (void)hipEventRecord(tn.ev_stop, stream);
   if (e != hipSuccess) { set_last_hip_error(e); return EFIM_ERR_LAUNCH; }
-  if (!plan.merges.empty()) {
-    const dim3 mgrid((unsigned)plan.merges.size(), (unsigned)(plan.rows_per_item * (b->head_dim / 4) / 256));
-    if (b->head_dim == 128) merge_kernel<128><<<mgrid, 256, 0, stream>>>(p, merges);
-    else merge_kernel<64><<<mgrid, 256, 0, stream>>>(p, merges);
-    e = hipGetLastError();
-    if (e != hipSuccess) { set_last_hip_error(e); return EFIM_ERR_LAUNCH; }
-  }
+  if (!plan.merges.empty() && p.ticket_base < 0) return launch_merge(b, plan, p, stream);
   return EFIM_OK;
 }
 
-int launch_decode_step(const efim_batch_t* b, const Plan& plan, const char* header, const void* q,
-                       const void* k_new, const void* v_new, void* k_cache, void* v_cache, void* out,
-                       double rope_base, int interleaved, float sm_scale, void* workspace,
+int launch_decode_step(const efim_batch_t* b, const Plan& plan, const char* header, int stage_slot,
+                       const void* q, const void* k_new, const void* v_new, void* k_cache, void* v_cache,
+                       void* out, double rope_base, int interleaved, float sm_scale, void* workspace,
                        hipStream_t stream) {
-  // workspace: the ticket counters first (kDecodeTicketBytes), the partial results behind them
   AttnParams p;
-  fill_params(&p, b, plan, header, q, k_cache, v_cache, out, sm_scale,
-              static_cast<char*>(workspace) + kDecodeTicketBytes);
+  fill_params(&p, b, plan, header, q, k_cache, v_cache, out, sm_scale, static_cast<char*>(workspace));
+  if (use_tickets(plan, true)) p.ticket_base = stage_slot * kTicketsPerSlot;
   p.k_new = static_cast<const uint16_t*>(k_new);
   p.v_new = static_cast<const uint16_t*>(v_new);
   p.k_cache_w = static_cast<uint16_t*>(k_cache);
   p.v_cache_w = static_cast<uint16_t*>(v_cache);
-  p.tickets = static_cast<int32_t*>(workspace);
   p.interleaved = interleaved;
   const int D = b->head_dim;
   for (int j = 0; j < D / 2; ++j) p.inv_freq[j] = pow(rope_base, -2.0 * j / D);
@@ -708,6 +727,7 @@ int launch_decode_step(const efim_batch_t* b, const Plan& plan, const char* head
   hipError_t e = hipGetLastError();
   if (tn.ev_stop) (void)hipEventRecord(tn.ev_stop, stream);
   if (e != hipSuccess) { set_last_hip_error(e); return EFIM_ERR_LAUNCH; }
+  if (!plan.merges.empty() && p.ticket_base < 0) return launch_merge(b, plan, p, stream);
   return EFIM_OK;
 }
 

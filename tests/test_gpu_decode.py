@@ -29,14 +29,13 @@ def run_decode(E, b, kc, vc, interleaved=0, ws=None, sm_scale=0.0):
     kcd, vcd = U.dev_bits(kc), U.dev_bits(vc)
     out = torch.full(q.shape, 0x7FC1, dtype=torch.int16, device="cuda")
     nbytes = E.efim_decode_workspace_bytes(desc)
-    assert nbytes >= 64 * 1024
+    assert nbytes >= 256
     if ws is None:
-        ws = torch.zeros(nbytes, dtype=torch.uint8, device="cuda")   # zero-filled once, as the header asks
+        ws = torch.full((nbytes,), 0xA5, dtype=torch.uint8, device="cuda")   # contents must not matter
     assert ws.numel() >= nbytes
     E.efim_decode_step(desc, q, k_new, v_new, kcd, vcd, out, b.rope_base, interleaved, sm_scale, ws, ws.numel())
     torch.cuda.synchronize()
     assert np.array_equal(U.host_bits(q), b.q_new), "q must stay as given"
-    assert not ws[:64 * 1024].any().item(), "arrival counters must be back at zero"
     return U.host_bits(out), U.host_bits(kcd), U.host_bits(vcd), ws
 
 
@@ -85,7 +84,7 @@ def test_decode_step_matches_oracle_and_two_call_path(E, name, cached, heads, d,
         assert np.array_equal(kc_got, kc_ref) and np.array_equal(vc_got, vc_ref), "cache append must be bit-exact"
         U.assert_close(got, ref, name)
         assert np.array_equal(got, two_call_path(E, b, kc, vc, interleaved)), "fused and two-call outputs differ"
-        # a second step on the same workspace (counters were left at zero), same result
+        # a second step on the same workspace (the arrival counters were put back), same result
         got2, _, _, _ = run_decode(E, b, kc, vc, interleaved, ws=ws)
         assert np.array_equal(got, got2)
     finally:
@@ -126,8 +125,8 @@ def test_decode_sequence_grows_the_cache_token_by_token(E):
     kc, vc = U.oracle_cache(roomy)
     kc_ref, vc_ref = kc.copy(), vc.copy()
     kc_dev, vc_dev = kc.copy(), vc.copy()
-    # one workspace for the whole sequence, zero-filled once; the plans of the steps differ
-    ws = torch.zeros(8 << 20, dtype=torch.uint8, device="cuda")
+    # one workspace for the whole sequence; the plans of the steps differ
+    ws = torch.full((8 << 20,), 0x5A, dtype=torch.uint8, device="cuda")
     for s in range(steps):
         b = W.make_batch("c1", seed=200 + s, lengths=(c0 + s, np.ones_like(c0)), heads=heads, head_dim=d,
                          with_history=False)

@@ -112,9 +112,44 @@ def test_extend_attention_split_kv_agrees(E, split):
     E.efim_set_tuning(E.EFIM_TUNE_SPLIT_KV, split)
     try:
         got = U.gpu_extend_attention(E, b, q_roped, kc, vc)
+        # the parts of a split range combined inside the kernel instead of by a second launch:
+        # same arithmetic, so the same bits
+        E.efim_set_tuning(E.EFIM_TUNE_FUSED_MERGE, 1)
+        one_launch = U.gpu_extend_attention(E, b, q_roped, kc, vc)
     finally:
         E.efim_set_tuning(E.EFIM_TUNE_SPLIT_KV, -1)
+        E.efim_set_tuning(E.EFIM_TUNE_FUSED_MERGE, -1)
     U.assert_close(got, ref, "split %d" % split)
+    assert np.array_equal(got, one_launch)
+
+
+def test_many_splits_and_overlapping_calls(E):
+    """More than eight parts per query tile (the merge takes them in groups of eight), and
+    several calls in flight on different streams: each uses its own block of arrival counters."""
+    b = _ragged(97, [5000, 1300], [3, 70], heads=(8, 2), head_dim=128)
+    q_roped, kc, vc = _oracle_inputs(b)
+    ref = O.extend_attention(b.cached_len, b.new_len, b.block_table, b.page_size, q_roped, kc, vc)
+    E.efim_set_tuning(E.EFIM_TUNE_SPLIT_KV, 256)
+    E.efim_set_tuning(E.EFIM_TUNE_FUSED_MERGE, 1)
+    try:
+        got = U.gpu_extend_attention(E, b, q_roped, kc, vc)
+        U.assert_close(got, ref, "20 parts")
+        table = torch.from_numpy(b.block_table).cuda()
+        desc = U.make_desc(E, b, table)
+        q, kcd, vcd = U.dev_bits(q_roped), U.dev_bits(kc), U.dev_bits(vc)
+        nbytes = E.efim_extend_workspace_bytes(desc)
+        streams = [torch.cuda.Stream() for _ in range(3)]
+        outs = [torch.full(q.shape, 0x7FC1, dtype=torch.int16, device="cuda") for _ in range(12)]
+        wss = [torch.empty(max(nbytes, 256), dtype=torch.uint8, device="cuda") for _ in range(12)]
+        torch.cuda.synchronize()
+        for i in range(12):
+            E.efim_extend_attention(desc, q, kcd, vcd, outs[i], 0.0, wss[i], nbytes, streams[i % 3])
+        torch.cuda.synchronize()
+        for o in outs:
+            assert np.array_equal(U.host_bits(o), got)
+    finally:
+        E.efim_set_tuning(E.EFIM_TUNE_SPLIT_KV, -1)
+        E.efim_set_tuning(E.EFIM_TUNE_FUSED_MERGE, -1)
 
 
 def test_single_key_is_bit_exact_value_row(E):

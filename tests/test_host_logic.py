@@ -92,6 +92,9 @@ def test_tuning_knobs_validate():
     assert lib.efim_set_tuning(E.EFIM_TUNE_SPLIT_KV, -2) == E.EFIM_ERR_INVALID_ARG
     assert lib.efim_set_tuning(99, 0) == E.EFIM_ERR_INVALID_ARG
     assert lib.efim_set_tuning(E.EFIM_TUNE_XCD_GROUPING, 2) == E.EFIM_ERR_INVALID_ARG
+    assert lib.efim_set_tuning(E.EFIM_TUNE_FUSED_MERGE, 2) == E.EFIM_ERR_INVALID_ARG
+    assert lib.efim_set_tuning(E.EFIM_TUNE_FUSED_MERGE, -2) == E.EFIM_ERR_INVALID_ARG
+    assert lib.efim_set_tuning(E.EFIM_TUNE_FUSED_MERGE, -1) == E.EFIM_OK
     assert lib.efim_set_kernel_events(FAKE_DEV, None) == E.EFIM_ERR_INVALID_ARG
     assert lib.efim_set_kernel_events(None, None) == E.EFIM_OK
 
