@@ -8,6 +8,7 @@
 // results a merge pass combines in a fixed order.
 #include <algorithm>
 #include <cstring>
+#include <functional>
 
 #include "efim_internal.h"
 
@@ -117,15 +118,58 @@ void build_plan(const efim_batch_t* b, int num_slots, Plan* plan) {
   }
 
   // Split policy.  chunk = key tiles per work item (0 = no split).  A workgroup slot's fair
-  // share of the whole step is `avg`; a tile much longer than that would finish last, so it
-  // is cut into pieces of about one share.
+  // share of the whole step is `avg`; a tile much longer than that would finish last, so long
+  // tiles are cut into pieces.  Which piece length is best depends on how the pieces pack
+  // into the slots (one piece too many costs a whole extra round with most slots idle), so
+  // for steps of moderate size the candidates are tried on a model of the device: pieces
+  // handed out longest first to `num_slots` slots, a fixed start-up cost per piece.
   const Tuning& tn = tuning();
+  constexpr int64_t kStartCost = 4;  // start-up of a work item, in units of one key tile
+  auto pieces_of = [&](const Tile& t, int64_t chunk) {
+    return (chunk > 0 && 10 * (int64_t)t.ktiles > 13 * chunk) ? (int)((t.ktiles + chunk - 1) / chunk) : 1;
+  };
   int64_t chunk = 0;
   if (tn.split_kv > 0) {
     chunk = std::max(1, tn.split_kv / kKeyTile);
   } else if (tn.split_kv < 0 && !tiles.empty()) {
     const double avg = (double)total_cost / std::max(1, num_slots);
-    if ((double)max_cost > 1.3 * avg) chunk = (int64_t)std::max(4.0, avg);
+    if ((double)max_cost > 1.3 * avg) {
+      chunk = (int64_t)std::max(4.0, avg);
+      if (tiles.size() <= (size_t)4 * num_slots) {
+        // Model of the device: pieces handed out longest first, each to the slot that is free
+        // first; the step takes as long as the fullest slot.  (A finer model, in which few
+        // busy slots run faster than many because they share the memory bandwidth, was fitted
+        // to chunk sweeps on the device and picked worse plans than this one.)
+        std::vector<int64_t> costs, load;
+        auto makespan = [&](int64_t c) {
+          costs.clear();
+          for (const Tile& t : tiles) {
+            const int n = pieces_of(t, c);
+            const int64_t per = (t.ktiles + n - 1) / n;
+            for (int64_t done = 0; done < t.ktiles; done += per)
+              costs.push_back(std::min<int64_t>(per, t.ktiles - done) + kStartCost);
+          }
+          std::sort(costs.begin(), costs.end(), std::greater<int64_t>());
+          load.assign((size_t)num_slots, 0);  // min-heap of slot loads
+          auto cmp = std::greater<int64_t>();
+          for (int64_t w : costs) {
+            std::pop_heap(load.begin(), load.end(), cmp);
+            load.back() += w;
+            std::push_heap(load.begin(), load.end(), cmp);
+          }
+          return *std::max_element(load.begin(), load.end());
+        };
+        const int64_t lo = std::max<int64_t>(4, (int64_t)(0.5 * avg));
+        const int64_t hi = std::max<int64_t>(lo, max_cost - kStartCost);
+        const int64_t step = std::max<int64_t>(1, (hi - lo) / 48);
+        int64_t best = makespan(chunk), best_chunk = chunk;
+        for (int64_t c = lo; c <= hi; c += step) {
+          const int64_t m = makespan(c);
+          if (m < best || (m == best && c > best_chunk)) { best = m; best_chunk = c; }
+        }
+        chunk = best_chunk;
+      }
+    }
   }
 
   struct Pending { WorkItem w; int64_t cost; int64_t group; };
@@ -133,8 +177,7 @@ void build_plan(const efim_batch_t* b, int num_slots, Plan* plan) {
   pend.reserve(tiles.size() * 2);
   int64_t slot = 0;
   for (const Tile& t : tiles) {
-    int nsplit = 1;
-    if (chunk > 0 && 10 * (int64_t)t.ktiles > 13 * chunk) nsplit = (int)((t.ktiles + chunk - 1) / chunk);
+    const int nsplit = pieces_of(t, chunk);
     const int64_t group = (int64_t)t.req * b->num_kv_heads + t.kv_head;
     if (nsplit == 1) {
       WorkItem w{t.req, t.kv_head, t.row_begin, t.row_count, 0, t.key_end, -1, -1};

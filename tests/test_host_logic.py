@@ -184,6 +184,26 @@ def test_xcd_grouping_places_tiles_sharing_kv_on_one_residue_class():
     assert max(per_xcd) - min(per_xcd) <= 1
 
 
+def test_split_policy_packs_the_pieces_into_the_slots():
+    """Automatic split of a step with fewer (request, kv head) pairs than workgroup slots: the
+    pieces fit the slots in one round (one piece too many would cost an extra round with most
+    slots idle), none is much longer than a slot's fair share, and coverage stays exact."""
+    E.efim_set_tuning(E.EFIM_TUNE_NUM_SLOTS, 512)
+    try:
+        spec = W.make_batch("c3", with_history=False, with_tensors=False)
+        for inc in (1, 16):
+            n = np.full_like(spec.new_len, inc)
+            d = _desc(spec.cached_len.tolist(), n.tolist(), hq=28, hkv=4, d=128)
+            items = E.efim_extend_plan_items(d)
+            _check_plan(spec.cached_len, n, 28, 4, items)
+            live = items[items["row_count"] > 0]
+            tiles = (live["key_end"] - live["key_begin"] + 63) // 64
+            assert 400 <= len(live) <= 512
+            assert tiles.max() <= 1.25 * tiles.sum() / 512 + 2
+    finally:
+        E.efim_set_tuning(E.EFIM_TUNE_NUM_SLOTS, 0)
+
+
 def test_plan_is_deterministic_and_cached_plan_matches_fresh_one():
     d = _desc([700, 0, 3000], [40, 300, 2])
     a = E.efim_extend_plan_items(d)
