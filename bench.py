@@ -100,35 +100,49 @@ def run_step(E, db, s, stream):
 
 
 def time_parts(torch, E, db, iters, warmup):
-    """Per-call device times (HIP events on the launch stream): rope_append, the whole
-    efim_extend_attention call, and its main kernel alone.  Returns median/min in microseconds."""
+    """Device times in microseconds (HIP events on the launch stream).  Phase 1, one call at a
+    time: the main attention kernel alone (events recorded by the library around it).  Phase 2,
+    calls queued back to back as a serving engine issues them: the whole efim_rope_append call
+    and the whole efim_extend_attention call (main kernel, merge pass, launch gaps), total
+    over the queue divided by the number of calls."""
     stream = torch.cuda.current_stream()
-    ev = [E.HipEvent() for _ in range(4)]
     k0, k1 = E.HipEvent(), E.HipEvent()
-    E.efim_set_kernel_events(k0.ptr, k1.ptr)
-    rope, attn, kern = [], [], []
+    e0, e1 = E.HipEvent(), E.HipEvent()
     b = db.host
+    kern = []
+    E.efim_set_kernel_events(k0.ptr, k1.ptr)
     try:
         for it in range(warmup + iters):
             s = db.sets[it % len(db.sets)]
             s["q"].copy_(s["q_raw"])
-            ev[0].record(stream)
             E.efim_rope_append(db.desc, s["q"], s["k_new"], s["v_new"], s["k_cache"], s["v_cache"], b.rope_base, 0, stream)
-            ev[1].record(stream)
-            ev[2].record(stream)
             E.efim_extend_attention(db.desc, s["q"], s["k_cache"], s["v_cache"], s["out"], 0.0, db.ws, db.ws_bytes, stream)
-            ev[3].record(stream)
-            ev[3].synchronize()
+            k1.synchronize()
             if it >= warmup:
-                rope.append(ev[0].elapsed_ms(ev[1]) * 1e3)
-                attn.append(ev[2].elapsed_ms(ev[3]) * 1e3)
                 kern.append(k0.elapsed_ms(k1) * 1e3)
     finally:
         E.efim_set_kernel_events(None, None)
+
+    def queued(call, reps=3):
+        times = []
+        for _ in range(reps):
+            torch.cuda.synchronize()
+            e0.record(stream)
+            for it in range(iters):
+                call(db.sets[it % len(db.sets)])
+            e1.record(stream)
+            e1.synchronize()
+            times.append(e0.elapsed_ms(e1) * 1e3 / iters)
+        return float(np.median(times))
+
+    # (roping an already roped q again only changes values, not the work)
+    rope = queued(lambda s: E.efim_rope_append(db.desc, s["q"], s["k_new"], s["v_new"], s["k_cache"], s["v_cache"],
+                                               b.rope_base, 0, stream))
+    attn = queued(lambda s: E.efim_extend_attention(db.desc, s["q"], s["k_cache"], s["v_cache"], s["out"], 0.0,
+                                                    db.ws, db.ws_bytes, stream))
     med = lambda x: float(np.median(x))
-    return {"rope_us": med(rope), "rope_us_mean": float(np.mean(rope)), "attn_call_us": med(attn),
-            "attn_kernel_us": med(kern), "attn_kernel_us_mean": float(np.mean(kern)),
-            "attn_kernel_us_min": float(np.min(kern))}
+    return {"rope_us": rope, "attn_call_us": attn, "attn_kernel_us": med(kern),
+            "attn_kernel_us_mean": float(np.mean(kern)), "attn_kernel_us_min": float(np.min(kern))}
 
 
 def summarize(db, parts):
@@ -208,7 +222,7 @@ def replay(torch, E, W, iters):
 def decode_steps(torch, E, W, iters):
     """Decode (one new token per request) at the batch shapes of c2 and c3: device time of the
     step through the two calls (efim_rope_append + efim_extend_attention) and through the
-    single-launch efim_decode_step, HIP events on the launch stream around the whole step."""
+    single-launch efim_decode_step; steps queued back to back, HIP events around the queue."""
     out = {}
     stream = torch.cuda.current_stream()
     for base in ("c2", "c3"):
@@ -217,24 +231,23 @@ def decode_steps(torch, E, W, iters):
         nbytes = E.efim_decode_workspace_bytes(d.desc)
         ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
         e0, e1 = E.HipEvent(), E.HipEvent()
-        two, one = [], []
         b = d.host
-        for it in range(10 + iters):
-            s = d.sets[it % len(d.sets)]
-            s["q"].copy_(s["q_raw"])
-            e0.record(stream)
-            run_step(E, d, s, stream)
-            e1.record(stream)
-            e1.synchronize()
-            if it >= 10:
-                two.append(e0.elapsed_ms(e1) * 1e3)
-            e0.record(stream)
-            E.efim_decode_step(d.desc, s["q_raw"], s["k_new"], s["v_new"], s["k_cache"], s["v_cache"], s["out"],
-                               b.rope_base, 0, 0.0, ws, nbytes, stream)
-            e1.record(stream)
-            e1.synchronize()
-            if it >= 10:
-                one.append(e0.elapsed_ms(e1) * 1e3)
+
+        def queued(call, reps=5):
+            times = []
+            for _ in range(reps):
+                torch.cuda.synchronize()
+                e0.record(stream)
+                for it in range(iters):
+                    call(d.sets[it % len(d.sets)])
+                e1.record(stream)
+                e1.synchronize()
+                times.append(e0.elapsed_ms(e1) * 1e3 / iters)
+            return times[1:]  # the first repetition warms up
+
+        two = queued(lambda s: run_step(E, d, s, stream))
+        one = queued(lambda s: E.efim_decode_step(d.desc, s["q_raw"], s["k_new"], s["v_new"], s["k_cache"],
+                                                  s["v_cache"], s["out"], b.rope_base, 0, 0.0, ws, nbytes, stream))
         t2, t1 = float(np.median(two)), float(np.median(one))
         nbytes_step = d.attn_bytes + d.rope_bytes
         out[base + "_decode"] = {
