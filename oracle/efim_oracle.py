@@ -162,6 +162,73 @@ def rope_append(cached_len, new_len, block_table, page_size, q_new, k_new, v_new
 
 
 # --------------------------------------------------------------------------
+# Rotary variants: caller-given frequency table, rotation of the leading part only
+# --------------------------------------------------------------------------
+
+
+def scaled_inv_freq(head_dim, base, factor, low_freq_factor, high_freq_factor, original_context):
+    """Frequency table with the long-context scaling published with the Llama 3.1 models
+    (one of the paper's two models, Sec. 4): with wavelength w_j = 2*pi / f_j of the plain
+    table f_j = base^(-2j/D),
+        w_j < original_context / high_freq_factor   ->  f_j unchanged,
+        w_j > original_context / low_freq_factor    ->  f_j / factor,
+        in between: blend (1 - t) * f_j / factor + t * f_j with
+                    t = (original_context / w_j - low_freq_factor) / (high_freq_factor - low_freq_factor).
+    """
+    plain = rope_inv_freq(head_dim, base)
+    out = np.empty_like(plain)
+    for j, f in enumerate(plain):
+        wavelen = 2.0 * np.pi / f
+        if wavelen < original_context / high_freq_factor:
+            out[j] = f
+        elif wavelen > original_context / low_freq_factor:
+            out[j] = f / factor
+        else:
+            t = (original_context / wavelen - low_freq_factor) / (high_freq_factor - low_freq_factor)
+            out[j] = (1.0 - t) * f / factor + t * f
+    return out
+
+
+def rope_cos_sin_table(positions, inv_freq):
+    """cos/sin of theta[p, j] = p * inv_freq[j] for a given table (same evaluation as rope_cos_sin)."""
+    positions = np.asarray(positions, dtype=np.int64)
+    theta = positions[:, None].astype(np.float64) * np.asarray(inv_freq, dtype=np.float64)[None, :]
+    wide = theta.astype(np.longdouble)
+    return np.cos(wide).astype(np.float64), np.sin(wide).astype(np.float64)
+
+
+def rope_rotate_leading(x, cos, sin, rotary_dim, interleaved=False):
+    """Rotate the first ``rotary_dim`` elements of every head row of ``x[n, H, D]`` (pairs taken
+    inside that part: (j, j + rotary_dim/2), or (2j, 2j+1) when interleaved; tables
+    ``[n, rotary_dim/2]``); the remaining D - rotary_dim elements pass through."""
+    x = np.asarray(x, dtype=np.float64)
+    y = x.copy()
+    y[..., :rotary_dim] = rope_rotate(x[..., :rotary_dim], cos, sin, interleaved)
+    return y
+
+
+def rope_append_table(cached_len, new_len, block_table, page_size, q_new, k_new, v_new,
+                      k_cache, v_cache, inv_freq, rotary_dim, interleaved=False):
+    """rope_append with a caller-given frequency table (rotary_dim/2 entries) and a rotation of
+    the leading rotary_dim elements only; everything else as rope_append."""
+    pos = new_token_positions(cached_len, new_len)
+    cos, sin = rope_cos_sin_table(pos, inv_freq)
+    k_roped = f64_to_bf16(rope_rotate_leading(bf16_to_f64(k_new), cos, sin, rotary_dim, interleaved))
+    q_roped = None
+    if q_new is not None:
+        q_roped = f64_to_bf16(rope_rotate_leading(bf16_to_f64(q_new), cos, sin, rotary_dim, interleaved))
+    row = 0
+    for r, (c, n) in enumerate(zip(cached_len, new_len)):
+        for i in range(int(n)):
+            p = int(c) + i
+            page = int(block_table[r, p // page_size])
+            k_cache[page, :, p % page_size, :] = k_roped[row]
+            v_cache[page, :, p % page_size, :] = v_new[row]
+            row += 1
+    return q_roped, k_roped
+
+
+# --------------------------------------------------------------------------
 # Paged gather and extend attention
 # --------------------------------------------------------------------------
 

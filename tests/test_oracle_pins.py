@@ -458,3 +458,51 @@ def test_gather_kv_walks_the_block_table_in_logical_order():
     got = O.gather_kv(cache, row, 10, page, 0)
     want = np.concatenate([cache[4, 0], cache[1, 0], cache[5, 0, :2]])
     assert np.array_equal(got, want)
+
+
+# --- rotary variants: frequency table given by the caller, leading-part rotation --------------
+
+def test_table_variant_reduces_to_the_plain_one():
+    b = W.make_batch("c1", seed=3, lengths=(np.array([37], dtype=np.int32), np.array([9], dtype=np.int32)))
+    kc1, vc1 = W.poisoned_cache(b), W.poisoned_cache(b)
+    kc2, vc2 = W.poisoned_cache(b), W.poisoned_cache(b)
+    for inter in (False, True):
+        q1, k1 = O.rope_append(b.cached_len, b.new_len, b.block_table, b.page_size, b.q_new, b.k_new, b.v_new,
+                               kc1, vc1, b.rope_base, inter)
+        q2, k2 = O.rope_append_table(b.cached_len, b.new_len, b.block_table, b.page_size, b.q_new, b.k_new, b.v_new,
+                                     kc2, vc2, O.rope_inv_freq(b.head_dim, b.rope_base), b.head_dim, inter)
+        assert np.array_equal(q1, q2) and np.array_equal(k1, k2)
+        assert np.array_equal(kc1, kc2) and np.array_equal(vc1, vc2)
+
+
+def test_leading_part_rotation_is_a_rotation_of_a_shorter_head():
+    rng = np.random.default_rng(12)
+    x = rng.standard_normal((5, 3, 64))
+    pos = np.array([0, 1, 7, 100, 4095])
+    for rd in (16, 32, 64):
+        table = O.rope_inv_freq(rd, 1.0e4)          # the table of a head of rd elements
+        cos, sin = O.rope_cos_sin_table(pos, table)
+        for inter in (False, True):
+            y = O.rope_rotate_leading(x, cos, sin, rd, inter)
+            assert np.array_equal(y[..., rd:], x[..., rd:])                      # tail untouched, bit for bit
+            c2, s2 = O.rope_cos_sin(pos, rd, 1.0e4)
+            assert np.array_equal(y[..., :rd], O.rope_rotate(x[..., :rd], c2, s2, inter))
+            # and a rotation preserves the norm of every pair
+            assert np.allclose((y[..., :rd] ** 2).sum(-1), (x[..., :rd] ** 2).sum(-1), rtol=1e-12)
+
+
+def test_scaled_table_band_edges_worked_out_by_hand():
+    # D = 128, base 5e5, factor 8, low 1, high 4, original context 8192.
+    # wavelength_j = 2*pi * base^(2j/128); unchanged while it is < 8192/4 = 2048:
+    #   base^(2j/128) < 2048 / (2 pi) = 325.9  <=>  j < 64 * ln(325.9) / ln(5e5) = 28.2
+    # divided by 8 once it is > 8192:  base^(2j/128) > 1303.8  <=>  j > 34.99
+    plain = O.rope_inv_freq(128, 5.0e5)
+    got = O.scaled_inv_freq(128, 5.0e5, 8.0, 1.0, 4.0, 8192)
+    assert np.array_equal(got[:29], plain[:29])
+    assert np.array_equal(got[35:], plain[35:] / 8.0)
+    mid = got[29:35] / plain[29:35]
+    assert np.all(mid < 1.0) and np.all(mid > 0.125) and np.all(np.diff(mid) < 0)   # blend, falling with j
+    # the blend is continuous at both edges: its weight is 1 at wavelength 2048 and 0 at 8192
+    f_edge = 2.0 * np.pi / 2048.0
+    t = (8192.0 / 2048.0 - 1.0) / (4.0 - 1.0)
+    assert t == 1.0 and (1 - t) * f_edge / 8.0 + t * f_edge == f_edge
