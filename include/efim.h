@@ -98,6 +98,22 @@ int efim_rope_append(const efim_batch_t* batch, void* q, const void* k_new, cons
                      void* stream);
 
 /*
+ * efim_rope_append_table -- the same with the rotary variants of the models the paper serves
+ * (Sec. 4: their public configurations scale the frequencies for long contexts or rotate
+ * only part of a head): pair j rotates by pos * inv_freq[j], and only the leading rotary_dim
+ * elements of every head row take part -- pairs (x[j], x[j + rotary_dim/2]) or, interleaved,
+ * (x[2j], x[2j + 1]), j < rotary_dim/2; elements rotary_dim .. D-1 are copied bit for bit.
+ *   inv_freq    HOST double[rotary_dim / 2], finite; read before the call returns
+ *   rotary_dim  multiple of 16, 16 <= rotary_dim <= head_dim
+ * efim_rope_append(.., rope_base, ..) is this call with inv_freq[j] = rope_base^(-2j/D) and
+ * rotary_dim = D.  Everything else (buffers, slots written, errors) as efim_rope_append;
+ * EFIM_ERR_INVALID_ARG also for a NULL or non-finite table or a bad rotary_dim.
+ */
+int efim_rope_append_table(const efim_batch_t* batch, void* q, const void* k_new, const void* v_new,
+                           void* k_cache, void* v_cache, const double* inv_freq, int rotary_dim,
+                           int rope_interleaved, void* stream);
+
+/*
  * efim_extend_workspace_bytes -- device workspace efim_extend_attention needs for this
  * batch (work list plus split-KV partial results).  Pure host function; returns 0 for an
  * invalid batch.  The size depends only on the host fields of `batch`.

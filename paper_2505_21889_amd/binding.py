@@ -77,6 +77,8 @@ def _load():
     bp = ctypes.POINTER(EfimBatch)
     lib.efim_rope_append.argtypes = [bp, vp, vp, vp, vp, vp, ctypes.c_double, i32, vp]
     lib.efim_rope_append.restype = i32
+    lib.efim_rope_append_table.argtypes = [bp, vp, vp, vp, vp, vp, ctypes.POINTER(ctypes.c_double), i32, i32, vp]
+    lib.efim_rope_append_table.restype = i32
     lib.efim_extend_workspace_bytes.argtypes = [bp]
     lib.efim_extend_workspace_bytes.restype = ctypes.c_size_t
     lib.efim_extend_attention.argtypes = [bp, vp, vp, vp, vp, ctypes.c_float, vp, ctypes.c_size_t, vp]
@@ -117,7 +119,7 @@ def _load():
 _lib = _load()
 LIBRARY_PATH = os.environ.get("EFIM_LIBRARY") or _build.LIB_PATH
 EXPORTED_SYMBOLS = (
-    "efim_rope_append", "efim_extend_workspace_bytes", "efim_extend_attention",
+    "efim_rope_append", "efim_rope_append_table", "efim_extend_workspace_bytes", "efim_extend_attention",
     "efim_decode_workspace_bytes", "efim_decode_step",
     "efim_extend_plan_items", "efim_set_tuning", "efim_set_kernel_events", "efim_status_string",
     "efim_last_hip_error", "efim_version",
@@ -178,6 +180,16 @@ def efim_rope_append(batch, q, k_new, v_new, k_cache, v_cache, rope_base, rope_i
     _check(_lib.efim_rope_append(ctypes.byref(batch.c), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(k_cache),
                                  _ptr(v_cache), float(rope_base), int(rope_interleaved), _stream_ptr(stream)),
            "efim_rope_append")
+
+
+def efim_rope_append_table(batch, q, k_new, v_new, k_cache, v_cache, inv_freq, rotary_dim, rope_interleaved=0,
+                           stream=None):
+    table = np.ascontiguousarray(np.asarray(inv_freq, dtype=np.float64).reshape(-1))
+    assert table.size >= int(rotary_dim) // 2, "inv_freq needs rotary_dim / 2 entries"
+    _check(_lib.efim_rope_append_table(ctypes.byref(batch.c), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(k_cache),
+                                       _ptr(v_cache), table.ctypes.data_as(ctypes.POINTER(ctypes.c_double)),
+                                       int(rotary_dim), int(rope_interleaved), _stream_ptr(stream)),
+           "efim_rope_append_table")
 
 
 def efim_extend_workspace_bytes(batch):

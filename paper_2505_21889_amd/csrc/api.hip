@@ -132,6 +132,22 @@ using namespace efim;
 
 extern "C" {
 
+namespace {
+
+int rope_append_checked(const efim_batch_t* batch, void* q, const void* k_new, const void* v_new,
+                        void* k_cache, void* v_cache, const double* inv_freq, int rotary_dim,
+                        int rope_interleaved, void* stream, int64_t total) {
+  if (total == 0) return EFIM_OK;
+  if (!k_new || !v_new || !k_cache || !v_cache) return EFIM_ERR_INVALID_ARG;
+  if (!aligned16(q) || !aligned16(k_new) || !aligned16(v_new) || !aligned16(k_cache) ||
+      !aligned16(v_cache) || (reinterpret_cast<uintptr_t>(batch->block_table) & 3u))
+    return EFIM_ERR_INVALID_ARG;
+  return launch_rope_append(batch, total, q, k_new, v_new, k_cache, v_cache, inv_freq, rotary_dim,
+                            rope_interleaved, static_cast<hipStream_t>(stream));
+}
+
+}  // namespace
+
 int efim_rope_append(const efim_batch_t* batch, void* q, const void* k_new, const void* v_new,
                      void* k_cache, void* v_cache, double rope_base, int rope_interleaved,
                      void* stream) {
@@ -139,13 +155,25 @@ int efim_rope_append(const efim_batch_t* batch, void* q, const void* k_new, cons
   int rc = validate_batch(batch, &total);
   if (rc != EFIM_OK) return rc;
   if (!(rope_base > 0.0) || (rope_interleaved != 0 && rope_interleaved != 1)) return EFIM_ERR_INVALID_ARG;
-  if (total == 0) return EFIM_OK;
-  if (!k_new || !v_new || !k_cache || !v_cache) return EFIM_ERR_INVALID_ARG;
-  if (!aligned16(q) || !aligned16(k_new) || !aligned16(v_new) || !aligned16(k_cache) ||
-      !aligned16(v_cache) || (reinterpret_cast<uintptr_t>(batch->block_table) & 3u))
-    return EFIM_ERR_INVALID_ARG;
-  return launch_rope_append(batch, total, q, k_new, v_new, k_cache, v_cache, rope_base,
-                            rope_interleaved, static_cast<hipStream_t>(stream));
+  const int D = batch->head_dim;
+  double inv_freq[64];
+  for (int j = 0; j < D / 2; ++j) inv_freq[j] = pow(rope_base, -2.0 * j / D);
+  return rope_append_checked(batch, q, k_new, v_new, k_cache, v_cache, inv_freq, D, rope_interleaved, stream,
+                             total);
+}
+
+int efim_rope_append_table(const efim_batch_t* batch, void* q, const void* k_new, const void* v_new,
+                           void* k_cache, void* v_cache, const double* inv_freq, int rotary_dim,
+                           int rope_interleaved, void* stream) {
+  int64_t total = 0;
+  int rc = validate_batch(batch, &total);
+  if (rc != EFIM_OK) return rc;
+  if (!inv_freq || (rope_interleaved != 0 && rope_interleaved != 1)) return EFIM_ERR_INVALID_ARG;
+  if (rotary_dim < 16 || rotary_dim > batch->head_dim || rotary_dim % 16 != 0) return EFIM_ERR_INVALID_ARG;
+  for (int j = 0; j < rotary_dim / 2; ++j)
+    if (!(inv_freq[j] == inv_freq[j]) || inv_freq[j] - inv_freq[j] != 0.0) return EFIM_ERR_INVALID_ARG;  // NaN / inf
+  return rope_append_checked(batch, q, k_new, v_new, k_cache, v_cache, inv_freq, rotary_dim, rope_interleaved,
+                             stream, total);
 }
 
 size_t efim_extend_workspace_bytes(const efim_batch_t* batch) {

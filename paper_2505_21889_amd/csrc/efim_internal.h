@@ -69,9 +69,10 @@ int validate_batch(const efim_batch_t* b, int64_t* total_new);
 // Builds the work list. num_slots = number of workgroups the device runs concurrently.
 void build_plan(const efim_batch_t* b, int num_slots, Plan* plan);
 
+// inv_freq: rotary_dim/2 host values; the leading rotary_dim elements of every head row rotate.
 int launch_rope_append(const efim_batch_t* b, int64_t total_new, void* q, const void* k_new,
-                       const void* v_new, void* k_cache, void* v_cache, double rope_base,
-                       int interleaved, hipStream_t stream);
+                       const void* v_new, void* k_cache, void* v_cache, const double* inv_freq,
+                       int rotary_dim, int interleaved, hipStream_t stream);
 
 // `header` is the device-visible address of the staged plan header (reqs, items, merges at
 // the plan's offsets); `workspace` holds the split-KV partial results.

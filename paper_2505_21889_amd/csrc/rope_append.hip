@@ -17,7 +17,7 @@ constexpr int kThreads = 256;
 constexpr int kMaxReqPerLaunch = 384;
 
 struct RopeArgs {
-  double inv_freq[64];                      // base^(-2j/D), computed on the host
+  double inv_freq[64];                      // rotation frequency of pair j (rotary_dim/2 entries)
   int32_t cached[kMaxReqPerLaunch];         // C_r of the requests of this launch
   int32_t row_start[kMaxReqPerLaunch + 1];  // first packed row of each request, and the end
   int32_t nreq;
@@ -26,6 +26,7 @@ struct RopeArgs {
   int32_t num_q_heads;
   int32_t num_kv_heads;
   int32_t rotate_q;                         // 0 when q is NULL
+  int32_t rotary_dim;                       // leading elements of a head row that are rotated
 };
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -39,6 +40,7 @@ __global__ __launch_bounds__(kThreads) void rope_append_kernel(
     uint16_t* __restrict__ v_cache, const int32_t* __restrict__ block_table) {
 #pragma clang fp contract(off)
   constexpr int HALF = D / 2;
+  const int rot_half = args.rotary_dim / 2;  // pairs per head row (D/2 when the whole row rotates)
   __shared__ double s_cos[kTokens][HALF];
   __shared__ double s_sin[kTokens][HALF];
   __shared__ int64_t s_dst[kTokens];  // element offset of (page, head 0, slot, 0) in the caches
@@ -52,7 +54,7 @@ __global__ __launch_bounds__(kThreads) void rope_append_kernel(
     const int tt = tid >> 6;
     const int j = tid & 63;
     const int row = tok0 + tt;
-    if (tt < kTokens && j < HALF && row < end_row) {
+    if (tt < kTokens && j < rot_half && row < end_row) {
       // request of this row: last r with row_start[r] <= row < row_start[r + 1]
       int lo = 0, hi = args.nreq;  // invariant: row_start[lo] <= row, row_start[hi] > row
       while (hi - lo > 1) {
@@ -74,9 +76,10 @@ __global__ __launch_bounds__(kThreads) void rope_append_kernel(
   __syncthreads();
 
   const int hq = args.num_q_heads, hkv = args.num_kv_heads;
-  // A unit is 16 bytes of one head row together with its partner 16 bytes: for rotate-half
-  // the chunk D/2 elements further on, for interleaved pairing (and for the plain copy of V)
-  // simply the next chunk.
+  // A unit is 16 bytes of one head row together with its partner 16 bytes.  Units inside the
+  // rotated part: for rotate-half the chunk rotary_dim/2 elements further on, for interleaved
+  // pairing the next chunk.  Units behind the rotated part (and all of V) are plain copies of
+  // two neighbouring chunks.
   constexpr int UNITS_PER_ROW = D / 16;
   const int rows_per_tok = hq + 2 * hkv;
   const int units_per_tok = rows_per_tok * UNITS_PER_ROW;
@@ -88,11 +91,12 @@ __global__ __launch_bounds__(kThreads) void rope_append_kernel(
     const int cp = w - hr * UNITS_PER_ROW;
     const int64_t row = tok0 + tt;
     int e0, e1;  // element offsets of the two chunks inside the head row
-    if (INTERLEAVED) { e0 = cp * 16; e1 = cp * 16 + 8; } else { e0 = cp * 8; e1 = cp * 8 + HALF; }
+    const bool in_rotary = cp * 16 < args.rotary_dim;
+    if (INTERLEAVED || !in_rotary) { e0 = cp * 16; e1 = cp * 16 + 8; } else { e0 = cp * 8; e1 = cp * 8 + rot_half; }
 
     const uint16_t* src;
     uint16_t* dst;
-    bool rotate = true;
+    bool rotate = in_rotary;
     if (hr < hq) {
       if (!args.rotate_q) continue;
       src = q + (row * hq + hr) * D;
@@ -152,13 +156,14 @@ __global__ __launch_bounds__(kThreads) void rope_append_kernel(
 }  // namespace
 
 int launch_rope_append(const efim_batch_t* b, int64_t total_new, void* q, const void* k_new,
-                       const void* v_new, void* k_cache, void* v_cache, double rope_base,
-                       int interleaved, hipStream_t stream) {
+                       const void* v_new, void* k_cache, void* v_cache, const double* inv_freq,
+                       int rotary_dim, int interleaved, hipStream_t stream) {
   (void)total_new;
   const int D = b->head_dim;
   RopeArgs args;
   for (int j = 0; j < 64; ++j) args.inv_freq[j] = 0.0;
-  for (int j = 0; j < D / 2; ++j) args.inv_freq[j] = pow(rope_base, -2.0 * j / D);
+  for (int j = 0; j < rotary_dim / 2; ++j) args.inv_freq[j] = inv_freq[j];
+  args.rotary_dim = rotary_dim;
   args.max_pages = b->max_pages_per_req;
   args.num_q_heads = b->num_q_heads;
   args.num_kv_heads = b->num_kv_heads;

@@ -221,3 +221,26 @@ def test_end_to_end_gpu_append_then_attention_equals_full_recompute(E):
         U.assert_close(got[ns:ns + n], ref, "request %d" % r)
         hs += c
         ns += n
+
+
+@pytest.mark.parametrize("d,rotary_dim,interleaved", [(128, 128, 0), (128, 64, 0), (128, 32, 1), (64, 64, 1),
+                                                     (64, 16, 0), (128, 96, 0)])
+def test_rope_append_table_bit_exact(E, d, rotary_dim, interleaved):
+    """Caller-given frequency table (the Llama 3.1 long-context scaling of the plain table) and
+    rotation of the leading rotary_dim elements only: roped q, K cache and V cache bit for bit."""
+    b = _ragged(140 + rotary_dim, [0, 33, 4000, 250], [70, 5, 1, 129], heads=(8, 2), head_dim=d)
+    table = O.scaled_inv_freq(rotary_dim, 5.0e5, 8.0, 1.0, 4.0, 8192)
+    kc, vc = U.oracle_cache(b)
+    kc_ref, vc_ref = kc.copy(), vc.copy()
+    q_ref, _ = O.rope_append_table(b.cached_len, b.new_len, b.block_table, b.page_size, b.q_new, b.k_new, b.v_new,
+                                   kc_ref, vc_ref, table, rotary_dim, bool(interleaved))
+    tab = torch.from_numpy(b.block_table).cuda()
+    desc = U.make_desc(E, b, tab)
+    q, kcd, vcd = U.dev_bits(b.q_new), U.dev_bits(kc), U.dev_bits(vc)
+    E.efim_rope_append_table(desc, q, U.dev_bits(b.k_new), U.dev_bits(b.v_new), kcd, vcd, table, rotary_dim, interleaved)
+    torch.cuda.synchronize()
+    assert np.array_equal(U.host_bits(q), q_ref)
+    assert np.array_equal(U.host_bits(kcd), kc_ref)
+    assert np.array_equal(U.host_bits(vcd), vc_ref)
+    if rotary_dim < d:   # the tail of every head row is the input, untouched
+        assert np.array_equal(U.host_bits(q)[..., rotary_dim:], b.q_new[..., rotary_dim:])

@@ -86,6 +86,25 @@ def test_empty_batches_succeed_without_launching():
     assert len(E.efim_extend_plan_items(no_rows)) == 0
 
 
+def test_rope_table_argument_validation_without_a_device():
+    lib = E.raw_library()
+    d = _desc([10], [5])
+    good = (ctypes.c_double * 64)(*[1.0 / (j + 1) for j in range(64)])
+    call = lambda table, rd, inter=0: lib.efim_rope_append_table(
+        ctypes.byref(d.c), FAKE_DEV, FAKE_DEV, FAKE_DEV, FAKE_DEV, FAKE_DEV, table, rd, inter, None)
+    bad = E.EFIM_ERR_INVALID_ARG
+    assert call(None, 128) == bad
+    for rd in (0, 8, 24, 144, -16):
+        assert call(good, rd) == bad            # multiple of 16 within [16, head_dim]
+    assert call(good, 64, 2) == bad
+    nan = (ctypes.c_double * 64)(*([1.0] * 10 + [float("nan")] + [1.0] * 53))
+    inf = (ctypes.c_double * 64)(*([float("inf")] + [1.0] * 63))
+    assert call(nan, 128) == bad and call(inf, 16) == bad
+    assert call(nan, 16) != bad                 # entries behind rotary_dim / 2 are not read
+    empty = _desc([10], [0])
+    assert lib.efim_rope_append_table(ctypes.byref(empty.c), None, None, None, None, None, good, 64, 0, None) == E.EFIM_OK
+
+
 def test_tuning_knobs_validate():
     lib = E.raw_library()
     assert lib.efim_set_tuning(E.EFIM_TUNE_SPLIT_KV, 100) == E.EFIM_ERR_INVALID_ARG   # not a multiple of 64
