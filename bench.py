@@ -32,7 +32,7 @@ if ROOT not in sys.path:
 # on: the digest of extend_attention.hip is recorded with it and checked at run time.
 MEASURED_TRAFFIC = {
     # workload: (bytes per launch, sha256 of csrc/extend_attention.hip when measured)
-    "c5": (2560415317, "398e7c7e05c7eb3bb5ab496662987b37cceb5bbbf84f3ffbc5b9e45b835e02ae"),
+    "c5": (2561195938, "5f989d60471b0031610614c7879fe3d0fc3f46af040f37e51f45cfc6a9a93cd8"),
 }
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak
@@ -48,6 +48,9 @@ def parse_args():
     ap.add_argument("--no-extra", action="store_true", help="skip the other workloads and sweeps")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--extra-iters", type=int, default=30)
+    ap.add_argument("--decode-only", action="store_true",
+                    help="run only the decode-step section (used to profile that kernel on its own; "
+                         "--workload c2 or c3 restricts it to that batch shape)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="first run a plain 1 GiB device copy (reference dispatch for the HBM byte counters)")
     return ap.parse_args()
@@ -100,28 +103,27 @@ def run_step(E, db, s, stream):
 
 
 def time_parts(torch, E, db, iters, warmup):
-    """Device times in microseconds (HIP events on the launch stream).  Phase 1, one call at a
-    time: the main attention kernel alone (events recorded by the library around it).  Phase 2,
-    calls queued back to back as a serving engine issues them: the whole efim_rope_append call
-    and the whole efim_extend_attention call (main kernel, merge pass, launch gaps), total
-    over the queue divided by the number of calls."""
+    """Device times in microseconds (HIP events on the launch stream), everything queued back to
+    back as a serving engine issues it (the device stays as warm as in the headline loop).
+    Phase 1, whole steps (rope_append + extend_attention): the main attention kernel alone, one
+    pair of events per step recorded by the library around it.  Phase 2: the whole
+    efim_rope_append call and the whole efim_extend_attention call (main kernel, merge pass,
+    launch gaps), total over the queue divided by the number of calls."""
     stream = torch.cuda.current_stream()
-    k0, k1 = E.HipEvent(), E.HipEvent()
     e0, e1 = E.HipEvent(), E.HipEvent()
     b = db.host
-    kern = []
-    E.efim_set_kernel_events(k0.ptr, k1.ptr)
+    pairs = [(E.HipEvent(), E.HipEvent()) for _ in range(iters)]
     try:
         for it in range(warmup + iters):
             s = db.sets[it % len(db.sets)]
-            s["q"].copy_(s["q_raw"])
+            if it >= warmup:
+                E.efim_set_kernel_events(pairs[it - warmup][0].ptr, pairs[it - warmup][1].ptr)
             E.efim_rope_append(db.desc, s["q"], s["k_new"], s["v_new"], s["k_cache"], s["v_cache"], b.rope_base, 0, stream)
             E.efim_extend_attention(db.desc, s["q"], s["k_cache"], s["v_cache"], s["out"], 0.0, db.ws, db.ws_bytes, stream)
-            k1.synchronize()
-            if it >= warmup:
-                kern.append(k0.elapsed_ms(k1) * 1e3)
+        torch.cuda.synchronize()
     finally:
         E.efim_set_kernel_events(None, None)
+    kern = [a.elapsed_ms(c) * 1e3 for a, c in pairs]
 
     def queued(call, reps=3):
         times = []
@@ -219,13 +221,13 @@ def replay(torch, E, W, iters):
     return out
 
 
-def decode_steps(torch, E, W, iters):
+def decode_steps(torch, E, W, iters, shapes=("c2", "c3")):
     """Decode (one new token per request) at the batch shapes of c2 and c3: device time of the
     step through the two calls (efim_rope_append + efim_extend_attention) and through the
     single-launch efim_decode_step; steps queued back to back, HIP events around the queue."""
     out = {}
     stream = torch.cuda.current_stream()
-    for base in ("c2", "c3"):
+    for base in shapes:
         spec = W.make_batch(base, with_history=False, with_tensors=False)
         d = DeviceBatch(torch, E, W, base, lengths=(spec.cached_len, np.ones_like(spec.new_len)), copies=3)
         nbytes = E.efim_decode_workspace_bytes(d.desc)
@@ -326,6 +328,11 @@ def main():
         torch.cuda.synchronize()
         del src, dst
         torch.cuda.empty_cache()
+
+    if args.decode_only:
+        shapes = (args.workload,) if args.workload in ("c2", "c3") else ("c2", "c3")
+        print(json.dumps({"decode_step": decode_steps(torch, E, W, iters=args.extra_iters, shapes=shapes)}))
+        return
 
     name = args.workload
     copies = 1 if name == "c5" else 3

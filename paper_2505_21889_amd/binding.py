@@ -286,6 +286,11 @@ class HipEvent:
         if rc != 0:
             raise RuntimeError("hipEventSynchronize failed: %d" % rc)
 
+    def __del__(self):
+        if getattr(self, "handle", None) and self.handle.value and self._hip is not None:
+            self._hip.hipEventDestroy(self.handle)
+            self.handle = ctypes.c_void_p()
+
     def elapsed_ms(self, end):
         ms = ctypes.c_float()
         rc = self._rt().hipEventElapsedTime(ctypes.byref(ms), self.handle, end.handle)
