@@ -2,17 +2,19 @@
 // prefix+suffix pages plus themselves (EFIM Sec. 1: only the incremental part is computed,
 // the rest of the reordered prompt is read from the KV cache).
 //
-// One workgroup (4 wavefronts) handles one work item: a tile of query rows of one
-// (request, kv head) against a range of keys.  Rows are (token, head-in-group) pairs so all
-// query heads that share a kv head read its K/V once.  Per 64-key tile:
+// One workgroup (4 or 8 wavefronts, 32 query rows each) handles one work item: a tile of
+// query rows of one (request, kv head) against a range of keys.  Rows are (token,
+// head-in-group) pairs so all query heads that share a kv head read its K/V once.  Per
+// 64-key tile:
 //   * the four 16-token pages are gathered through the block table straight from HBM into
-//     LDS (16 bytes per lane, 1 KB per wave instruction, XOR-swizzled 16-byte chunks),
-//     double buffered, the next tile in flight while the current one is consumed;
+//     LDS (16 bytes per lane, 1 KB per wave instruction, XOR-swizzled 16-byte chunks), one or
+//     two tiles ahead of the one being consumed;
 //   * S^T = K Q^T with 32x32x16 bf16 MFMA: every lane ends up with 32 scores of ONE query
 //     row, so the running max / sum are per-lane scalars plus one cross-half exchange;
 //   * P is rounded to bf16 in registers and is directly the B operand of O^T += V^T P^T;
 //     V^T operands come from the row-major V tile through the transposing LDS read.
-// Accumulation is fp32; partial results of split key ranges are merged by a second kernel.
+// Accumulation is fp32; partial results of split key ranges are merged by a second kernel or,
+// for the decode step, by the workgroup that finishes last.
 #include "efim_internal.h"
 #include "rope_math.h"
 

@@ -112,6 +112,27 @@ def test_decode_merge_across_compute_dies(E):
         E.efim_set_tuning(E.EFIM_TUNE_SPLIT_KV, -1)
 
 
+def test_decode_step_with_the_merge_in_a_second_launch(E):
+    """The decode step also works when the parts of a split key range are combined by the
+    separate merge kernel (the path taken when a launch has more split tiles than arrival
+    counters): same bits as the in-kernel merge."""
+    c = np.array([2500, 700, 4100], dtype=np.int32)
+    b = W.make_batch("c1", seed=61, lengths=(c, np.ones_like(c)), heads=(8, 2), head_dim=128)
+    kc, vc = U.oracle_cache(b)
+    _, kc_ref, vc_ref, ref = oracle_step(b, kc, vc)
+    E.efim_set_tuning(E.EFIM_TUNE_SPLIT_KV, 512)
+    try:
+        in_kernel, _, _, _ = run_decode(E, b, kc, vc)
+        E.efim_set_tuning(E.EFIM_TUNE_FUSED_MERGE, 0)
+        second_launch, kc_got, vc_got, _ = run_decode(E, b, kc, vc)
+    finally:
+        E.efim_set_tuning(E.EFIM_TUNE_SPLIT_KV, -1)
+        E.efim_set_tuning(E.EFIM_TUNE_FUSED_MERGE, -1)
+    assert np.array_equal(kc_got, kc_ref) and np.array_equal(vc_got, vc_ref)
+    U.assert_close(second_launch, ref, "second launch")
+    assert np.array_equal(in_kernel, second_launch)
+
+
 def test_decode_sequence_grows_the_cache_token_by_token(E):
     """Eight consecutive decode steps of three requests: the caches after the last step and
     every step's output equal the oracle's, which appends token by token too."""
