@@ -136,10 +136,21 @@ void build_plan(const efim_batch_t* b, int num_slots, Plan* plan) {
     if ((double)max_cost > 1.3 * avg) {
       chunk = (int64_t)std::max(4.0, avg);
       if (tiles.size() <= (size_t)4 * num_slots) {
-        // Model of the device: pieces handed out longest first, each to the slot that is free
-        // first; the step takes as long as the fullest slot.  (A finer model, in which few
-        // busy slots run faster than many because they share the memory bandwidth, was fitted
-        // to chunk sweeps on the device and picked worse plans than this one.)
+        // Quick estimate of a candidate: the pieces run in rounds of `num_slots`, a round
+        // lasts as long as the longest piece.  The most promising candidates are then played
+        // through: pieces handed out longest first, each to the slot that is free first, the
+        // step taking as long as the fullest slot.  (A finer model with bandwidth sharing
+        // between busy slots was fitted to chunk sweeps on the device and picked worse plans.)
+        auto estimate = [&](int64_t c) {
+          int64_t pieces = 0, longest = 0;
+          for (const Tile& t : tiles) {
+            const int n = pieces_of(t, c);
+            pieces += n;
+            longest = std::max<int64_t>(longest, (t.ktiles + n - 1) / n);
+          }
+          const int64_t rounds = (pieces + num_slots - 1) / num_slots;
+          return rounds * (longest + kStartCost);
+        };
         std::vector<int64_t> costs, load;
         auto makespan = [&](int64_t c) {
           costs.clear();
@@ -161,9 +172,13 @@ void build_plan(const efim_batch_t* b, int num_slots, Plan* plan) {
         };
         const int64_t lo = std::max<int64_t>(4, (int64_t)(0.5 * avg));
         const int64_t hi = std::max<int64_t>(lo, max_cost - kStartCost);
-        const int64_t step = std::max<int64_t>(1, (hi - lo) / 48);
+        const int64_t step = std::max<int64_t>(1, (hi - lo) / 64);
+        std::vector<std::pair<int64_t, int64_t>> ranked;  // (estimate, candidate)
+        for (int64_t c = lo; c <= hi; c += step) ranked.push_back({estimate(c), c});
+        std::sort(ranked.begin(), ranked.end());
         int64_t best = makespan(chunk), best_chunk = chunk;
-        for (int64_t c = lo; c <= hi; c += step) {
+        for (size_t i = 0; i < ranked.size() && i < 6; ++i) {
+          const int64_t c = ranked[i].second;
           const int64_t m = makespan(c);
           if (m < best || (m == best && c > best_chunk)) { best = m; best_chunk = c; }
         }
