@@ -115,8 +115,9 @@ int efim_rope_append_table(const efim_batch_t* batch, void* q, const void* k_new
 
 /*
  * efim_extend_workspace_bytes -- device workspace efim_extend_attention needs for this
- * batch (work list plus split-KV partial results).  Pure host function; returns 0 for an
- * invalid batch.  The size depends only on the host fields of `batch`.
+ * batch (the partial results of split key ranges; at least 256).  Pure host function;
+ * returns 0 for an invalid batch.  The size depends only on the host fields of `batch`
+ * and on the tuning knobs in force.
  */
 size_t efim_extend_workspace_bytes(const efim_batch_t* batch);
 
