@@ -205,8 +205,7 @@ int efim_version(void);        /* major * 10000 + minor * 100 + patch */
  * workspace: DEVICE, 256-byte aligned, at least efim_decode_workspace_bytes(batch) bytes,
  * contents irrelevant (as for efim_extend_attention).
  * Errors: as efim_extend_attention / efim_rope_append; EFIM_ERR_UNSUPPORTED if some
- * new_len[r] != 1, if there are more than 32 query heads per kv head, or if the planner was
- * forced to 256-row tiles (EFIM_TUNE_ROW_TILE).
+ * new_len[r] != 1 or if there are more than 32 query heads per kv head.
  * efim_decode_workspace_bytes returns 0 for a batch efim_decode_step would reject.
  * ------------------------------------------------------------------------------------- */
 size_t efim_decode_workspace_bytes(const efim_batch_t* batch);

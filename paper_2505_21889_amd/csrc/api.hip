@@ -255,7 +255,6 @@ int efim_decode_step(const efim_batch_t* batch, const void* q, const void* k_new
     return EFIM_ERR_INVALID_ARG;
   std::lock_guard<std::mutex> lock(g_plan_mutex);
   const Plan& plan = cached_plan(batch);
-  if (plan.rows_per_item != 128) return EFIM_ERR_UNSUPPORTED;
   if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) || workspace_bytes < plan.total_bytes)
     return EFIM_ERR_WORKSPACE;
   if (sm_scale == 0.f) sm_scale = 1.0f / sqrtf((float)batch->head_dim);

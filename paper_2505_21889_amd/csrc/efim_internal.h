@@ -66,7 +66,7 @@ struct Plan {
 // Validates the host-visible part of a batch. total_new receives T.
 int validate_batch(const efim_batch_t* b, int64_t* total_new);
 
-// Builds the work list. num_slots = number of workgroups the device runs concurrently.
+// Builds the work list. num_slots = number of 4-wave workgroups the device runs concurrently.
 void build_plan(const efim_batch_t* b, int num_slots, Plan* plan);
 
 // inv_freq: rotary_dim/2 host values; the leading rotary_dim elements of every head row rotate.

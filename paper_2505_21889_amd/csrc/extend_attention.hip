@@ -724,8 +724,14 @@ int launch_decode_step(const efim_batch_t* b, const Plan& plan, const char* head
   const dim3 grid((unsigned)plan.items.size());
   const Tuning& tn = tuning();
   if (tn.ev_start) (void)hipEventRecord(tn.ev_start, stream);
-  if (D == 128) extend_attention_kernel<128, 4, 2, true><<<grid, 256, 0, stream>>>(p);
-  else extend_attention_kernel<64, 4, 2, true><<<grid, 256, 0, stream>>>(p);
+  const bool wide = plan.rows_per_item == 256;
+  if (D == 128) {
+    if (wide) extend_attention_kernel<128, 8, 3, true><<<grid, 512, 0, stream>>>(p);
+    else extend_attention_kernel<128, 4, 2, true><<<grid, 256, 0, stream>>>(p);
+  } else {
+    if (wide) extend_attention_kernel<64, 8, 3, true><<<grid, 512, 0, stream>>>(p);
+    else extend_attention_kernel<64, 4, 2, true><<<grid, 256, 0, stream>>>(p);
+  }
   hipError_t e = hipGetLastError();
   if (tn.ev_stop) (void)hipEventRecord(tn.ev_stop, stream);
   if (e != hipSuccess) { set_last_hip_error(e); return EFIM_ERR_LAUNCH; }

@@ -88,8 +88,18 @@ void build_plan(const efim_batch_t* b, int num_slots, Plan* plan) {
     flops += 4.0 * D * b->num_q_heads * n * (c + 0.5 * (n + 1));
     bytes += 4.0 * D * ((c + n) * b->num_kv_heads + n * b->num_q_heads);
   }
+  // A step bound by HBM also takes the 256-row configuration when it has at least two such
+  // tiles per compute unit: the tiles then balance over the 256 slots without cutting key
+  // ranges (no merge pass), and that configuration gathers two tiles ahead.
   int M = 128;
-  if (tn0.row_tile == 256 || (tn0.row_tile == 0 && max_rows > 128 && flops > 315.0 * bytes)) M = 256;
+  if (tn0.row_tile == 256) {
+    M = 256;
+  } else if (tn0.row_tile == 0) {
+    int64_t wide_tiles = 0;
+    for (int r = 0; r < b->batch; ++r)
+      wide_tiles += (int64_t)b->num_kv_heads * (((int64_t)g * b->new_len[r] + 255) / 256);
+    if ((max_rows > 128 && flops > 315.0 * bytes) || wide_tiles >= num_slots) M = 256;
+  }
   plan->rows_per_item = M;
   if (M == 256) num_slots = std::max(1, num_slots / 2);  // 8-wave workgroups: one per compute unit
 

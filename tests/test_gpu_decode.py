@@ -91,6 +91,25 @@ def test_decode_step_matches_oracle_and_two_call_path(E, name, cached, heads, d,
         E.efim_set_tuning(E.EFIM_TUNE_SPLIT_KV, -1)
 
 
+@pytest.mark.parametrize("name,cached,heads,d,interleaved", [CASES[0], CASES[3]])
+def test_decode_step_in_the_eight_wave_configuration(E, name, cached, heads, d, interleaved):
+    """The 256-row launch configuration (chosen by the planner for large batches; forced here)."""
+    E.efim_set_tuning(E.EFIM_TUNE_ROW_TILE, 256)
+    E.efim_set_tuning(E.EFIM_TUNE_SPLIT_KV, 128)
+    try:
+        c = np.array(cached, dtype=np.int32)
+        b = W.make_batch("c1", seed=70 + len(cached), lengths=(c, np.ones_like(c)), heads=heads, head_dim=d)
+        kc, vc = U.oracle_cache(b)
+        _, kc_ref, vc_ref, ref = oracle_step(b, kc, vc, bool(interleaved))
+        got, kc_got, vc_got, _ = run_decode(E, b, kc, vc, interleaved)
+        assert np.array_equal(kc_got, kc_ref) and np.array_equal(vc_got, vc_ref)
+        U.assert_close(got, ref, name)
+        assert np.array_equal(got, two_call_path(E, b, kc, vc, interleaved))
+    finally:
+        E.efim_set_tuning(E.EFIM_TUNE_ROW_TILE, 0)
+        E.efim_set_tuning(E.EFIM_TUNE_SPLIT_KV, -1)
+
+
 def test_decode_merge_across_compute_dies(E):
     """With the planner's XCD grouping off the parts of a split key range land on different
     dies: the merging workgroup must still see every partial result."""

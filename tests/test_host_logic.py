@@ -203,6 +203,23 @@ def test_xcd_grouping_places_tiles_sharing_kv_on_one_residue_class():
     assert max(per_xcd) - min(per_xcd) <= 1
 
 
+def test_row_tile_choice():
+    """128-row tiles by default; 256-row tiles for compute-heavy steps and for steps bound by
+    HBM that have at least two such tiles per compute unit."""
+    E.efim_set_tuning(E.EFIM_TUNE_NUM_SLOTS, 512)
+    try:
+        def rows_per_item(c, n, hq, hkv):
+            items = E.efim_extend_plan_items(_desc(c, n, hq=hq, hkv=hkv, d=128))
+            _check_plan(np.asarray(c), np.asarray(n), hq, hkv, items)
+            return 256 if items["row_count"].max() > 128 else 128
+        assert rows_per_item([16384] * 4, [512] * 4, 32, 8) == 256           # compute heavy
+        assert rows_per_item([4000] * 32, [16] * 32, 28, 4) == 128            # 128 pairs: HBM bound, few tiles
+        many = E.efim_extend_plan_items(_desc([3000] * 16, [1] * 16, hq=32, hkv=32, d=128))
+        assert len(many[many["row_count"] > 0]) == 512 and (many["partial_slot"] < 0).all()   # 512 pairs: one item each, no split
+    finally:
+        E.efim_set_tuning(E.EFIM_TUNE_NUM_SLOTS, 0)
+
+
 def test_split_policy_packs_the_pieces_into_the_slots():
     """Automatic split of a step with fewer (request, kv head) pairs than workgroup slots: the
     pieces fit the slots in one round (one piece too many would cost an extra round with most
