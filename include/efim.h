@@ -46,7 +46,7 @@ extern "C" {
 typedef enum efim_status {
   EFIM_OK = 0,
   EFIM_ERR_INVALID_ARG = -1, /* NULL pointer, negative size, misaligned pointer, Hq % Hkv != 0 ... */
-  EFIM_ERR_UNSUPPORTED = -2, /* head_dim not in {64,128}, page_size != 16, batch too large       */
+  EFIM_ERR_UNSUPPORTED = -2, /* head_dim not in {64,128}, page_size not a power of two in [8,256], batch too large */
   EFIM_ERR_WORKSPACE = -3,   /* workspace NULL/misaligned or smaller than efim_extend_workspace_bytes */
   EFIM_ERR_LAUNCH = -4       /* a HIP call failed; efim_last_hip_error() holds its hipError_t     */
 } efim_status_t;
@@ -67,7 +67,7 @@ typedef struct efim_batch {
   int32_t num_q_heads;       /* Hq, a multiple of num_kv_heads                           */
   int32_t num_kv_heads;      /* Hkv >= 1                                                 */
   int32_t head_dim;          /* D: 64 or 128                                             */
-  int32_t page_size;         /* P: 16                                                    */
+  int32_t page_size;         /* P: a power of two, 8 <= P <= 256 (16 in the paper's engine)  */
   int32_t max_pages_per_req; /* row stride of block_table                                */
   int64_t num_pages;         /* pages in each of k_cache and v_cache                     */
   const int32_t* cached_len; /* HOST  [B]  C_r >= 0                                      */

@@ -10,8 +10,9 @@
 
 namespace efim {
 
-constexpr int kPageSize = 16;         // tokens per KV page
-constexpr int kKeyTile = 64;          // keys staged in LDS per main-loop iteration (4 pages)
+constexpr int kMinPageSize = 8;       // tokens per KV page: a power of two in this range
+constexpr int kMaxPageSize = 256;
+constexpr int kKeyTile = 64;          // keys staged in LDS per main-loop iteration
 constexpr int kWavesPerGroup = 4;     // wavefronts per attention workgroup
 constexpr int kMaxRowsPerItem = 256;  // largest query-row tile of one workgroup
 constexpr int kStageSlots = 8;        // work lists (= launches) that can be in flight at once

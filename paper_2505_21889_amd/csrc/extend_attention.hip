@@ -61,6 +61,7 @@ struct AttnParams {
   const MergeItem* merges;
   int32_t ticket_base;    // first arrival counter of this launch in g_tickets, or -1: the split
                           // key ranges are combined by merge_kernel in a second launch
+  int32_t page_shift;     // log2 of the page size (tokens per page)
   int32_t interleaved;    // rotary pairing
   double inv_freq[64];    // base^(-2j/D)
 };
@@ -271,25 +272,29 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
   const int k_end = it.key_end;
   const int ntiles = (k_end - k_begin + kKeyTile - 1) / kKeyTile;
   const int32_t* bt = p.block_table + (int64_t)it.req * p.max_pages;
-  const int last_page = (k_end - 1) / kPageSize;
+  const int ps = p.page_shift;
+  const int page_mask = (1 << ps) - 1;
+  const int last_page = (k_end - 1) >> ps;
 
-  // Block-table entries are fetched 64 pages (16 tiles) at a time: lane l holds the page id
-  // of page (chunk start + l); the wave-uniform page id of a load is then a cross-lane read
-  // instead of a dependent memory load in front of every gather.
-  constexpr int kPagesPerTile = kKeyTile / kPageSize;
-  constexpr int kTilesPerChunk = 64 / kPagesPerTile;
-  const int first_page = k_begin / kPageSize;
-  auto load_pages = [&](int tile0) { return bt[min(first_page + tile0 * kPagesPerTile + lane, last_page)]; };
-  int pages_tile0 = 0;
+  // Block-table entries are fetched 64 pages (a "chunk") at a time: lane l holds the page id
+  // of page (first page of the key range + 64 * chunk + l); the wave-uniform page id of a load
+  // is then a cross-lane read instead of a dependent memory load in front of every gather.
+  // A tile never straddles two chunks: pages of up to 64 tokens tile the 64-key tiles evenly,
+  // larger pages hold whole tiles.
+  const int first_page = k_begin >> ps;
+  const int first_off = k_begin & page_mask;  // nonzero only for pages larger than a tile
+  auto load_pages = [&](int chunk) { return bt[min(first_page + chunk * 64 + lane, last_page)]; };
+  const int last_chunk = (last_page - first_page) >> 6;
+  int pages_chunk = 0;
   int pages_cur = load_pages(0);
-  int pages_next = ntiles > kTilesPerChunk ? load_pages(kTilesPerChunk) : 0;
-  const int64_t page_bytes = (int64_t)p.num_kv_heads * kPageSize * G::kRowBytes;
-  const int64_t head_bytes = (int64_t)it.kv_head * kPageSize * G::kRowBytes;
+  int pages_next = last_chunk > 0 ? load_pages(1) : 0;
+  const int64_t page_bytes = ((int64_t)p.num_kv_heads * G::kRowBytes) << ps;
+  const int64_t head_bytes = ((int64_t)it.kv_head * G::kRowBytes) << ps;
   // Rows of a tile past the end of the key range are fetched from the last key of the range
   // instead: every tile then issues the same number of loads, pages that may not exist are
   // never touched, and LDS only ever holds finite data (the scores of those rows are masked).
   const int64_t last_off =
-      (int64_t)bt[last_page] * page_bytes + head_bytes + ((k_end - 1) % kPageSize) * G::kRowBytes;
+      (int64_t)bt[last_page] * page_bytes + head_bytes + ((k_end - 1) & page_mask) * G::kRowBytes;
   // Everything loaded so far (Q operands, page ids) must have landed before the main loop:
   // inside it the only outstanding vector-memory operations are the gathers, which are
   // awaited by hand.  (vmcnt(0), expcnt/lgkmcnt untouched)
@@ -302,11 +307,12 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
   const int g_pc = lane % G::kChunks;   // physical 16-byte chunk this lane fills
   auto issue_tile = [&](int t, char* kbuf, char* vbuf) {
     const int key0 = k_begin + t * kKeyTile;
-    if (t - pages_tile0 == kTilesPerChunk) {
+    const int tile_page = (first_off + t * kKeyTile) >> ps;  // first page of the tile, relative to first_page
+    if ((tile_page >> 6) != pages_chunk) {
       // called right after the loop-top wait, so pages_next has arrived
       pages_cur = pages_next;
-      pages_tile0 = t;
-      if (t + kTilesPerChunk < ntiles) pages_next = load_pages(t + kTilesPerChunk);
+      pages_chunk = tile_page >> 6;
+      if (pages_chunk < last_chunk) pages_next = load_pages(pages_chunk + 1);
     }
     const char* kc = reinterpret_cast<const char*>(p.k_cache);
     const char* vc = reinterpret_cast<const char*>(p.v_cache);
@@ -318,8 +324,8 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
       const int row0 = idx * G::kKeysPerLoad;                  // first tile row of this load
       const int tile_row = row0 + g_key;
       const int64_t page =
-          __builtin_amdgcn_readlane(pages_cur, (t - pages_tile0) * kPagesPerTile + row0 / kPageSize);
-      const int64_t in_off = page * page_bytes + head_bytes + (tile_row % kPageSize) * G::kRowBytes;
+          __builtin_amdgcn_readlane(pages_cur, ((first_off + t * kKeyTile + row0) >> ps) & 63);
+      const int64_t in_off = page * page_bytes + head_bytes + ((key0 + tile_row) & page_mask) * G::kRowBytes;
       const int64_t row_off = (key0 + tile_row < k_end) ? in_off : last_off;
       const int swz = is_v ? G::vswz(tile_row) : G::kswz(tile_row);
       const char* src = (is_v ? vc : kc) + row_off + ((g_pc ^ swz) << 4);
@@ -535,9 +541,9 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
               char* tile = lds + s0 * kStageBytes + (is_v ? G::kTileBytes : 0);
               *reinterpret_cast<u32x4*>(tile + row * G::kRowBytes + ((c ^ swz) << 4)) = val;
               if (row == prow) {
-                const int64_t page = bt[pos / kPageSize];
+                const int64_t page = bt[pos >> ps];
                 uint16_t* cache = is_v ? p.v_cache_w : p.k_cache_w;
-                *reinterpret_cast<u32x4*>(cache + ((page * p.num_kv_heads + it.kv_head) * kPageSize + pos % kPageSize) * D + c * 8) = val;
+                *reinterpret_cast<u32x4*>(cache + ((((page * p.num_kv_heads + it.kv_head) << ps) + (pos & page_mask)) * D + c * 8)) = val;
               }
             }
             __syncthreads();
@@ -652,6 +658,8 @@ void fill_params(AttnParams* p, const efim_batch_t* b, const Plan& plan, const c
   p->v_cache_w = nullptr;
   p->ticket_base = -1;
   p->merges = reinterpret_cast<const MergeItem*>(header + plan.off_merges);
+  p->page_shift = 0;
+  while ((1 << p->page_shift) < b->page_size) ++p->page_shift;
   p->interleaved = 0;
   for (double& f : p->inv_freq) f = 0.0;
 }

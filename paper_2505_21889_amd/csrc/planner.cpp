@@ -26,7 +26,9 @@ int validate_batch(const efim_batch_t* b, int64_t* total_new) {
     return EFIM_ERR_INVALID_ARG;
   if (b->num_q_heads % b->num_kv_heads != 0) return EFIM_ERR_INVALID_ARG;
   if (b->head_dim != 64 && b->head_dim != 128) return EFIM_ERR_UNSUPPORTED;
-  if (b->page_size != kPageSize) return EFIM_ERR_UNSUPPORTED;
+  // pages are powers of two; a 1 KB gather (4 or 8 tokens of one head) must not cross one
+  if (b->page_size < kMinPageSize || b->page_size > kMaxPageSize || (b->page_size & (b->page_size - 1)) != 0)
+    return EFIM_ERR_UNSUPPORTED;
   if (b->num_q_heads / b->num_kv_heads > 64) return EFIM_ERR_UNSUPPORTED;
   int64_t total = 0;
   if (b->batch > 0) {

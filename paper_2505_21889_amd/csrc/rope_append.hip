@@ -27,6 +27,7 @@ struct RopeArgs {
   int32_t num_kv_heads;
   int32_t rotate_q;                         // 0 when q is NULL
   int32_t rotary_dim;                       // leading elements of a head row that are rotated
+  int32_t page_shift;                       // log2 of the page size (tokens per page)
 };
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -68,8 +69,8 @@ __global__ __launch_bounds__(kThreads) void rope_append_kernel(
       s_sin[tt][j] = s;
       if (j == 0) {
         const int64_t page =
-            block_table[(int64_t)(args.req_base + lo) * args.max_pages + (pos / kPageSize)];
-        s_dst[tt] = (page * args.num_kv_heads * kPageSize + (pos % kPageSize)) * D;
+            block_table[(int64_t)(args.req_base + lo) * args.max_pages + (pos >> args.page_shift)];
+        s_dst[tt] = (((page * args.num_kv_heads) << args.page_shift) + (pos & ((1 << args.page_shift) - 1))) * D;
       }
     }
   }
@@ -104,11 +105,11 @@ __global__ __launch_bounds__(kThreads) void rope_append_kernel(
     } else if (hr < hq + hkv) {
       const int h = hr - hq;
       src = k_new + (row * hkv + h) * D;
-      dst = k_cache + s_dst[tt] + (int64_t)h * kPageSize * D;
+      dst = k_cache + s_dst[tt] + (((int64_t)h * D) << args.page_shift);
     } else {
       const int h = hr - hq - hkv;
       src = v_new + (row * hkv + h) * D;
-      dst = v_cache + s_dst[tt] + (int64_t)h * kPageSize * D;
+      dst = v_cache + s_dst[tt] + (((int64_t)h * D) << args.page_shift);
       rotate = false;
     }
     u32x4 a = *reinterpret_cast<const u32x4*>(src + e0);
@@ -164,6 +165,8 @@ int launch_rope_append(const efim_batch_t* b, int64_t total_new, void* q, const 
   for (int j = 0; j < 64; ++j) args.inv_freq[j] = 0.0;
   for (int j = 0; j < rotary_dim / 2; ++j) args.inv_freq[j] = inv_freq[j];
   args.rotary_dim = rotary_dim;
+  args.page_shift = 0;
+  while ((1 << args.page_shift) < b->page_size) ++args.page_shift;
   args.max_pages = b->max_pages_per_req;
   args.num_q_heads = b->num_q_heads;
   args.num_kv_heads = b->num_kv_heads;

@@ -110,6 +110,23 @@ def test_decode_step_in_the_eight_wave_configuration(E, name, cached, heads, d, 
         E.efim_set_tuning(E.EFIM_TUNE_SPLIT_KV, -1)
 
 
+@pytest.mark.parametrize("page_size", [8, 64, 256])
+def test_decode_step_other_page_sizes(E, page_size):
+    c = np.array([0, 7, 8, 63, 64, 255, 256, 1000, 2049], dtype=np.int32)
+    b = W.make_batch("c1", seed=40 + page_size, lengths=(c, np.ones_like(c)), heads=(8, 2), head_dim=128,
+                     page_size=page_size)
+    kc, vc = U.oracle_cache(b)
+    _, kc_ref, vc_ref, ref = oracle_step(b, kc, vc)
+    for split in (-1, 64):
+        E.efim_set_tuning(E.EFIM_TUNE_SPLIT_KV, split)
+        try:
+            got, kc_got, vc_got, _ = run_decode(E, b, kc, vc)
+        finally:
+            E.efim_set_tuning(E.EFIM_TUNE_SPLIT_KV, -1)
+        assert np.array_equal(kc_got, kc_ref) and np.array_equal(vc_got, vc_ref)
+        U.assert_close(got, ref, "page %d split %d" % (page_size, split))
+
+
 def test_decode_merge_across_compute_dies(E):
     """With the planner's XCD grouping off the parts of a split key range land on different
     dies: the merging workgroup must still see every partial result."""

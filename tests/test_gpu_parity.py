@@ -244,3 +244,31 @@ def test_rope_append_table_bit_exact(E, d, rotary_dim, interleaved):
     assert np.array_equal(U.host_bits(vcd), vc_ref)
     if rotary_dim < d:   # the tail of every head row is the input, untouched
         assert np.array_equal(U.host_bits(q)[..., rotary_dim:], b.q_new[..., rotary_dim:])
+
+
+@pytest.mark.parametrize("page_size", [8, 32, 64, 128, 256])
+def test_other_page_sizes(E, page_size):
+    """Pages of 8 to 256 tokens (a power of two): append bit-exact, attention within the bar, with
+    and without cut key ranges, and the decode step on top of the resulting cache."""
+    b = _ragged(300 + page_size, [0, 5, 700, 129, 2000], [200, 1, 33, 64, 7], heads=(8, 2), head_dim=128,
+                page_size=page_size)
+    assert b.page_size == page_size
+    kc, vc = U.oracle_cache(b, fill=0xABCD)
+    kc_ref, vc_ref = kc.copy(), vc.copy()
+    q_ref, _ = O.rope_append(b.cached_len, b.new_len, b.block_table, b.page_size, b.q_new, b.k_new, b.v_new,
+                             kc_ref, vc_ref, b.rope_base)
+    q_gpu, kc_gpu, vc_gpu = U.gpu_rope_append(E, b, kc, vc)
+    assert np.array_equal(q_gpu, q_ref) and np.array_equal(kc_gpu, kc_ref) and np.array_equal(vc_gpu, vc_ref)
+    kc_p, vc_p = U.oracle_cache(b)          # poisoned outside the requests
+    q_ref, _ = O.rope_append(b.cached_len, b.new_len, b.block_table, b.page_size, b.q_new, b.k_new, b.v_new,
+                             kc_p, vc_p, b.rope_base)
+    ref = O.extend_attention(b.cached_len, b.new_len, b.block_table, b.page_size, q_ref, kc_p, vc_p)
+    for split in (-1, 128):
+        E.efim_set_tuning(E.EFIM_TUNE_SPLIT_KV, split)
+        try:
+            got = U.gpu_extend_attention(E, b, q_ref, kc_p, vc_p)
+        finally:
+            E.efim_set_tuning(E.EFIM_TUNE_SPLIT_KV, -1)
+        # (requests with a handful of keys give outputs of magnitude 2-4, whose bf16 rounding
+        # alone is up to 7.8e-3: the absolute bound is taken relative to the largest output)
+        U.assert_close(got, ref, "page %d split %d" % (page_size, split), scale_abs_with_output=True)

@@ -50,7 +50,8 @@ def _attn_status(desc, q=FAKE_DEV, kc=FAKE_DEV + 0x100000, vc=FAKE_DEV + 0x20000
 def test_argument_validation_without_a_device():
     ok = _desc([10], [5])
     assert _rope_status(_desc([10], [5], d=96)) == E.EFIM_ERR_UNSUPPORTED
-    assert _rope_status(_desc([10], [5], page=32)) == E.EFIM_ERR_UNSUPPORTED
+    for bad_page in (4, 24, 512):
+        assert _rope_status(_desc([10], [5], page=bad_page, max_pages=8, num_pages=8)) == E.EFIM_ERR_UNSUPPORTED
     assert _rope_status(_desc([10], [5], hq=5, hkv=2)) == E.EFIM_ERR_INVALID_ARG
     assert _rope_status(_desc([-1], [5])) == E.EFIM_ERR_INVALID_ARG
     assert _rope_status(_desc([10], [-5])) == E.EFIM_ERR_INVALID_ARG
