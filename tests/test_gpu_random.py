@@ -1,6 +1,6 @@
 """Seeded random batches through the whole path (efim_rope_append then efim_extend_attention)
 against the oracle: ragged lengths with zeros, cached lengths on and around page and tile
-boundaries, every supported head layout, random planner knobs.  Caches start poisoned, so a
+boundaries, every supported head layout and page size, random planner knobs.  Caches start poisoned, so a
 read of any slot that is not part of a request shows up as NaN."""
 import numpy as np
 import pytest
@@ -45,7 +45,8 @@ def test_random_batch(E, seed):
     rng = np.random.default_rng(9000 + seed)
     cached, new, heads, d, knobs = draw_case(rng)
     b = W.make_batch("c1", seed=500 + seed, lengths=(np.array(cached, dtype=np.int32), np.array(new, dtype=np.int32)),
-                     heads=heads, head_dim=d, sigma=float(rng.choice([0.5, 1.0, 2.0])))
+                     heads=heads, head_dim=d, sigma=float(rng.choice([0.5, 1.0, 2.0])),
+                     page_size=int(rng.choice([8, 16, 16, 32, 64, 128, 256])))
     kc, vc = U.oracle_cache(b)
     kc_ref, vc_ref = kc.copy(), vc.copy()
     inter = bool(knobs["interleaved"])
@@ -83,7 +84,8 @@ def test_random_decode_step(E, seed):
     heads = HEADS[int(rng.integers(len(HEADS)))]
     d = int(rng.choice([64, 128]))
     inter = int(rng.integers(0, 2))
-    b = W.make_batch("c1", seed=800 + seed, lengths=(cached, np.ones_like(cached)), heads=heads, head_dim=d)
+    b = W.make_batch("c1", seed=800 + seed, lengths=(cached, np.ones_like(cached)), heads=heads, head_dim=d,
+                     page_size=int(rng.choice([8, 16, 16, 32, 128])))
     kc, vc = U.oracle_cache(b)
     kc_ref, vc_ref = kc.copy(), vc.copy()
     q_ref, _ = O.rope_append(b.cached_len, b.new_len, b.block_table, b.page_size, b.q_new, b.k_new, b.v_new,
