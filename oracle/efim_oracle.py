@@ -234,20 +234,23 @@ def rope_append_table(cached_len, new_len, block_table, page_size, q_new, k_new,
 
 
 def gather_kv(cache, block_table_row, length, page_size, kv_head):
-    """Logical rows 0..length-1 of one request and kv head, as bf16 bits [length, D]."""
+    """Logical rows 0..length-1 of one request and kv head, as stored (bf16 bits) [length, D]."""
     pos = np.arange(length)
     pages = np.asarray(block_table_row)[pos // page_size]
     return cache[pages, kv_head, pos % page_size]
 
 
 def extend_attention_rows(r, q_head, cached_len, new_len, block_table, page_size,
-                          q_roped, k_cache, v_cache, sm_scale=None, rows=None):
+                          q_roped, k_cache, v_cache, sm_scale=None, rows=None,
+                          k_values=bf16_to_f64, v_values=bf16_to_f64):
     """Attention output (fp64, [len(rows), D]) of request r, query head q_head.
 
     New row i sees keys 0 .. C_r + i (causal, itself included):
         s_j = sm_scale * <q_i, k_j>,  p = softmax(s),  o = sum_j p_j v_j.
     Query head a reads kv head a // (Hq / Hkv).
     Readings: scale 1/sqrt(D) unless given; no soft-cap, window or bias.
+    k_values / v_values turn stored cache entries into their fp64 values (bf16 bit patterns
+    unless the cache holds another number format).
     """
     c, n = int(cached_len[r]), int(new_len[r])
     num_q_heads, head_dim = q_roped.shape[1], q_roped.shape[2]
@@ -260,8 +263,8 @@ def extend_attention_rows(r, q_head, cached_len, new_len, block_table, page_size
     rows = np.asarray(list(rows), dtype=np.int64)
     start = int(np.sum(np.asarray(new_len[:r], dtype=np.int64)))
     length = c + n
-    k = bf16_to_f64(gather_kv(k_cache, block_table[r], length, page_size, kv_head))
-    v = bf16_to_f64(gather_kv(v_cache, block_table[r], length, page_size, kv_head))
+    k = k_values(gather_kv(k_cache, block_table[r], length, page_size, kv_head))
+    v = v_values(gather_kv(v_cache, block_table[r], length, page_size, kv_head))
     q = bf16_to_f64(q_roped[start + rows, q_head, :])
     s = sm_scale * (q @ k.T)
     visible = np.arange(length)[None, :] <= (c + rows)[:, None]
