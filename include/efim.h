@@ -214,6 +214,36 @@ int efim_decode_step(const efim_batch_t* batch, const void* q, const void* k_new
                      float sm_scale, void* workspace, size_t workspace_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------------------
+ * 8-bit KV cache.  The paper serves unmodified models on a stock engine (Sec. 4.2) and does
+ * not discuss the cache's number format; these three calls are the calls above for the common
+ * engine option of a cache held in 8-bit floating point, which halves the bytes the cache-hit
+ * attention reads.
+ *
+ * Format: OCP FP8 E4M3 (1 sign, 4 exponent bits with bias 7, 3 mantissa bits, no infinities,
+ * largest finite value 448), one byte per element, same [num_pages, Hkv, P, D] layout, one
+ * scale per tensor:  value = code_value * scale.
+ *   k_cache, v_cache  DEVICE  uint8 [num_pages, Hkv, P, D]
+ *   k_scale, v_scale  finite, > 0
+ * Append: what the bf16 call would have stored (the rotated key after its rounding to bf16,
+ * the value as given) is divided by the scale in binary32 and rounded to the nearest code,
+ * ties to the even code, magnitudes of 448 and above saturating to +-448.  q is rotated in
+ * place exactly as by efim_rope_append.
+ * Attention: as efim_extend_attention with code_value * scale in place of the bf16 cache
+ * entries; q and out stay bf16.  Workspace as for the bf16 calls (same size queries).
+ * Errors: as the bf16 calls; EFIM_ERR_INVALID_ARG for a scale that is not finite and positive.
+ * ------------------------------------------------------------------------------------- */
+int efim_rope_append_fp8(const efim_batch_t* batch, void* q, const void* k_new, const void* v_new,
+                         void* k_cache, void* v_cache, double rope_base, int rope_interleaved,
+                         float k_scale, float v_scale, void* stream);
+int efim_extend_attention_fp8(const efim_batch_t* batch, const void* q, const void* k_cache,
+                              const void* v_cache, void* out, float sm_scale, float k_scale, float v_scale,
+                              void* workspace, size_t workspace_bytes, void* stream);
+int efim_decode_step_fp8(const efim_batch_t* batch, const void* q, const void* k_new, const void* v_new,
+                         void* k_cache, void* v_cache, void* out, double rope_base, int rope_interleaved,
+                         float sm_scale, float k_scale, float v_scale, void* workspace, size_t workspace_bytes,
+                         void* stream);
+
+/* ---------------------------------------------------------------------------------------
  * Session pool: the FIM -> EFIM prompt rewrite in front of the engine (Sec. 3.1, steps 1-5
  * of the prompt transformation figure).  Host code only; no device is touched.
  *

@@ -88,6 +88,14 @@ def _load():
     lib.efim_decode_step.argtypes = [bp, vp, vp, vp, vp, vp, vp, ctypes.c_double, i32, ctypes.c_float, vp,
                                      ctypes.c_size_t, vp]
     lib.efim_decode_step.restype = i32
+    f32 = ctypes.c_float
+    lib.efim_rope_append_fp8.argtypes = [bp, vp, vp, vp, vp, vp, ctypes.c_double, i32, f32, f32, vp]
+    lib.efim_rope_append_fp8.restype = i32
+    lib.efim_extend_attention_fp8.argtypes = [bp, vp, vp, vp, vp, f32, f32, f32, vp, ctypes.c_size_t, vp]
+    lib.efim_extend_attention_fp8.restype = i32
+    lib.efim_decode_step_fp8.argtypes = [bp, vp, vp, vp, vp, vp, vp, ctypes.c_double, i32, f32, f32, f32, vp,
+                                         ctypes.c_size_t, vp]
+    lib.efim_decode_step_fp8.restype = i32
     lib.efim_extend_plan_items.argtypes = [bp, vp, i64]
     lib.efim_extend_plan_items.restype = i64
     lib.efim_set_tuning.argtypes = [i32, i32]
@@ -121,6 +129,7 @@ LIBRARY_PATH = os.environ.get("EFIM_LIBRARY") or _build.LIB_PATH
 EXPORTED_SYMBOLS = (
     "efim_rope_append", "efim_rope_append_table", "efim_extend_workspace_bytes", "efim_extend_attention",
     "efim_decode_workspace_bytes", "efim_decode_step",
+    "efim_rope_append_fp8", "efim_extend_attention_fp8", "efim_decode_step_fp8",
     "efim_extend_plan_items", "efim_set_tuning", "efim_set_kernel_events", "efim_status_string",
     "efim_last_hip_error", "efim_version",
     "efim_session_pool_create", "efim_session_pool_destroy", "efim_session_transform", "efim_session_prompt",
@@ -212,6 +221,31 @@ def efim_decode_step(batch, q, k_new, v_new, k_cache, v_cache, out, rope_base, r
                                  _ptr(v_cache), _ptr(out), float(rope_base), int(rope_interleaved), float(sm_scale),
                                  _ptr(workspace), int(workspace_bytes), _stream_ptr(stream)),
            "efim_decode_step")
+
+
+def efim_rope_append_fp8(batch, q, k_new, v_new, k_cache, v_cache, rope_base, rope_interleaved, k_scale, v_scale,
+                         stream=None):
+    _check(_lib.efim_rope_append_fp8(ctypes.byref(batch.c), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(k_cache),
+                                     _ptr(v_cache), float(rope_base), int(rope_interleaved), float(k_scale),
+                                     float(v_scale), _stream_ptr(stream)),
+           "efim_rope_append_fp8")
+
+
+def efim_extend_attention_fp8(batch, q, k_cache, v_cache, out, sm_scale, k_scale, v_scale, workspace,
+                              workspace_bytes, stream=None):
+    _check(_lib.efim_extend_attention_fp8(ctypes.byref(batch.c), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(out),
+                                          float(sm_scale), float(k_scale), float(v_scale), _ptr(workspace),
+                                          int(workspace_bytes), _stream_ptr(stream)),
+           "efim_extend_attention_fp8")
+
+
+def efim_decode_step_fp8(batch, q, k_new, v_new, k_cache, v_cache, out, rope_base, rope_interleaved, sm_scale,
+                         k_scale, v_scale, workspace, workspace_bytes, stream=None):
+    _check(_lib.efim_decode_step_fp8(ctypes.byref(batch.c), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(k_cache),
+                                     _ptr(v_cache), _ptr(out), float(rope_base), int(rope_interleaved),
+                                     float(sm_scale), float(k_scale), float(v_scale), _ptr(workspace),
+                                     int(workspace_bytes), _stream_ptr(stream)),
+           "efim_decode_step_fp8")
 
 
 def efim_extend_plan_items(batch):

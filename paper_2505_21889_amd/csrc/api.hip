@@ -136,21 +136,21 @@ namespace {
 
 int rope_append_checked(const efim_batch_t* batch, void* q, const void* k_new, const void* v_new,
                         void* k_cache, void* v_cache, const double* inv_freq, int rotary_dim,
-                        int rope_interleaved, void* stream, int64_t total) {
+                        int rope_interleaved, void* stream, int64_t total, const CacheFormat& fmt = CacheFormat()) {
   if (total == 0) return EFIM_OK;
   if (!k_new || !v_new || !k_cache || !v_cache) return EFIM_ERR_INVALID_ARG;
   if (!aligned16(q) || !aligned16(k_new) || !aligned16(v_new) || !aligned16(k_cache) ||
       !aligned16(v_cache) || (reinterpret_cast<uintptr_t>(batch->block_table) & 3u))
     return EFIM_ERR_INVALID_ARG;
   return launch_rope_append(batch, total, q, k_new, v_new, k_cache, v_cache, inv_freq, rotary_dim,
-                            rope_interleaved, static_cast<hipStream_t>(stream));
+                            rope_interleaved, fmt, static_cast<hipStream_t>(stream));
 }
 
-}  // namespace
+// Scales of an 8-bit cache: finite and positive.
+bool scale_ok(float s) { return s > 0.f && s - s == 0.f; }
 
-int efim_rope_append(const efim_batch_t* batch, void* q, const void* k_new, const void* v_new,
-                     void* k_cache, void* v_cache, double rope_base, int rope_interleaved,
-                     void* stream) {
+int rope_append_base(const efim_batch_t* batch, void* q, const void* k_new, const void* v_new, void* k_cache,
+                     void* v_cache, double rope_base, int rope_interleaved, void* stream, const CacheFormat& fmt) {
   int64_t total = 0;
   int rc = validate_batch(batch, &total);
   if (rc != EFIM_OK) return rc;
@@ -159,7 +159,27 @@ int efim_rope_append(const efim_batch_t* batch, void* q, const void* k_new, cons
   double inv_freq[64];
   for (int j = 0; j < D / 2; ++j) inv_freq[j] = pow(rope_base, -2.0 * j / D);
   return rope_append_checked(batch, q, k_new, v_new, k_cache, v_cache, inv_freq, D, rope_interleaved, stream,
-                             total);
+                             total, fmt);
+}
+
+}  // namespace
+
+int efim_rope_append_fp8(const efim_batch_t* batch, void* q, const void* k_new, const void* v_new,
+                         void* k_cache, void* v_cache, double rope_base, int rope_interleaved,
+                         float k_scale, float v_scale, void* stream) {
+  if (!scale_ok(k_scale) || !scale_ok(v_scale)) return EFIM_ERR_INVALID_ARG;
+  CacheFormat fmt;
+  fmt.fp8 = true;
+  fmt.k_scale = k_scale;
+  fmt.v_scale = v_scale;
+  return rope_append_base(batch, q, k_new, v_new, k_cache, v_cache, rope_base, rope_interleaved, stream, fmt);
+}
+
+int efim_rope_append(const efim_batch_t* batch, void* q, const void* k_new, const void* v_new,
+                     void* k_cache, void* v_cache, double rope_base, int rope_interleaved,
+                     void* stream) {
+  return rope_append_base(batch, q, k_new, v_new, k_cache, v_cache, rope_base, rope_interleaved, stream,
+                          CacheFormat());
 }
 
 int efim_rope_append_table(const efim_batch_t* batch, void* q, const void* k_new, const void* v_new,
@@ -184,8 +204,10 @@ size_t efim_extend_workspace_bytes(const efim_batch_t* batch) {
   return plan.total_bytes < 256 ? 256 : plan.total_bytes;
 }
 
-int efim_extend_attention(const efim_batch_t* batch, const void* q, const void* k_cache,
-                          const void* v_cache, void* out, float sm_scale, void* workspace,
+namespace {
+
+int extend_attention_base(const efim_batch_t* batch, const void* q, const void* k_cache, const void* v_cache,
+                          void* out, float sm_scale, const CacheFormat& fmt, void* workspace,
                           size_t workspace_bytes, void* stream) {
   int64_t total = 0;
   int rc = validate_batch(batch, &total);
@@ -209,11 +231,32 @@ int efim_extend_attention(const efim_batch_t* batch, const void* q, const void* 
   rc = stage_plan(plan, &slot, &header);
   if (rc != EFIM_OK) return rc;
   rc = launch_extend_attention(batch, plan, header, (int)(slot - g_stage), q, k_cache, v_cache, out, sm_scale,
-                               workspace, s);
+                               fmt, workspace, s);
   // the slot is busy until everything enqueued so far on the stream has run
   if (hipEventRecord(slot->done, s) == hipSuccess) slot->in_flight = true;
   else (void)hipStreamSynchronize(s);
   return rc;
+}
+
+}  // namespace
+
+int efim_extend_attention(const efim_batch_t* batch, const void* q, const void* k_cache,
+                          const void* v_cache, void* out, float sm_scale, void* workspace,
+                          size_t workspace_bytes, void* stream) {
+  return extend_attention_base(batch, q, k_cache, v_cache, out, sm_scale, CacheFormat(), workspace,
+                               workspace_bytes, stream);
+}
+
+int efim_extend_attention_fp8(const efim_batch_t* batch, const void* q, const void* k_cache,
+                              const void* v_cache, void* out, float sm_scale, float k_scale, float v_scale,
+                              void* workspace, size_t workspace_bytes, void* stream) {
+  if (!scale_ok(k_scale) || !scale_ok(v_scale)) return EFIM_ERR_INVALID_ARG;
+  CacheFormat fmt;
+  fmt.fp8 = true;
+  fmt.k_scale = k_scale;
+  fmt.v_scale = v_scale;
+  return extend_attention_base(batch, q, k_cache, v_cache, out, sm_scale, fmt, workspace, workspace_bytes,
+                               stream);
 }
 
 namespace {
@@ -239,9 +282,12 @@ size_t efim_decode_workspace_bytes(const efim_batch_t* batch) {
   return plan.total_bytes < 256 ? 256 : plan.total_bytes;
 }
 
-int efim_decode_step(const efim_batch_t* batch, const void* q, const void* k_new, const void* v_new,
+namespace {
+
+int decode_step_base(const efim_batch_t* batch, const void* q, const void* k_new, const void* v_new,
                      void* k_cache, void* v_cache, void* out, double rope_base, int rope_interleaved,
-                     float sm_scale, void* workspace, size_t workspace_bytes, void* stream) {
+                     float sm_scale, const CacheFormat& fmt, void* workspace, size_t workspace_bytes,
+                     void* stream) {
   int64_t total = 0;
   int rc = validate_decode_batch(batch, &total);
   if (rc != EFIM_OK) return rc;
@@ -265,10 +311,32 @@ int efim_decode_step(const efim_batch_t* batch, const void* q, const void* k_new
   rc = stage_plan(plan, &slot, &header);
   if (rc != EFIM_OK) return rc;
   rc = launch_decode_step(batch, plan, header, (int)(slot - g_stage), q, k_new, v_new, k_cache, v_cache, out,
-                          rope_base, rope_interleaved, sm_scale, workspace, s);
+                          rope_base, rope_interleaved, sm_scale, fmt, workspace, s);
   if (hipEventRecord(slot->done, s) == hipSuccess) slot->in_flight = true;
   else (void)hipStreamSynchronize(s);
   return rc;
+}
+
+}  // namespace
+
+int efim_decode_step(const efim_batch_t* batch, const void* q, const void* k_new, const void* v_new,
+                     void* k_cache, void* v_cache, void* out, double rope_base, int rope_interleaved,
+                     float sm_scale, void* workspace, size_t workspace_bytes, void* stream) {
+  return decode_step_base(batch, q, k_new, v_new, k_cache, v_cache, out, rope_base, rope_interleaved, sm_scale,
+                          CacheFormat(), workspace, workspace_bytes, stream);
+}
+
+int efim_decode_step_fp8(const efim_batch_t* batch, const void* q, const void* k_new, const void* v_new,
+                         void* k_cache, void* v_cache, void* out, double rope_base, int rope_interleaved,
+                         float sm_scale, float k_scale, float v_scale, void* workspace, size_t workspace_bytes,
+                         void* stream) {
+  if (!scale_ok(k_scale) || !scale_ok(v_scale)) return EFIM_ERR_INVALID_ARG;
+  CacheFormat fmt;
+  fmt.fp8 = true;
+  fmt.k_scale = k_scale;
+  fmt.v_scale = v_scale;
+  return decode_step_base(batch, q, k_new, v_new, k_cache, v_cache, out, rope_base, rope_interleaved, sm_scale,
+                          fmt, workspace, workspace_bytes, stream);
 }
 
 int64_t efim_extend_plan_items(const efim_batch_t* batch, efim_work_item_t* items, int64_t capacity) {

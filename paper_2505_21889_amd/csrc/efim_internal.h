@@ -64,6 +64,14 @@ struct Plan {
   size_t off_part_o = 0, off_part_ml = 0, total_bytes = 0;
 };
 
+// Number format of the paged caches: bf16, or E4M3 codes with one scale per tensor
+// (value = code value * scale).
+struct CacheFormat {
+  bool fp8 = false;
+  float k_scale = 1.f;
+  float v_scale = 1.f;
+};
+
 // Validates the host-visible part of a batch. total_new receives T.
 int validate_batch(const efim_batch_t* b, int64_t* total_new);
 
@@ -73,7 +81,7 @@ void build_plan(const efim_batch_t* b, int num_slots, Plan* plan);
 // inv_freq: rotary_dim/2 host values; the leading rotary_dim elements of every head row rotate.
 int launch_rope_append(const efim_batch_t* b, int64_t total_new, void* q, const void* k_new,
                        const void* v_new, void* k_cache, void* v_cache, const double* inv_freq,
-                       int rotary_dim, int interleaved, hipStream_t stream);
+                       int rotary_dim, int interleaved, const CacheFormat& fmt, hipStream_t stream);
 
 // `header` is the device-visible address of the staged plan header (reqs, items, merges at
 // the plan's offsets); `workspace` holds the split-KV partial results.
@@ -81,15 +89,15 @@ int launch_rope_append(const efim_batch_t* b, int64_t total_new, void* q, const 
 // block of arrival counters.
 int launch_extend_attention(const efim_batch_t* b, const Plan& plan, const char* header, int stage_slot,
                             const void* q, const void* k_cache, const void* v_cache, void* out,
-                            float sm_scale, void* workspace, hipStream_t stream);
+                            float sm_scale, const CacheFormat& fmt, void* workspace, hipStream_t stream);
 
 // Fused decode step (every request has exactly one new token): one launch does the rotary
 // embedding, the cache append, the attention and the merge of split key ranges.
 constexpr int kDecodeMaxGroup = 32;  // query heads per kv head the fused kernel handles
 int launch_decode_step(const efim_batch_t* b, const Plan& plan, const char* header, int stage_slot,
                        const void* q, const void* k_new, const void* v_new, void* k_cache, void* v_cache,
-                       void* out, double rope_base, int interleaved, float sm_scale, void* workspace,
-                       hipStream_t stream);
+                       void* out, double rope_base, int interleaved, float sm_scale, const CacheFormat& fmt,
+                       void* workspace, hipStream_t stream);
 
 void set_last_hip_error(hipError_t e);
 

@@ -15,7 +15,14 @@
 //     V^T operands come from the row-major V tile through the transposing LDS read.
 // Accumulation is fp32; partial results of split key ranges are merged by a second kernel or,
 // for the decode step, by the workgroup that finishes last.
+//
+// 8-bit caches (E4M3 codes, one scale per tensor): the gather moves the codes (half the bytes)
+// into staging buffers; once a tile has landed the workgroup converts it, every element once,
+// into a bf16 tile of the usual swizzled layout and the products run on that.  The codes'
+// values are exact in bf16; the key scale is folded into the softmax scale and the value scale
+// into the final normalisation.
 #include "efim_internal.h"
+#include "fp8_math.h"
 #include "rope_math.h"
 
 namespace efim {
@@ -29,6 +36,7 @@ __device__ int32_t g_tickets[kTicketSlots * kTicketsPerSlot];
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
@@ -52,7 +60,10 @@ struct AttnParams {
   int32_t num_kv_heads;
   int32_t group;          // Hq / Hkv
   int32_t rows_per_item;
-  float scale_log2;       // sm_scale * log2(e)
+  float scale_log2;       // sm_scale * log2(e) (times the key scale of an 8-bit cache)
+  float out_scale;        // 1, or the value scale of an 8-bit cache
+  float k_scale;          // 8-bit caches, fused decode step: code = value / scale
+  float v_scale;
   // --- fused decode step only (one new token per request) ---
   const uint16_t* k_new;  // [B, Hkv, D] raw keys of the new tokens
   const uint16_t* v_new;  // [B, Hkv, D]
@@ -182,7 +193,7 @@ __device__ __forceinline__ void merge_rows(const AttnParams& p, const MergeItem&
         acc += v[i] * w;
       }
     }
-    const float inv = 1.f / l;
+    const float inv = p.out_scale / l;
     const int row = mi.row_begin + lr;
     const int tok = row / g;
     const int hg = row - tok * g;
@@ -206,13 +217,24 @@ __device__ __forceinline__ void merge_rows(const AttnParams& p, const MergeItem&
 // kernel also does what efim_rope_append does for that token -- q is rotated on the way in
 // (global q stays raw), the workgroup whose key range ends with the new token rotates its key,
 // stores key and value into the paged cache and patches them into its LDS tile.
-template <int D, int WAVES, int STAGES, bool FUSED>
+//
+// KV8: the caches hold E4M3 codes.  The stages then hold code tiles (half the size) and one
+// more bf16 K/V tile, in front of them, receives the converted tile the products run on.
+template <int D, int WAVES, int STAGES, bool FUSED, bool KV8>
 __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const AttnParams p) {
   using G = Geometry<D>;
-  static_assert(STAGES >= 2 && STAGES * 2 * G::kTileBytes <= 160 * 1024, "stages must fit the 160 KB LDS");
-  // stage s: K tile at s * kStageBytes, V tile right behind it
-  constexpr int kStageBytes = 2 * G::kTileBytes;
-  __shared__ __attribute__((aligned(1024))) char lds[STAGES * kStageBytes];
+  // geometry of the gather: rows as they lie in the cache
+  constexpr int kGRowBytes = KV8 ? D : 2 * D;
+  constexpr int kGChunks = kGRowBytes / 16;
+  constexpr int kGTileBytes = kKeyTile * kGRowBytes;
+  constexpr int kGKeysPerLoad = 1024 / kGRowBytes;      // keys moved by one 1 KB wave load
+  constexpr int kGLoadsPerMatrix = kGTileBytes / 1024;  // wave loads per K (or V) tile
+  // stage s: K tile at s * kStageBytes behind the compute tile (if any), V tile right behind it
+  constexpr int kStageBytes = 2 * kGTileBytes;
+  constexpr int kComputeBytes = KV8 ? 2 * G::kTileBytes : 0;
+  static_assert(STAGES >= 2 && kComputeBytes + STAGES * kStageBytes <= 160 * 1024, "stages must fit the 160 KB LDS");
+  __shared__ __attribute__((aligned(1024))) char lds[kComputeBytes + STAGES * kStageBytes];
+  char* const stages = lds + kComputeBytes;
   // fused decode step: the rotated query rows of the tile, the new token's rotated key and its
   // value, cos/sin of the token's position, and the "this workgroup merges" flag
   constexpr int kFusedRows = 32;
@@ -288,23 +310,23 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
   int pages_chunk = 0;
   int pages_cur = load_pages(0);
   int pages_next = last_chunk > 0 ? load_pages(1) : 0;
-  const int64_t page_bytes = ((int64_t)p.num_kv_heads * G::kRowBytes) << ps;
-  const int64_t head_bytes = ((int64_t)it.kv_head * G::kRowBytes) << ps;
+  const int64_t page_bytes = ((int64_t)p.num_kv_heads * kGRowBytes) << ps;
+  const int64_t head_bytes = ((int64_t)it.kv_head * kGRowBytes) << ps;
   // Rows of a tile past the end of the key range are fetched from the last key of the range
   // instead: every tile then issues the same number of loads, pages that may not exist are
   // never touched, and LDS only ever holds finite data (the scores of those rows are masked).
   const int64_t last_off =
-      (int64_t)bt[last_page] * page_bytes + head_bytes + ((k_end - 1) & page_mask) * G::kRowBytes;
+      (int64_t)bt[last_page] * page_bytes + head_bytes + ((k_end - 1) & page_mask) * kGRowBytes;
   // Everything loaded so far (Q operands, page ids) must have landed before the main loop:
   // inside it the only outstanding vector-memory operations are the gathers, which are
   // awaited by hand.  (vmcnt(0), expcnt/lgkmcnt untouched)
   __builtin_amdgcn_s_waitcnt(0x0F70);
 
   // --- gather of one 64-key tile: the 2 * kLoadsPerMatrix 1 KB loads are dealt to the waves
-  constexpr int kLoadsPerWave = 2 * G::kLoadsPerMatrix / WAVES;
-  static_assert(kLoadsPerWave * WAVES == 2 * G::kLoadsPerMatrix, "loads must divide evenly");
-  const int g_key = lane / G::kChunks;  // key within one 1 KB load
-  const int g_pc = lane % G::kChunks;   // physical 16-byte chunk this lane fills
+  constexpr int kLoadsPerWave = 2 * kGLoadsPerMatrix / WAVES;
+  static_assert(kLoadsPerWave * WAVES == 2 * kGLoadsPerMatrix, "loads must divide evenly");
+  const int g_key = lane / kGChunks;  // key within one 1 KB load
+  const int g_pc = lane % kGChunks;   // physical 16-byte chunk this lane fills
   auto issue_tile = [&](int t, char* kbuf, char* vbuf) {
     const int key0 = k_begin + t * kKeyTile;
     const int tile_page = (first_off + t * kKeyTile) >> ps;  // first page of the tile, relative to first_page
@@ -318,16 +340,22 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
     const char* vc = reinterpret_cast<const char*>(p.v_cache);
 #pragma unroll
     for (int j = 0; j < kLoadsPerWave; ++j) {
-      const int load = wave * kLoadsPerWave + j;              // 0 .. 2*kLoadsPerMatrix-1
-      const bool is_v = load >= G::kLoadsPerMatrix;           // wave-uniform
-      const int idx = is_v ? load - G::kLoadsPerMatrix : load;
-      const int row0 = idx * G::kKeysPerLoad;                  // first tile row of this load
+      const int load = wave * kLoadsPerWave + j;              // 0 .. 2*kGLoadsPerMatrix-1
+      const bool is_v = load >= kGLoadsPerMatrix;             // wave-uniform
+      const int idx = is_v ? load - kGLoadsPerMatrix : load;
+      const int row0 = idx * kGKeysPerLoad;                    // first tile row of this load
       const int tile_row = row0 + g_key;
-      const int64_t page =
-          __builtin_amdgcn_readlane(pages_cur, ((first_off + t * kKeyTile + row0) >> ps) & 63);
-      const int64_t in_off = page * page_bytes + head_bytes + ((key0 + tile_row) & page_mask) * G::kRowBytes;
+      // one load never spans two pages, except for the shortest rows on the smallest pages:
+      // then every lane looks its own page up
+      int64_t page;
+      if constexpr (kGKeysPerLoad <= kMinPageSize)
+        page = __builtin_amdgcn_readlane(pages_cur, ((first_off + t * kKeyTile + row0) >> ps) & 63);
+      else
+        page = __builtin_amdgcn_ds_bpermute((((first_off + t * kKeyTile + tile_row) >> ps) & 63) << 2, pages_cur);
+      const int64_t in_off = page * page_bytes + head_bytes + ((key0 + tile_row) & page_mask) * kGRowBytes;
       const int64_t row_off = (key0 + tile_row < k_end) ? in_off : last_off;
-      const int swz = is_v ? G::vswz(tile_row) : G::kswz(tile_row);
+      // code tiles stay row-major: the conversion pass applies the swizzles
+      const int swz = KV8 ? 0 : (is_v ? G::vswz(tile_row) : G::kswz(tile_row));
       const char* src = (is_v ? vc : kc) + row_off + ((g_pc ^ swz) << 4);
       load_to_lds_16(src, (is_v ? vbuf : kbuf) + idx * 1024);
     }
@@ -453,6 +481,34 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
     }
   };
 
+  // 8-bit caches: the landed code tile (K rows, then V rows, row-major) becomes the bf16 tile
+  // at the front of the LDS, in the swizzled layout compute_tile reads.  A thread takes 16
+  // codes at a time: one 16-byte read, eight two-at-a-time conversions, two 16-byte writes.
+  auto convert_tile = [&](const char* codes) {
+    constexpr int kUnitsPerMatrix = kKeyTile * kGChunks;
+#pragma unroll
+    for (int u0 = 0; u0 < 2 * kUnitsPerMatrix; u0 += 64 * WAVES) {
+      const int u = u0 + tid;
+      const bool is_v = u >= kUnitsPerMatrix;
+      const int idx = is_v ? u - kUnitsPerMatrix : u;
+      const int row = idx / kGChunks;
+      const int c = idx - row * kGChunks;
+      const u32x4 w = *reinterpret_cast<const u32x4*>(codes + u * 16);
+      u32x4 lo, hi;
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        lo[2 * j] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w[j], 1.0f, false));
+        lo[2 * j + 1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w[j], 1.0f, true));
+        hi[2 * j] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w[2 + j], 1.0f, false));
+        hi[2 * j + 1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w[2 + j], 1.0f, true));
+      }
+      const int swz = is_v ? G::vswz(row) : G::kswz(row);
+      char* dst = lds + (is_v ? G::kTileBytes : 0) + row * G::kRowBytes;
+      *reinterpret_cast<u32x4*>(dst + (((2 * c) ^ swz) << 4)) = lo;
+      *reinterpret_cast<u32x4*>(dst + (((2 * c + 1) ^ swz) << 4)) = hi;
+    }
+  };
+
   auto step = [&](int t, const char* ks, const char* vs) {
     if (wave_active && k_begin + t * kKeyTile < wave_max_vis) compute_tile(t, ks, vs);
   };
@@ -471,7 +527,7 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
 
 #pragma unroll
   for (int s0 = 0; s0 < STAGES - 1; ++s0)
-    if (s0 < ntiles) issue_tile(s0, lds + s0 * kStageBytes, lds + s0 * kStageBytes + G::kTileBytes);
+    if (s0 < ntiles) issue_tile(s0, stages + s0 * kStageBytes, stages + s0 * kStageBytes + kGTileBytes);
   if constexpr (FUSED) {
     // rotary embedding of the tile's query rows and of the new token's key at position C_r
     // (the request's only new token is packed row rq.row_start), same arithmetic as the
@@ -499,10 +555,20 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
       }
       uint32_t y1, y2;
       rotate_pair_bf16(src[e1], src[e2], s_cs[j], s_cs[64 + j], &y1, &y2);
-      dst[e1] = (uint16_t)y1;
-      dst[e2] = (uint16_t)y2;
+      if (KV8 && r == it.row_count) {
+        // the key goes into the cache as a code: D bytes, the value's D bytes behind them
+        uint8_t* codes = reinterpret_cast<uint8_t*>(s_kv);
+        codes[e1] = (uint8_t)bf16_bits_to_e4m3(y1, p.k_scale);
+        codes[e2] = (uint8_t)bf16_bits_to_e4m3(y2, p.k_scale);
+      } else {
+        dst[e1] = (uint16_t)y1;
+        dst[e2] = (uint16_t)y2;
+      }
     }
-    for (int e = tid; e < D; e += 64 * WAVES) s_kv[D + e] = p.v_new[kv_row + e];
+    for (int e = tid; e < D; e += 64 * WAVES) {
+      if constexpr (KV8) reinterpret_cast<uint8_t*>(s_kv)[D + e] = (uint8_t)bf16_bits_to_e4m3(p.v_new[kv_row + e], p.v_scale);
+      else s_kv[D + e] = p.v_new[kv_row + e];
+    }
     __syncthreads();
   }
   if constexpr (FUSED) {
@@ -521,7 +587,7 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
         wait_tile(t);
         constexpr int kAhead = STAGES - 1;
         const int sl = (s0 + kAhead) % STAGES;  // static after unrolling
-        if (t + kAhead < ntiles) issue_tile(t + kAhead, lds + sl * kStageBytes, lds + sl * kStageBytes + G::kTileBytes);
+        if (t + kAhead < ntiles) issue_tile(t + kAhead, stages + sl * kStageBytes, stages + sl * kStageBytes + kGTileBytes);
         if constexpr (FUSED) {
           // The key range that ends with the new token: the cache slot of that token has not
           // been written yet, so its row of the landed tile and the rows behind it (which the
@@ -530,26 +596,36 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
           if (k_end == rq.cached + 1 && t == ntiles - 1) {
             const int pos = rq.cached;
             const int prow = pos - (k_begin + t * kKeyTile);
-            constexpr int kPerRow = 2 * G::kChunks;  // 16-byte chunks of a key row and a value row
+            constexpr int kPerRow = 2 * kGChunks;  // 16-byte chunks of a key row and a value row
             for (int u = tid; u < (kKeyTile - prow) * kPerRow; u += 64 * WAVES) {
               const int row = prow + u / kPerRow;
               const int w = u % kPerRow;
-              const bool is_v = w >= G::kChunks;
-              const int c = is_v ? w - G::kChunks : w;
-              const u32x4 val = *reinterpret_cast<const u32x4*>(s_kv + (is_v ? D : 0) + c * 8);
-              const int swz = is_v ? G::vswz(row) : G::kswz(row);
-              char* tile = lds + s0 * kStageBytes + (is_v ? G::kTileBytes : 0);
-              *reinterpret_cast<u32x4*>(tile + row * G::kRowBytes + ((c ^ swz) << 4)) = val;
+              const bool is_v = w >= kGChunks;
+              const int c = is_v ? w - kGChunks : w;
+              const u32x4 val =
+                  *reinterpret_cast<const u32x4*>(reinterpret_cast<const char*>(s_kv) + (is_v ? kGRowBytes : 0) + c * 16);
+              const int swz = KV8 ? 0 : (is_v ? G::vswz(row) : G::kswz(row));
+              char* tile = stages + s0 * kStageBytes + (is_v ? kGTileBytes : 0);
+              *reinterpret_cast<u32x4*>(tile + row * kGRowBytes + ((c ^ swz) << 4)) = val;
               if (row == prow) {
                 const int64_t page = bt[pos >> ps];
-                uint16_t* cache = is_v ? p.v_cache_w : p.k_cache_w;
-                *reinterpret_cast<u32x4*>(cache + ((((page * p.num_kv_heads + it.kv_head) << ps) + (pos & page_mask)) * D + c * 8)) = val;
+                char* cache = reinterpret_cast<char*>(is_v ? p.v_cache_w : p.k_cache_w);
+                *reinterpret_cast<u32x4*>(
+                    cache + (((page * p.num_kv_heads + it.kv_head) << ps) + (pos & page_mask)) * kGRowBytes + c * 16) = val;
               }
             }
             __syncthreads();
           }
         }
-        step(t, lds + s0 * kStageBytes, lds + s0 * kStageBytes + G::kTileBytes);
+        if constexpr (KV8) {
+          // every wave is done with the previous bf16 tile (loop-top barrier); the second
+          // barrier publishes the converted one
+          convert_tile(stages + s0 * kStageBytes);
+          __syncthreads();
+          step(t, lds, lds + G::kTileBytes);
+        } else {
+          step(t, stages + s0 * kStageBytes, stages + s0 * kStageBytes + kGTileBytes);
+        }
       }
     }
   }
@@ -559,7 +635,7 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
     const float l_tot = cross_half_sum(l_run);
     if (row_ok) {
       if (it.partial_slot < 0) {
-        const float inv = 1.f / l_tot;
+        const float inv = p.out_scale / l_tot;
         uint16_t* dst = p.out + q_off;
 #pragma unroll
         for (int d = 0; d < G::kDBlocks; ++d)
@@ -636,7 +712,8 @@ __global__ __launch_bounds__(256) void merge_kernel(const AttnParams p, const Me
 namespace {
 
 void fill_params(AttnParams* p, const efim_batch_t* b, const Plan& plan, const char* header, const void* q,
-                 const void* k_cache, const void* v_cache, void* out, float sm_scale, char* partials) {
+                 const void* k_cache, const void* v_cache, void* out, float sm_scale, const CacheFormat& fmt,
+                 char* partials) {
   p->reqs = reinterpret_cast<const ReqInfo*>(header + plan.off_reqs);
   p->items = reinterpret_cast<const WorkItem*>(header + plan.off_items);
   p->q = static_cast<const uint16_t*>(q);
@@ -652,6 +729,13 @@ void fill_params(AttnParams* p, const efim_batch_t* b, const Plan& plan, const c
   p->group = b->num_q_heads / b->num_kv_heads;
   p->rows_per_item = plan.rows_per_item;
   p->scale_log2 = sm_scale * 1.4426950408889634f;
+  p->out_scale = 1.f;
+  p->k_scale = fmt.k_scale;
+  p->v_scale = fmt.v_scale;
+  if (fmt.fp8) {
+    p->scale_log2 *= fmt.k_scale;
+    p->out_scale = fmt.v_scale;
+  }
   p->k_new = nullptr;
   p->v_new = nullptr;
   p->k_cache_w = nullptr;
@@ -678,6 +762,21 @@ bool use_tickets(const Plan& plan, bool decode) {
   return want && !plan.merges.empty() && plan.merges.size() <= (size_t)kTicketsPerSlot;
 }
 
+template <bool FUSED>
+void launch_kernel(int head_dim, bool wide, bool fp8, dim3 grid, const AttnParams& p, hipStream_t stream) {
+#define EFIM_ATTN_LAUNCH(DD, F8)                                                                   \
+  do {                                                                                             \
+    if (wide) extend_attention_kernel<DD, 8, 3, FUSED, F8><<<grid, 512, 0, stream>>>(p);           \
+    else extend_attention_kernel<DD, 4, 2, FUSED, F8><<<grid, 256, 0, stream>>>(p);                \
+  } while (0)
+  if (head_dim == 128) {
+    if (fp8) EFIM_ATTN_LAUNCH(128, true); else EFIM_ATTN_LAUNCH(128, false);
+  } else {
+    if (fp8) EFIM_ATTN_LAUNCH(64, true); else EFIM_ATTN_LAUNCH(64, false);
+  }
+#undef EFIM_ATTN_LAUNCH
+}
+
 int launch_merge(const efim_batch_t* b, const Plan& plan, const AttnParams& p, hipStream_t stream) {
   const dim3 mgrid((unsigned)plan.merges.size(), (unsigned)(plan.rows_per_item * (b->head_dim / 4) / 256));
   if (b->head_dim == 128) merge_kernel<128><<<mgrid, 256, 0, stream>>>(p, p.merges);
@@ -691,22 +790,16 @@ int launch_merge(const efim_batch_t* b, const Plan& plan, const AttnParams& p, h
 
 int launch_extend_attention(const efim_batch_t* b, const Plan& plan, const char* header, int stage_slot,
                             const void* q, const void* k_cache, const void* v_cache, void* out,
-                            float sm_scale, void* workspace, hipStream_t stream) {
+                            float sm_scale, const CacheFormat& fmt, void* workspace, hipStream_t stream) {
   AttnParams p;
-  fill_params(&p, b, plan, header, q, k_cache, v_cache, out, sm_scale, static_cast<char*>(workspace));
+  fill_params(&p, b, plan, header, q, k_cache, v_cache, out, sm_scale, fmt, static_cast<char*>(workspace));
   if (use_tickets(plan, false)) p.ticket_base = stage_slot * kTicketsPerSlot;
 
   const dim3 grid((unsigned)plan.items.size());
   const Tuning& tn = tuning();
   if (tn.ev_start) (void)hipEventRecord(tn.ev_start, stream);
   const bool wide = plan.rows_per_item == 256;
-  if (b->head_dim == 128) {
-    if (wide) extend_attention_kernel<128, 8, 3, false><<<grid, 512, 0, stream>>>(p);
-    else extend_attention_kernel<128, 4, 2, false><<<grid, 256, 0, stream>>>(p);
-  } else {
-    if (wide) extend_attention_kernel<64, 8, 3, false><<<grid, 512, 0, stream>>>(p);
-    else extend_attention_kernel<64, 4, 2, false><<<grid, 256, 0, stream>>>(p);
-  }
+  launch_kernel<false>(b->head_dim, wide, fmt.fp8, grid, p, stream);
   hipError_t e = hipGetLastError();
   if (tn.ev_stop) (void)hipEventRecord(tn.ev_stop, stream);
   if (e != hipSuccess) { set_last_hip_error(e); return EFIM_ERR_LAUNCH; }
@@ -716,10 +809,10 @@ int launch_extend_attention(const efim_batch_t* b, const Plan& plan, const char*
 
 int launch_decode_step(const efim_batch_t* b, const Plan& plan, const char* header, int stage_slot,
                        const void* q, const void* k_new, const void* v_new, void* k_cache, void* v_cache,
-                       void* out, double rope_base, int interleaved, float sm_scale, void* workspace,
-                       hipStream_t stream) {
+                       void* out, double rope_base, int interleaved, float sm_scale, const CacheFormat& fmt,
+                       void* workspace, hipStream_t stream) {
   AttnParams p;
-  fill_params(&p, b, plan, header, q, k_cache, v_cache, out, sm_scale, static_cast<char*>(workspace));
+  fill_params(&p, b, plan, header, q, k_cache, v_cache, out, sm_scale, fmt, static_cast<char*>(workspace));
   if (use_tickets(plan, true)) p.ticket_base = stage_slot * kTicketsPerSlot;
   p.k_new = static_cast<const uint16_t*>(k_new);
   p.v_new = static_cast<const uint16_t*>(v_new);
@@ -733,13 +826,7 @@ int launch_decode_step(const efim_batch_t* b, const Plan& plan, const char* head
   const Tuning& tn = tuning();
   if (tn.ev_start) (void)hipEventRecord(tn.ev_start, stream);
   const bool wide = plan.rows_per_item == 256;
-  if (D == 128) {
-    if (wide) extend_attention_kernel<128, 8, 3, true><<<grid, 512, 0, stream>>>(p);
-    else extend_attention_kernel<128, 4, 2, true><<<grid, 256, 0, stream>>>(p);
-  } else {
-    if (wide) extend_attention_kernel<64, 8, 3, true><<<grid, 512, 0, stream>>>(p);
-    else extend_attention_kernel<64, 4, 2, true><<<grid, 256, 0, stream>>>(p);
-  }
+  launch_kernel<true>(D, wide, fmt.fp8, grid, p, stream);
   hipError_t e = hipGetLastError();
   if (tn.ev_stop) (void)hipEventRecord(tn.ev_stop, stream);
   if (e != hipSuccess) { set_last_hip_error(e); return EFIM_ERR_LAUNCH; }

@@ -7,7 +7,12 @@
 // bit for bit with a double-precision definition.  One workgroup handles kTokens tokens:
 // first one thread per (token, pair index) evaluates sincos once and parks it in LDS, then
 // all threads stream the (Hq + 2*Hkv) head rows of those tokens with 16-byte accesses.
+//
+// KV8 variant: the caches hold E4M3 codes (one byte per element, same [page, head, slot, D]
+// layout); the rotated key (after its rounding to bf16) and the value are divided by the
+// tensor's scale and rounded to the nearest code on their way out.
 #include "efim_internal.h"
+#include "fp8_math.h"
 #include "rope_math.h"
 
 namespace efim {
@@ -28,18 +33,35 @@ struct RopeArgs {
   int32_t rotate_q;                         // 0 when q is NULL
   int32_t rotary_dim;                       // leading elements of a head row that are rotated
   int32_t page_shift;                       // log2 of the page size (tokens per page)
+  float k_scale;                            // 8-bit caches: code = value / scale
+  float v_scale;
 };
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+// E4M3 codes of eight bf16 values
+__device__ __forceinline__ u32x2 quantize8(u32x4 x, float scale) {
+  u32x2 r;
+#pragma unroll
+  for (int t = 0; t < 2; ++t) {
+    const uint32_t lo = x[2 * t], hi = x[2 * t + 1];
+    r[t] = bf16_bits_to_e4m3(lo & 0xFFFFu, scale) | (bf16_bits_to_e4m3(lo >> 16, scale) << 8) |
+           (bf16_bits_to_e4m3(hi & 0xFFFFu, scale) << 16) | (bf16_bits_to_e4m3(hi >> 16, scale) << 24);
+  }
+  return r;
+}
 
 // kTokens = tokens per workgroup: 4 for large steps (all threads busy in the sincos phase),
 // 1 for small ones so that even a few hundred tokens spread over the whole device.
-template <int D, bool INTERLEAVED, int kTokens>
+template <int D, bool INTERLEAVED, int kTokens, bool KV8>
 __global__ __launch_bounds__(kThreads) void rope_append_kernel(
     const RopeArgs args, uint16_t* __restrict__ q, const uint16_t* __restrict__ k_new,
-    const uint16_t* __restrict__ v_new, uint16_t* __restrict__ k_cache,
-    uint16_t* __restrict__ v_cache, const int32_t* __restrict__ block_table) {
+    const uint16_t* __restrict__ v_new, void* __restrict__ k_cache_raw,
+    void* __restrict__ v_cache_raw, const int32_t* __restrict__ block_table) {
 #pragma clang fp contract(off)
+  uint16_t* k_cache = static_cast<uint16_t*>(k_cache_raw);
+  uint16_t* v_cache = static_cast<uint16_t*>(v_cache_raw);
   constexpr int HALF = D / 2;
   const int rot_half = args.rotary_dim / 2;  // pairs per head row (D/2 when the whole row rotates)
   __shared__ double s_cos[kTokens][HALF];
@@ -97,6 +119,7 @@ __global__ __launch_bounds__(kThreads) void rope_append_kernel(
 
     const uint16_t* src;
     uint16_t* dst;
+    int64_t cache_off = 0;  // element offset of the head row in the cache
     bool rotate = in_rotary;
     if (hr < hq) {
       if (!args.rotate_q) continue;
@@ -105,11 +128,13 @@ __global__ __launch_bounds__(kThreads) void rope_append_kernel(
     } else if (hr < hq + hkv) {
       const int h = hr - hq;
       src = k_new + (row * hkv + h) * D;
-      dst = k_cache + s_dst[tt] + (((int64_t)h * D) << args.page_shift);
+      cache_off = s_dst[tt] + (((int64_t)h * D) << args.page_shift);
+      dst = k_cache + cache_off;
     } else {
       const int h = hr - hq - hkv;
       src = v_new + (row * hkv + h) * D;
-      dst = v_cache + s_dst[tt] + (((int64_t)h * D) << args.page_shift);
+      cache_off = s_dst[tt] + (((int64_t)h * D) << args.page_shift);
+      dst = v_cache + cache_off;
       rotate = false;
     }
     u32x4 a = *reinterpret_cast<const u32x4*>(src + e0);
@@ -149,8 +174,16 @@ __global__ __launch_bounds__(kThreads) void rope_append_kernel(
         b[t] = yb[2 * t] | (yb[2 * t + 1] << 16);
       }
     }
-    *reinterpret_cast<u32x4*>(dst + e0) = a;
-    *reinterpret_cast<u32x4*>(dst + e1) = b;
+    if (KV8 && hr >= hq) {
+      const bool is_k = hr < hq + hkv;
+      uint8_t* row8 = static_cast<uint8_t*>(is_k ? k_cache_raw : v_cache_raw) + cache_off;
+      const float scale = is_k ? args.k_scale : args.v_scale;
+      *reinterpret_cast<u32x2*>(row8 + e0) = quantize8(a, scale);
+      *reinterpret_cast<u32x2*>(row8 + e1) = quantize8(b, scale);
+    } else {
+      *reinterpret_cast<u32x4*>(dst + e0) = a;
+      *reinterpret_cast<u32x4*>(dst + e1) = b;
+    }
   }
 }
 
@@ -158,7 +191,7 @@ __global__ __launch_bounds__(kThreads) void rope_append_kernel(
 
 int launch_rope_append(const efim_batch_t* b, int64_t total_new, void* q, const void* k_new,
                        const void* v_new, void* k_cache, void* v_cache, const double* inv_freq,
-                       int rotary_dim, int interleaved, hipStream_t stream) {
+                       int rotary_dim, int interleaved, const CacheFormat& fmt, hipStream_t stream) {
   (void)total_new;
   const int D = b->head_dim;
   RopeArgs args;
@@ -171,6 +204,8 @@ int launch_rope_append(const efim_batch_t* b, int64_t total_new, void* q, const 
   args.num_q_heads = b->num_q_heads;
   args.num_kv_heads = b->num_kv_heads;
   args.rotate_q = q != nullptr;
+  args.k_scale = fmt.k_scale;
+  args.v_scale = fmt.v_scale;
 
   int64_t row = 0;
   for (int r0 = 0; r0 < b->batch; r0 += kMaxReqPerLaunch) {
@@ -189,11 +224,11 @@ int launch_rope_append(const efim_batch_t* b, int64_t total_new, void* q, const 
     auto qp = static_cast<uint16_t*>(q);
     auto kn = static_cast<const uint16_t*>(k_new);
     auto vn = static_cast<const uint16_t*>(v_new);
-    auto kc = static_cast<uint16_t*>(k_cache);
-    auto vc = static_cast<uint16_t*>(v_cache);
-#define EFIM_ROPE_LAUNCH(DD, IL, TOK)                                                        \
-  rope_append_kernel<DD, IL, TOK><<<dim3((unsigned)((ntok + TOK - 1) / TOK)), kThreads, 0, stream>>>( \
-      args, qp, kn, vn, kc, vc, b->block_table)
+#define EFIM_ROPE_LAUNCH3(DD, IL, TOK, F8)                                                        \
+  rope_append_kernel<DD, IL, TOK, F8><<<dim3((unsigned)((ntok + TOK - 1) / TOK)), kThreads, 0, stream>>>( \
+      args, qp, kn, vn, k_cache, v_cache, b->block_table)
+#define EFIM_ROPE_LAUNCH(DD, IL, TOK) \
+  do { if (fmt.fp8) EFIM_ROPE_LAUNCH3(DD, IL, TOK, true); else EFIM_ROPE_LAUNCH3(DD, IL, TOK, false); } while (0)
     const bool small = ntok < 16384;
     if (D == 128) {
       if (interleaved) { if (small) EFIM_ROPE_LAUNCH(128, true, 1); else EFIM_ROPE_LAUNCH(128, true, 4); }
@@ -203,6 +238,7 @@ int launch_rope_append(const efim_batch_t* b, int64_t total_new, void* q, const 
       else { if (small) EFIM_ROPE_LAUNCH(64, false, 1); else EFIM_ROPE_LAUNCH(64, false, 4); }
     }
 #undef EFIM_ROPE_LAUNCH
+#undef EFIM_ROPE_LAUNCH3
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) { set_last_hip_error(e); return EFIM_ERR_LAUNCH; }
   }

@@ -1,0 +1,257 @@
+"""The 8-bit (E4M3, per-tensor scale) KV cache calls against the oracle: the quantising append is
+byte-exact, the conversion back is exact on every code, attention and the decode step stay within
+the attention tolerance of the fp64 result over the same codes."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import efim_oracle as O
+from oracle import fp8_oracle as F
+from paper_2505_21889_amd import workloads as W
+
+import gpu_util as U
+
+pytestmark = pytest.mark.gpu
+
+POISON_CODE = 0x7F   # the NaN code: a stray read of an unwritten slot shows in the output
+TIE_SCALE = float.fromhex("0x1.af286cp-8")   # 2^-7 / TIE_SCALE is a rounding tie only in binary32
+
+
+@pytest.fixture(scope="module")
+def E():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2505_21889_amd import binding
+    return binding
+
+
+def dev_u8(x):
+    return torch.from_numpy(np.ascontiguousarray(x)).cuda()
+
+
+def oracle_cache8(b, k_scale, v_scale):
+    """Code caches holding the history (positions 0..C-1) as the oracle quantises it; the rest poison."""
+    kc = np.full(b.cache_shape(), POISON_CODE, dtype=np.uint8)
+    vc = np.full(b.cache_shape(), POISON_CODE, dtype=np.uint8)
+    if b.k_hist is not None and int(b.cached_len.sum()) > 0:
+        F.rope_append_fp8(np.zeros_like(b.cached_len), b.cached_len, b.block_table, b.page_size, None,
+                          b.k_hist, b.v_hist, kc, vc, b.rope_base, k_scale, v_scale)
+    return kc, vc
+
+
+def gpu_append8(E, b, kc, vc, k_scale, v_scale, interleaved=0):
+    table = torch.from_numpy(b.block_table).cuda()
+    desc = U.make_desc(E, b, table)
+    q = U.dev_bits(b.q_new)
+    kcd, vcd = dev_u8(kc), dev_u8(vc)
+    E.efim_rope_append_fp8(desc, q, U.dev_bits(b.k_new), U.dev_bits(b.v_new), kcd, vcd, b.rope_base, interleaved,
+                           k_scale, v_scale)
+    torch.cuda.synchronize()
+    return U.host_bits(q), kcd.cpu().numpy(), vcd.cpu().numpy()
+
+
+def gpu_attention8(E, b, q_roped, kc, vc, k_scale, v_scale, sm_scale=0.0):
+    table = torch.from_numpy(b.block_table).cuda()
+    desc = U.make_desc(E, b, table)
+    q = U.dev_bits(q_roped)
+    out = torch.full(q.shape, 0x7FC1, dtype=torch.int16, device="cuda")
+    nbytes = E.efim_extend_workspace_bytes(desc)
+    ws = torch.full((max(nbytes, 256),), 0xA5, dtype=torch.uint8, device="cuda")
+    E.efim_extend_attention_fp8(desc, q, dev_u8(kc), dev_u8(vc), out, sm_scale, k_scale, v_scale, ws, nbytes)
+    torch.cuda.synchronize()
+    return U.host_bits(out)
+
+
+def oracle_step8(b, kc, vc, k_scale, v_scale, interleaved=False):
+    kc, vc = kc.copy(), vc.copy()
+    q_roped, _ = F.rope_append_fp8(b.cached_len, b.new_len, b.block_table, b.page_size, b.q_new, b.k_new, b.v_new,
+                                   kc, vc, b.rope_base, k_scale, v_scale, interleaved)
+    ref = F.extend_attention_fp8(b.cached_len, b.new_len, b.block_table, b.page_size, q_roped, kc, vc,
+                                 k_scale, v_scale)
+    return q_roped, kc, vc, ref
+
+
+# ------------------------------------------------------------------ append ----
+
+@pytest.mark.parametrize("k_scale,v_scale", [(1.0, 1.0), (0.0123, 0.031), (TIE_SCALE, 3.7)])
+@pytest.mark.parametrize("heads,d,interleaved,page_size", [((8, 2), 128, 0, 16), ((4, 4), 64, 1, 16), ((6, 2), 128, 1, 64),
+                                                           ((4, 1), 64, 0, 8)])
+def test_fp8_append_is_byte_exact(E, heads, d, interleaved, page_size, k_scale, v_scale):
+    c = np.array([0, 5, 16, 100, 31, 0, 257], dtype=np.int32)
+    n = np.array([1, 40, 0, 17, 300, 64, 3], dtype=np.int32)
+    b = W.make_batch("c1", seed=610 + d + page_size, lengths=(c, n), heads=heads, head_dim=d, page_size=page_size)
+    kc, vc = oracle_cache8(b, k_scale, v_scale)
+    q_ref, kc_ref, vc_ref, _ = None, kc.copy(), vc.copy(), None
+    q_ref, _ = F.rope_append_fp8(b.cached_len, b.new_len, b.block_table, b.page_size, b.q_new, b.k_new, b.v_new,
+                                 kc_ref, vc_ref, b.rope_base, k_scale, v_scale, bool(interleaved))
+    q_got, kc_got, vc_got = gpu_append8(E, b, kc, vc, k_scale, v_scale, interleaved)
+    assert np.array_equal(q_got, q_ref)
+    assert np.array_equal(kc_got, kc_ref), "key codes differ (unwritten slots included)"
+    assert np.array_equal(vc_got, vc_ref), "value codes differ (unwritten slots included)"
+
+
+@pytest.mark.parametrize("scale", [1.0, 0.37, TIE_SCALE, 1e-3, 300.0])
+def test_fp8_quantiser_on_every_bf16_value(E, scale):
+    """All 65536 bf16 patterns go through the append as values (which are not rotated): every
+    code equals the oracle's, ties, saturation, subnormals, infinities and NaN included."""
+    heads, d = (64, 64), 128
+    n = np.array([8], dtype=np.int32)
+    b = W.make_batch("c1", seed=3, lengths=(np.zeros(1, dtype=np.int32), n), heads=heads, head_dim=d)
+    b.v_new = np.arange(65536, dtype=np.uint32).astype(np.uint16).reshape(8, 64, 128)
+    kc = np.full(b.cache_shape(), POISON_CODE, dtype=np.uint8)
+    vc = kc.copy()
+    kc_ref, vc_ref = kc.copy(), vc.copy()
+    F.rope_append_fp8(b.cached_len, b.new_len, b.block_table, b.page_size, None, b.k_new, b.v_new, kc_ref, vc_ref,
+                      b.rope_base, 1.0, scale)
+    _, kc_got, vc_got = gpu_append8(E, b, kc, vc, 1.0, scale)
+    assert np.array_equal(vc_got, vc_ref)
+    assert np.array_equal(kc_got, kc_ref)
+
+
+# --------------------------------------------------------------- attention ----
+
+@pytest.mark.parametrize("d", [64, 128])
+def test_fp8_every_code_converts_back_exactly(E, d):
+    """One visible key: the output is that key's value row.  The value rows hold every finite
+    code; with a power-of-two scale the expected bf16 output is exact."""
+    hkv = 256 // d
+    b = W.make_batch("c1", seed=4, lengths=(np.zeros(1, dtype=np.int32), np.ones(1, dtype=np.int32)),
+                     heads=(2 * hkv, hkv), head_dim=d)
+    codes = np.arange(256, dtype=np.uint8)
+    codes[(codes & 0x7F) == 0x7F] = 0x38
+    kc = np.full(b.cache_shape(), POISON_CODE, dtype=np.uint8)
+    vc = np.full(b.cache_shape(), POISON_CODE, dtype=np.uint8)
+    page = b.block_table[0, 0]
+    kc[page, :, 0, :] = 0x38
+    vc[page, :, 0, :] = codes.reshape(hkv, d)
+    for v_scale in (1.0, 0.25):
+        got = O.bf16_to_f64(gpu_attention8(E, b, b.q_new, kc, vc, 0.5, v_scale))
+        want = (F.e4m3_decode(codes) * v_scale).reshape(hkv, d)
+        for a in range(2 * hkv):
+            # (values only: the sign of a zero does not survive the sum over the key tile)
+            assert np.array_equal(got[0, a], want[a // 2]), "head %d scale %g" % (a, v_scale)
+
+
+@pytest.mark.parametrize("row_tile,split", [(0, -1), (128, 64), (256, 128), (256, 0)])
+@pytest.mark.parametrize("heads,d,page_size", [((8, 2), 128, 16), ((4, 4), 128, 16), ((8, 4), 64, 16), ((14, 2), 128, 64),
+                                               ((4, 2), 64, 8)])
+def test_fp8_attention_parity(E, heads, d, page_size, row_tile, split):
+    c = np.array([0, 3, 64, 130, 1000, 17, 2100, 0], dtype=np.int32)
+    n = np.array([70, 1, 16, 129, 8, 300, 2, 1], dtype=np.int32)
+    k_scale, v_scale = 0.0123, 0.031
+    b = W.make_batch("c1", seed=620 + d + page_size, lengths=(c, n), heads=heads, head_dim=d, page_size=page_size)
+    kc, vc = oracle_cache8(b, k_scale, v_scale)
+    q_roped, kc, vc, ref = oracle_step8(b, kc, vc, k_scale, v_scale)
+    E.efim_set_tuning(E.EFIM_TUNE_ROW_TILE, row_tile)
+    E.efim_set_tuning(E.EFIM_TUNE_SPLIT_KV, split)
+    try:
+        got = gpu_attention8(E, b, q_roped, kc, vc, k_scale, v_scale)
+    finally:
+        E.efim_set_tuning(E.EFIM_TUNE_ROW_TILE, 0)
+        E.efim_set_tuning(E.EFIM_TUNE_SPLIT_KV, -1)
+    U.assert_close(got, ref, "fp8 attention")
+
+
+def test_fp8_attention_with_unit_scales_and_sm_scale(E):
+    c = np.array([500, 64], dtype=np.int32)
+    n = np.array([33, 128], dtype=np.int32)
+    b = W.make_batch("c1", seed=630, lengths=(c, n), heads=(8, 2), head_dim=128)
+    kc, vc = oracle_cache8(b, 1.0, 1.0)
+    q_roped, kc, vc, _ = oracle_step8(b, kc, vc, 1.0, 1.0)
+    ref = F.extend_attention_fp8(b.cached_len, b.new_len, b.block_table, b.page_size, q_roped, kc, vc, 1.0, 1.0,
+                                 sm_scale=0.05)
+    U.assert_close(gpu_attention8(E, b, q_roped, kc, vc, 1.0, 1.0, sm_scale=0.05), ref, "unit scales")
+
+
+def test_fp8_gpu_append_then_attention(E):
+    """Both calls on the device, back to back on device-resident codes."""
+    c = np.array([200, 0, 1500], dtype=np.int32)
+    n = np.array([50, 260, 4], dtype=np.int32)
+    k_scale, v_scale = 0.02, 0.02
+    b = W.make_batch("c1", seed=640, lengths=(c, n), heads=(8, 2), head_dim=128)
+    kc, vc = oracle_cache8(b, k_scale, v_scale)
+    q_ref, kc_ref, vc_ref, ref = oracle_step8(b, kc, vc, k_scale, v_scale)
+    q_got, kc_got, vc_got = gpu_append8(E, b, kc, vc, k_scale, v_scale)
+    assert np.array_equal(kc_got, kc_ref) and np.array_equal(vc_got, vc_ref) and np.array_equal(q_got, q_ref)
+    U.assert_close(gpu_attention8(E, b, q_got, kc_got, vc_got, k_scale, v_scale), ref, "append then attention")
+
+
+# ------------------------------------------------------------- decode step ----
+
+def run_decode8(E, b, kc, vc, k_scale, v_scale, interleaved=0, ws=None):
+    table = torch.from_numpy(b.block_table).cuda()
+    desc = U.make_desc(E, b, table)
+    q = U.dev_bits(b.q_new)
+    kcd, vcd = dev_u8(kc), dev_u8(vc)
+    out = torch.full(q.shape, 0x7FC1, dtype=torch.int16, device="cuda")
+    nbytes = E.efim_decode_workspace_bytes(desc)
+    if ws is None:
+        ws = torch.full((max(nbytes, 256),), 0xA5, dtype=torch.uint8, device="cuda")
+    assert ws.numel() >= nbytes
+    E.efim_decode_step_fp8(desc, q, U.dev_bits(b.k_new), U.dev_bits(b.v_new), kcd, vcd, out, b.rope_base, interleaved,
+                           0.0, k_scale, v_scale, ws, ws.numel())
+    torch.cuda.synchronize()
+    assert np.array_equal(U.host_bits(q), b.q_new), "q must stay as given"
+    return U.host_bits(out), kcd.cpu().numpy(), vcd.cpu().numpy(), ws
+
+
+DECODE_CASES = [
+    ("gqa_ragged", [0, 1, 15, 16, 17, 63, 64, 300, 1000, 2047], (8, 2), 128, 0, 16),
+    ("mha",        [5, 129, 640],                            (4, 4), 128, 1, 16),
+    ("d64",        [0, 100, 1025, 48],                       (8, 4), 64, 0, 16),
+    ("page64",     [63, 64, 255, 3000],                      (8, 2), 128, 0, 64),
+]
+
+
+@pytest.mark.parametrize("row_tile,split", [(0, -1), (0, 64), (256, 128)])
+@pytest.mark.parametrize("name,cached,heads,d,interleaved,page_size", DECODE_CASES)
+def test_fp8_decode_step(E, name, cached, heads, d, interleaved, page_size, row_tile, split):
+    k_scale, v_scale = 0.0123, 0.031
+    c = np.array(cached, dtype=np.int32)
+    b = W.make_batch("c1", seed=650 + len(cached), lengths=(c, np.ones_like(c)), heads=heads, head_dim=d,
+                     page_size=page_size)
+    kc, vc = oracle_cache8(b, k_scale, v_scale)
+    _, kc_ref, vc_ref, ref = oracle_step8(b, kc, vc, k_scale, v_scale, bool(interleaved))
+    E.efim_set_tuning(E.EFIM_TUNE_ROW_TILE, row_tile)
+    E.efim_set_tuning(E.EFIM_TUNE_SPLIT_KV, split)
+    try:
+        got, kc_got, vc_got, ws = run_decode8(E, b, kc, vc, k_scale, v_scale, interleaved)
+        got2, _, _, _ = run_decode8(E, b, kc, vc, k_scale, v_scale, interleaved, ws=ws)
+    finally:
+        E.efim_set_tuning(E.EFIM_TUNE_ROW_TILE, 0)
+        E.efim_set_tuning(E.EFIM_TUNE_SPLIT_KV, -1)
+    assert np.array_equal(kc_got, kc_ref) and np.array_equal(vc_got, vc_ref), "cache append must be byte-exact"
+    U.assert_close(got, ref, name)
+    assert np.array_equal(got, got2)
+
+
+def test_fp8_decode_sequence(E):
+    """Six consecutive decode steps: codes and outputs follow the oracle step by step."""
+    heads, d, steps = (8, 2), 128, 6
+    k_scale, v_scale = 0.02, 0.05
+    c0 = np.array([14, 250, 1023], dtype=np.int32)
+    roomy = W.make_batch("c1", seed=92, lengths=(c0, np.full_like(c0, steps)), heads=heads, head_dim=d)
+    kc_ref, vc_ref = oracle_cache8(roomy, k_scale, v_scale)
+    kc_dev, vc_dev = kc_ref.copy(), vc_ref.copy()
+    ws = torch.full((8 << 20,), 0x5A, dtype=torch.uint8, device="cuda")
+    for s in range(steps):
+        b = W.make_batch("c1", seed=300 + s, lengths=(c0 + s, np.ones_like(c0)), heads=heads, head_dim=d,
+                         with_history=False)
+        b.block_table, b.num_pages = roomy.block_table, roomy.num_pages
+        _, kc_ref, vc_ref, ref = oracle_step8(b, kc_ref, vc_ref, k_scale, v_scale)
+        got, kc_dev, vc_dev, ws = run_decode8(E, b, kc_dev, vc_dev, k_scale, v_scale, ws=ws)
+        assert np.array_equal(kc_dev, kc_ref) and np.array_equal(vc_dev, vc_ref), "step %d" % s
+        U.assert_close(got, ref, "step %d" % s)
+
+
+def test_fp8_calls_reject_bad_scales(E):
+    b = W.make_batch("c1", lengths=(np.array([4], dtype=np.int32), np.array([1], dtype=np.int32)), heads=(4, 4), head_dim=64)
+    table = torch.from_numpy(b.block_table).cuda()
+    desc = U.make_desc(E, b, table)
+    for bad in (0.0, -1.0, float("nan"), float("inf")):
+        with pytest.raises(E.EfimError):
+            E.efim_rope_append_fp8(desc, None, 1, 1, 1, 1, 1e4, 0, bad, 1.0)
+        with pytest.raises(E.EfimError):
+            E.efim_extend_attention_fp8(desc, 1, 1, 1, 1, 0.0, 1.0, bad, 1, 256)
+        with pytest.raises(E.EfimError):
+            E.efim_decode_step_fp8(desc, 1, 1, 1, 1, 1, 1, 1e4, 0, 0.0, bad, 1.0, 1, 256)

@@ -28,7 +28,7 @@ def _desc(c, n, hq=4, hkv=2, d=128, page=16, table=FAKE_DEV, max_pages=None, num
 
 def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "efim.h")).read()
-    declared = set(re.findall(r"\b(efim_[a-z_]+)\s*\(", header))
+    declared = set(re.findall(r"\b(efim_[a-z0-9_]+)\s*\(", header))
     assert declared, "no declarations found"
     lib = ctypes.CDLL(E.LIBRARY_PATH)
     for name in declared:
