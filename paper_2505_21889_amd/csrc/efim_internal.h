@@ -54,6 +54,7 @@ Tuning& tuning();
 
 struct Plan {
   int rows_per_item = 128;  // query rows per workgroup tile (32 per wave)
+  int max_item_rows = 0;    // largest row_count of a work item
   std::vector<ReqInfo> reqs;
   std::vector<WorkItem> items;
   std::vector<MergeItem> merges;

@@ -80,10 +80,10 @@ struct AttnParams {
 
 constexpr float kSlack = 8.f;  // log2 units by which a row max may outgrow its reference
 
+// Plain nested maxima: the compiler turns them into three-operand max instructions itself and,
+// unlike for hand-written assembly, inserts the wait states a read of fresh MFMA results needs.
 __device__ __forceinline__ float max3(float a, float b, float c) {
-  float r;
-  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
-  return r;
+  return __builtin_fmaxf(__builtin_fmaxf(a, b), c);
 }
 
 // max / sum of a value with the one held by the lane 32 positions away (the two halves of a
@@ -220,8 +220,14 @@ __device__ __forceinline__ void merge_rows(const AttnParams& p, const MergeItem&
 //
 // KV8: the caches hold E4M3 codes.  The stages then hold code tiles (half the size) and one
 // more bf16 K/V tile, in front of them, receives the converted tile the products run on.
-template <int D, int WAVES, int STAGES, bool FUSED, bool KV8>
+//
+// KP ("key parallel"): every work item of the launch has at most 32 query rows (decode steps,
+// short increments).  One wave would be busy and the others idle: instead waves 0 and 1 both
+// take all the rows and one 32-key half of every key tile each, with their own running max and
+// sums, and their partial results are combined through LDS at the end.
+template <int D, int WAVES, int STAGES, bool FUSED, bool KV8, bool KP>
 __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const AttnParams p) {
+  static_assert(KP || !FUSED, "the decode step has at most 32 rows per tile");
   using G = Geometry<D>;
   // geometry of the gather: rows as they lie in the cache
   constexpr int kGRowBytes = KV8 ? D : 2 * D;
@@ -254,8 +260,10 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
   const int hi = lane >> 5;
   const int g = p.group;
 
+  const int wave_row0 = KP ? 0 : wave * 32;
+
   // --- this lane's query row (column of S^T / O^T) ----------------------------------
-  const int local_row = wave * 32 + i32;
+  const int local_row = wave_row0 + i32;
   const bool row_ok = local_row < it.row_count;
   const int row = it.row_begin + local_row;
   const int tok = row / g;
@@ -264,9 +272,9 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
   const int64_t q_off =
       ((int64_t)(rq.row_start + tok) * p.num_q_heads + it.kv_head * g + head_in_group) * D;
 
-  const bool wave_active = wave * 32 < it.row_count;
-  const int wave_first_row = it.row_begin + wave * 32;
-  const int wave_last_row = it.row_begin + min(it.row_count, wave * 32 + 32) - 1;
+  bool wave_active = wave_row0 < it.row_count;
+  const int wave_first_row = it.row_begin + wave_row0;
+  const int wave_last_row = it.row_begin + min(it.row_count, wave_row0 + 32) - 1;
   const int wave_min_vis = rq.cached + wave_first_row / g + 1;
   const int wave_max_vis = rq.cached + wave_last_row / g + 1;
 
@@ -509,8 +517,80 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
     }
   };
 
+  // One 32-key half (kb = 0 or 1, wave-uniform) of a tile, same products and softmax as
+  // compute_tile on that half alone.
+  auto compute_half = [&](int t, const char* ks, const char* vs, int kb) {
+    const int key0 = k_begin + t * kKeyTile + kb * 32;
+    f32x16 sc;
+    u32x4 ka[G::kSteps];
+    const char* krow = ks + k_row_off + kb * 32 * G::kRowBytes;
+#pragma unroll
+    for (int st = 0; st < G::kSteps; ++st)
+      ka[st] = *reinterpret_cast<const u32x4*>(krow + (((2 * st + hi) ^ k_swz) << 4));
+#pragma unroll
+    for (int r = 0; r < 16; ++r) sc[r] = 0.f;
+#pragma unroll
+    for (int st = 0; st < G::kSteps; ++st)
+      sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ka[st]), qb[st], sc, 0, 0, 0);
+    bf16x4 va[2][G::kDBlocks][2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const char* vrow = vs + ((kb * 2 + h) * 16 + v_key) * G::kRowBytes + v_sub;
+#pragma unroll
+      for (int d = 0; d < G::kDBlocks; ++d) {
+        const int off = ((d * 4 + v_chunk) ^ v_swz) << 4;
+        va[h][d][0] = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))(vrow + off));
+        va[h][d][1] = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))(vrow + 8 * G::kRowBytes + off));
+      }
+    }
+    if (key0 + 32 > wave_min_vis) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int key = key0 + (r >> 2) * 8 + hi * 4 + (r & 3);
+        if (key >= n_vis) sc[r] = -INFINITY;
+      }
+    }
+    float tmax = max3(sc[0], sc[1], sc[2]);
+#pragma unroll
+    for (int r = 3; r < 15; r += 2) tmax = max3(tmax, sc[r], sc[r + 1]);
+    tmax = cross_half_max(fmaxf(tmax, sc[15]));
+    const float m_new = tmax * p.scale_log2;
+    if (__any(m_new > m_run + kSlack)) {
+      const float m_next = fmaxf(m_run, m_new);
+      const float m_safe = (m_next == -INFINITY) ? 0.f : m_next;
+      const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);
+      l_run *= alpha;
+#pragma unroll
+      for (int d = 0; d < G::kDBlocks; ++d)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[d][r] *= alpha;
+      m_run = m_next;
+    }
+    const float m_use = (m_run == -INFINITY) ? 0.f : m_run;
+    float psum = 0.f;
+    bf16x8 pb[2];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const float e = __builtin_amdgcn_exp2f(sc[r] * p.scale_log2 - m_use);
+      psum += e;
+      pb[r >> 3][r & 7] = (__bf16)e;
+    }
+    l_run += psum;
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+      for (int d = 0; d < G::kDBlocks; ++d) {
+        const bf16x8 a = __builtin_shufflevector(va[h][d][0], va[h][d][1], 0, 1, 2, 3, 4, 5, 6, 7);
+        o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[h], o[d], 0, 0, 0);
+      }
+  };
+
   auto step = [&](int t, const char* ks, const char* vs) {
-    if (wave_active && k_begin + t * kKeyTile < wave_max_vis) compute_tile(t, ks, vs);
+    if constexpr (KP) {
+      if (wave < 2 && k_begin + t * kKeyTile + wave * 32 < wave_max_vis) compute_half(t, ks, vs, wave);
+    } else {
+      if (wave_active && k_begin + t * kKeyTile < wave_max_vis) compute_tile(t, ks, vs);
+    }
   };
   // Loop top for tile t: the gathers of up to STAGES - 2 later tiles (this wave's newest
   // loads) may stay in flight; everything older must have landed.  The barrier publishes tile
@@ -628,6 +708,63 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
         }
       }
     }
+  }
+
+  // --- waves that shared the rows: combine their results in wave 0 ---------------------
+  // With M = max_w m_w every wave rescales its sums by 2^(m_w - M); then the upper half of the
+  // waves hands its sums to the lower half through LDS, halving until wave 0 holds the total.
+  if constexpr (KP) {
+    // (no fused multiply-add here: whether the rescaling and the sums below end up fused would
+    // depend on how each variant of the kernel is scheduled, and the variants must agree bit
+    // for bit)
+#pragma clang fp contract(off)
+    constexpr int kRegs = G::kDBlocks * 16;
+    float* xo = reinterpret_cast<float*>(lds);          // [WAVES / 2][kRegs / 4][64 lanes] x 4 floats
+    float* xm = xo + (WAVES / 2) * kRegs * 64;          // [WAVES][64]
+    float* xl = xm + WAVES * 64;                        // [WAVES / 2][64]
+    static_assert(((WAVES / 2) * kRegs * 64 + WAVES * 64 + (WAVES / 2) * 64) * 4 <= (int)sizeof(lds),
+                  "the exchange area must fit the tile buffers");
+    __syncthreads();  // every wave is done with the tiles
+    xm[wave * 64 + lane] = m_run;
+    __syncthreads();
+    float m_all = xm[lane];
+#pragma unroll
+    for (int w = 1; w < WAVES; ++w) m_all = fmaxf(m_all, xm[w * 64 + lane]);
+    const float sc = (m_run == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m_run - m_all);
+    l_run *= sc;
+#pragma unroll
+    for (int d = 0; d < G::kDBlocks; ++d)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) o[d][r] *= sc;
+    m_run = m_all;
+#pragma unroll
+    for (int half = WAVES / 2; half >= 1; half >>= 1) {
+      if (wave >= half && wave < 2 * half) {
+        float* dst = xo + (wave - half) * kRegs * 64;
+#pragma unroll
+        for (int d = 0; d < G::kDBlocks; ++d)
+#pragma unroll
+          for (int rr = 0; rr < 4; ++rr)
+            *reinterpret_cast<f32x4*>(dst + ((d * 4 + rr) * 64 + lane) * 4) =
+                f32x4{o[d][rr * 4], o[d][rr * 4 + 1], o[d][rr * 4 + 2], o[d][rr * 4 + 3]};
+        xl[(wave - half) * 64 + lane] = l_run;
+      }
+      __syncthreads();
+      if (wave < half) {
+        const float* src = xo + wave * kRegs * 64;
+#pragma unroll
+        for (int d = 0; d < G::kDBlocks; ++d)
+#pragma unroll
+          for (int rr = 0; rr < 4; ++rr) {
+            const f32x4 v = *reinterpret_cast<const f32x4*>(src + ((d * 4 + rr) * 64 + lane) * 4);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) o[d][rr * 4 + e] += v[e];
+          }
+        l_run += xl[wave * 64 + lane];
+      }
+      __syncthreads();
+    }
+    wave_active = wave == 0;
   }
 
   // --- epilogue ---------------------------------------------------------------------
@@ -762,12 +899,20 @@ bool use_tickets(const Plan& plan, bool decode) {
   return want && !plan.merges.empty() && plan.merges.size() <= (size_t)kTicketsPerSlot;
 }
 
+// few_rows: no work item has more than 32 query rows (always so for the decode step)
 template <bool FUSED>
-void launch_kernel(int head_dim, bool wide, bool fp8, dim3 grid, const AttnParams& p, hipStream_t stream) {
-#define EFIM_ATTN_LAUNCH(DD, F8)                                                                   \
+void launch_kernel(int head_dim, bool wide, bool fp8, bool few_rows, dim3 grid, const AttnParams& p,
+                   hipStream_t stream) {
+#define EFIM_ATTN_LAUNCH2(DD, F8, KP)                                                              \
   do {                                                                                             \
-    if (wide) extend_attention_kernel<DD, 8, 3, FUSED, F8><<<grid, 512, 0, stream>>>(p);           \
-    else extend_attention_kernel<DD, 4, 2, FUSED, F8><<<grid, 256, 0, stream>>>(p);                \
+    if (wide) extend_attention_kernel<DD, 8, 3, FUSED, F8, KP><<<grid, 512, 0, stream>>>(p);       \
+    else extend_attention_kernel<DD, 4, 2, FUSED, F8, KP><<<grid, 256, 0, stream>>>(p);            \
+  } while (0)
+#define EFIM_ATTN_LAUNCH(DD, F8)                                               \
+  do {                                                                         \
+    if constexpr (FUSED) EFIM_ATTN_LAUNCH2(DD, F8, true);                      \
+    else if (few_rows) EFIM_ATTN_LAUNCH2(DD, F8, true);                        \
+    else EFIM_ATTN_LAUNCH2(DD, F8, FUSED);                                     \
   } while (0)
   if (head_dim == 128) {
     if (fp8) EFIM_ATTN_LAUNCH(128, true); else EFIM_ATTN_LAUNCH(128, false);
@@ -775,6 +920,7 @@ void launch_kernel(int head_dim, bool wide, bool fp8, dim3 grid, const AttnParam
     if (fp8) EFIM_ATTN_LAUNCH(64, true); else EFIM_ATTN_LAUNCH(64, false);
   }
 #undef EFIM_ATTN_LAUNCH
+#undef EFIM_ATTN_LAUNCH2
 }
 
 int launch_merge(const efim_batch_t* b, const Plan& plan, const AttnParams& p, hipStream_t stream) {
@@ -799,7 +945,7 @@ int launch_extend_attention(const efim_batch_t* b, const Plan& plan, const char*
   const Tuning& tn = tuning();
   if (tn.ev_start) (void)hipEventRecord(tn.ev_start, stream);
   const bool wide = plan.rows_per_item == 256;
-  launch_kernel<false>(b->head_dim, wide, fmt.fp8, grid, p, stream);
+  launch_kernel<false>(b->head_dim, wide, fmt.fp8, plan.max_item_rows <= 32, grid, p, stream);
   hipError_t e = hipGetLastError();
   if (tn.ev_stop) (void)hipEventRecord(tn.ev_stop, stream);
   if (e != hipSuccess) { set_last_hip_error(e); return EFIM_ERR_LAUNCH; }
@@ -826,7 +972,7 @@ int launch_decode_step(const efim_batch_t* b, const Plan& plan, const char* head
   const Tuning& tn = tuning();
   if (tn.ev_start) (void)hipEventRecord(tn.ev_start, stream);
   const bool wide = plan.rows_per_item == 256;
-  launch_kernel<true>(D, wide, fmt.fp8, grid, p, stream);
+  launch_kernel<true>(D, wide, fmt.fp8, true, grid, p, stream);
   hipError_t e = hipGetLastError();
   if (tn.ev_stop) (void)hipEventRecord(tn.ev_stop, stream);
   if (e != hipSuccess) { set_last_hip_error(e); return EFIM_ERR_LAUNCH; }

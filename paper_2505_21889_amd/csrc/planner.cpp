@@ -293,6 +293,9 @@ void build_plan(const efim_batch_t* b, int num_slots, Plan* plan) {
     while (!plan->items.empty() && plan->items.back().row_count == 0) plan->items.pop_back();
   }
 
+  plan->max_item_rows = 0;
+  for (const WorkItem& w : plan->items) plan->max_item_rows = std::max(plan->max_item_rows, (int)w.row_count);
+
   // Layout of the staged header and of the device workspace.
   size_t off = 0;
   plan->off_reqs = off;

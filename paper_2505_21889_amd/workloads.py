@@ -227,19 +227,21 @@ def attention_flops(batch):
     return 4 * batch.head_dim * batch.num_q_heads * pairs
 
 
-def attention_bytes(batch):
+def attention_bytes(batch, kv_elem_bytes=2):
     """Algorithmic HBM bytes of extend attention: K and V of every visible
-    position once per kv head, Q in and O out, and the block-table entries."""
+    position once per kv head (kv_elem_bytes per element: 2 for a bf16 cache, 1 for
+    an 8-bit one), Q in and O out, and the block-table entries."""
     c = batch.cached_len.astype(np.int64)
     n = batch.new_len.astype(np.int64)
     live = n > 0
-    kv = int(((c + n) * live).sum()) * 2 * batch.num_kv_heads * batch.head_dim * 2
+    kv = int(((c + n) * live).sum()) * 2 * batch.num_kv_heads * batch.head_dim * kv_elem_bytes
     qo = int(n.sum()) * 2 * batch.num_q_heads * batch.head_dim * 2
     bt = int((-(-(c + n) // batch.page_size) * live).sum()) * 4
     return kv + qo + bt
 
 
-def rope_append_bytes(batch):
-    """Algorithmic HBM bytes of rope_append: read q, k, v; write q, K, V."""
+def rope_append_bytes(batch, kv_elem_bytes=2):
+    """Algorithmic HBM bytes of rope_append: read q, k, v; write q, K, V (the cache entries
+    at kv_elem_bytes per element)."""
     t = batch.total_new
-    return 2 * t * (batch.num_q_heads + 2 * batch.num_kv_heads) * batch.head_dim * 2
+    return t * batch.head_dim * (4 * batch.num_q_heads + 2 * batch.num_kv_heads * (2 + kv_elem_bytes))
