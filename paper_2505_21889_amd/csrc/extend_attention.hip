@@ -16,11 +16,14 @@
 // Accumulation is fp32; partial results of split key ranges are merged by a second kernel or,
 // for the decode step, by the workgroup that finishes last.
 //
-// 8-bit caches (E4M3 codes, one scale per tensor): the gather moves the codes (half the bytes)
-// into staging buffers; once a tile has landed the workgroup converts it, every element once,
-// into a bf16 tile of the usual swizzled layout and the products run on that.  The codes'
-// values are exact in bf16; the key scale is folded into the softmax scale and the value scale
-// into the final normalisation.
+// 8-bit caches (E4M3 codes, one scale per tensor): the gather moves the codes (half the bytes).
+// Key codes are read from the landed tile as they are and converted to bf16 operands in
+// registers (eight codes per lane and MFMA); value codes, which the PV product needs
+// transposed, are converted once per workgroup into a bf16 tile of the usual swizzled layout.
+// The codes' values are exact in bf16; the key scale is folded into the softmax scale and the
+// value scale into the final normalisation.
+#include <type_traits>
+
 #include "efim_internal.h"
 #include "fp8_math.h"
 #include "rope_math.h"
@@ -218,8 +221,8 @@ __device__ __forceinline__ void merge_rows(const AttnParams& p, const MergeItem&
 // (global q stays raw), the workgroup whose key range ends with the new token rotates its key,
 // stores key and value into the paged cache and patches them into its LDS tile.
 //
-// KV8: the caches hold E4M3 codes.  The stages then hold code tiles (half the size) and one
-// more bf16 K/V tile, in front of them, receives the converted tile the products run on.
+// KV8: the caches hold E4M3 codes.  The stages then hold code tiles (half the size, so one
+// more of them fits) and one bf16 V tile, in front of them, receives the converted values.
 //
 // KP ("key parallel"): every work item of the launch has at most 32 query rows (decode steps,
 // short increments).  One wave would be busy and the others idle: instead waves 0 and 1 both
@@ -237,17 +240,23 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
   constexpr int kGLoadsPerMatrix = kGTileBytes / 1024;  // wave loads per K (or V) tile
   // stage s: K tile at s * kStageBytes behind the compute tile (if any), V tile right behind it
   constexpr int kStageBytes = 2 * kGTileBytes;
-  constexpr int kComputeBytes = KV8 ? 2 * G::kTileBytes : 0;
-  static_assert(STAGES >= 2 && kComputeBytes + STAGES * kStageBytes <= 160 * 1024, "stages must fit the 160 KB LDS");
-  __shared__ __attribute__((aligned(1024))) char lds[kComputeBytes + STAGES * kStageBytes];
-  char* const stages = lds + kComputeBytes;
+  constexpr int kComputeBytes = KV8 ? G::kTileBytes : 0;  // bf16 V tile of the 8-bit variant
+  // chunk swizzle of a key-code row: the 8-byte operand reads of 32 keys spread over all banks
+  auto kswz8 = [](int row) { return D == 128 ? (row & 7) : ((row >> 1) & 3); };
   // fused decode step: the rotated query rows of the tile, the new token's rotated key and its
-  // value, cos/sin of the token's position, and the "this workgroup merges" flag
+  // value, cos/sin of the token's position -- behind the tile buffers
   constexpr int kFusedRows = 32;
-  __shared__ __attribute__((aligned(16))) uint16_t s_q[FUSED ? kFusedRows * D : 8];
-  __shared__ __attribute__((aligned(16))) uint16_t s_kv[FUSED ? 2 * D : 8];
-  __shared__ double s_cs[FUSED ? 128 : 1];
-  __shared__ int s_last;
+  constexpr int kTileBufBytes = kComputeBytes + STAGES * kStageBytes;
+  constexpr int kFusedBytes = FUSED ? kFusedRows * D * 2 + 2 * D * 2 + 128 * 8 : 0;
+  static_assert(STAGES >= 2 && kTileBufBytes + kFusedBytes <= 160 * 1024, "stages must fit the 160 KB LDS");
+  // One array, carved by hand.
+  __shared__ __attribute__((aligned(1024))) char lds[kTileBufBytes + kFusedBytes];
+  char* const stages = lds + kComputeBytes;
+  uint16_t* const s_q = reinterpret_cast<uint16_t*>(lds + kTileBufBytes);
+  uint16_t* const s_kv = s_q + kFusedRows * D;
+  double* const s_cs = reinterpret_cast<double*>(s_kv + 2 * D);
+  // the "this workgroup merges" flag is only used once the tile buffers are dead
+  int* const s_last = reinterpret_cast<int*>(lds);
 
   const WorkItem it = p.items[blockIdx.x];
   if (it.row_count == 0) return;
@@ -362,8 +371,8 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
         page = __builtin_amdgcn_ds_bpermute((((first_off + t * kKeyTile + tile_row) >> ps) & 63) << 2, pages_cur);
       const int64_t in_off = page * page_bytes + head_bytes + ((key0 + tile_row) & page_mask) * kGRowBytes;
       const int64_t row_off = (key0 + tile_row < k_end) ? in_off : last_off;
-      // code tiles stay row-major: the conversion pass applies the swizzles
-      const int swz = KV8 ? 0 : (is_v ? G::vswz(tile_row) : G::kswz(tile_row));
+      // value codes stay row-major: the conversion pass applies their swizzle
+      const int swz = KV8 ? (is_v ? 0 : kswz8(tile_row)) : (is_v ? G::vswz(tile_row) : G::kswz(tile_row));
       const char* src = (is_v ? vc : kc) + row_off + ((g_pc ^ swz) << 4);
       load_to_lds_16(src, (is_v ? vbuf : kbuf) + idx * 1024);
     }
@@ -372,6 +381,29 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
   // per-lane LDS offsets of the MFMA operands
   const int k_row_off = i32 * G::kRowBytes;
   const int k_swz = G::kswz(i32);
+  const int k8_swz = kswz8(i32);  // same for key i32 + 32
+  // K operand of key block kb, MFMA step st: 8 consecutive head-dim elements (2 * st + hi) * 8 ..
+  // of key kb * 32 + i32 -- 16 bytes of the bf16 tile, or 8 codes that become bf16 in registers
+  using KRaw = std::conditional_t<KV8, u32x2, u32x4>;
+  auto read_k = [&](const char* ks, int kb, int st) -> KRaw {
+    if constexpr (KV8)
+      return *reinterpret_cast<const u32x2*>(ks + (kb * 32 + i32) * D + ((st ^ k8_swz) << 4) + 8 * hi);
+    else
+      return *reinterpret_cast<const u32x4*>(ks + k_row_off + kb * 32 * G::kRowBytes + (((2 * st + hi) ^ k_swz) << 4));
+  };
+  auto k_operand = [&](KRaw raw) -> bf16x8 {
+    if constexpr (KV8) {
+      u32x4 v;
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        v[2 * j] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(raw[j], 1.0f, false));
+        v[2 * j + 1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(raw[j], 1.0f, true));
+      }
+      return __builtin_bit_cast(bf16x8, v);
+    } else {
+      return __builtin_bit_cast(bf16x8, raw);
+    }
+  };
   // 16-lane block b of the wave reads a 4-key x 16-d patch of V through the transposing
   // read; lane w of the block supplies the address of key w/4, d-offset 4*(w%4) and receives
   // column w of the patch (4 consecutive keys of one d).
@@ -390,21 +422,18 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
     // V^T operands of the PV product stream in under the second chain, so that by the time
     // the softmax is done they are all in registers.
     f32x16 s[2];
-    u32x4 ka[2][G::kSteps];
-    const char* krow = ks + k_row_off;
+    KRaw ka[2][G::kSteps];
 #pragma unroll
-    for (int st = 0; st < G::kSteps; ++st)
-      ka[0][st] = *reinterpret_cast<const u32x4*>(krow + (((2 * st + hi) ^ k_swz) << 4));
+    for (int st = 0; st < G::kSteps; ++st) ka[0][st] = read_k(ks, 0, st);
 #pragma unroll
-    for (int st = 0; st < G::kSteps; ++st)
-      ka[1][st] = *reinterpret_cast<const u32x4*>(krow + 32 * G::kRowBytes + (((2 * st + hi) ^ k_swz) << 4));
+    for (int st = 0; st < G::kSteps; ++st) ka[1][st] = read_k(ks, 1, st);
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) s[kb][r] = 0.f;
 #pragma unroll
       for (int st = 0; st < G::kSteps; ++st)
-        s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ka[kb][st]), qb[st], s[kb], 0, 0, 0);
+        s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k_operand(ka[kb][st]), qb[st], s[kb], 0, 0, 0);
     }
     bf16x4 va[4][G::kDBlocks][2];
     auto read_v = [&](int ks4) {
@@ -489,31 +518,30 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
     }
   };
 
-  // 8-bit caches: the landed code tile (K rows, then V rows, row-major) becomes the bf16 tile
-  // at the front of the LDS, in the swizzled layout compute_tile reads.  A thread takes 16
-  // codes at a time: one 16-byte read, eight two-at-a-time conversions, two 16-byte writes.
+  // 8-bit caches: the landed value codes (row-major) become the bf16 V tile at the front of the
+  // LDS, in the swizzled layout the transposing reads expect.  A thread takes 16 codes at a
+  // time: one 16-byte read, eight two-at-a-time conversions, two 16-byte writes.
   auto convert_tile = [&](const char* codes) {
-    constexpr int kUnitsPerMatrix = kKeyTile * kGChunks;
+    constexpr int kUnits = kKeyTile * kGChunks;
 #pragma unroll
-    for (int u0 = 0; u0 < 2 * kUnitsPerMatrix; u0 += 64 * WAVES) {
+    for (int u0 = 0; u0 < kUnits; u0 += 64 * WAVES) {
       const int u = u0 + tid;
-      const bool is_v = u >= kUnitsPerMatrix;
-      const int idx = is_v ? u - kUnitsPerMatrix : u;
-      const int row = idx / kGChunks;
-      const int c = idx - row * kGChunks;
+      if (kUnits % (64 * WAVES) != 0 && u >= kUnits) break;
+      const int row = u / kGChunks;
+      const int c = u - row * kGChunks;
       const u32x4 w = *reinterpret_cast<const u32x4*>(codes + u * 16);
-      u32x4 lo, hi;
+      u32x4 lo, hi4;
 #pragma unroll
       for (int j = 0; j < 2; ++j) {
         lo[2 * j] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w[j], 1.0f, false));
         lo[2 * j + 1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w[j], 1.0f, true));
-        hi[2 * j] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w[2 + j], 1.0f, false));
-        hi[2 * j + 1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w[2 + j], 1.0f, true));
+        hi4[2 * j] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w[2 + j], 1.0f, false));
+        hi4[2 * j + 1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w[2 + j], 1.0f, true));
       }
-      const int swz = is_v ? G::vswz(row) : G::kswz(row);
-      char* dst = lds + (is_v ? G::kTileBytes : 0) + row * G::kRowBytes;
+      const int swz = G::vswz(row);
+      char* dst = lds + row * G::kRowBytes;
       *reinterpret_cast<u32x4*>(dst + (((2 * c) ^ swz) << 4)) = lo;
-      *reinterpret_cast<u32x4*>(dst + (((2 * c + 1) ^ swz) << 4)) = hi;
+      *reinterpret_cast<u32x4*>(dst + (((2 * c + 1) ^ swz) << 4)) = hi4;
     }
   };
 
@@ -522,16 +550,14 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
   auto compute_half = [&](int t, const char* ks, const char* vs, int kb) {
     const int key0 = k_begin + t * kKeyTile + kb * 32;
     f32x16 sc;
-    u32x4 ka[G::kSteps];
-    const char* krow = ks + k_row_off + kb * 32 * G::kRowBytes;
+    KRaw ka[G::kSteps];
 #pragma unroll
-    for (int st = 0; st < G::kSteps; ++st)
-      ka[st] = *reinterpret_cast<const u32x4*>(krow + (((2 * st + hi) ^ k_swz) << 4));
+    for (int st = 0; st < G::kSteps; ++st) ka[st] = read_k(ks, kb, st);
 #pragma unroll
     for (int r = 0; r < 16; ++r) sc[r] = 0.f;
 #pragma unroll
     for (int st = 0; st < G::kSteps; ++st)
-      sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ka[st]), qb[st], sc, 0, 0, 0);
+      sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k_operand(ka[st]), qb[st], sc, 0, 0, 0);
     bf16x4 va[2][G::kDBlocks][2];
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
@@ -684,7 +710,7 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
               const int c = is_v ? w - kGChunks : w;
               const u32x4 val =
                   *reinterpret_cast<const u32x4*>(reinterpret_cast<const char*>(s_kv) + (is_v ? kGRowBytes : 0) + c * 16);
-              const int swz = KV8 ? 0 : (is_v ? G::vswz(row) : G::kswz(row));
+              const int swz = KV8 ? (is_v ? 0 : kswz8(row)) : (is_v ? G::vswz(row) : G::kswz(row));
               char* tile = stages + s0 * kStageBytes + (is_v ? kGTileBytes : 0);
               *reinterpret_cast<u32x4*>(tile + row * kGRowBytes + ((c ^ swz) << 4)) = val;
               if (row == prow) {
@@ -698,11 +724,11 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
           }
         }
         if constexpr (KV8) {
-          // every wave is done with the previous bf16 tile (loop-top barrier); the second
+          // every wave is done with the previous bf16 V tile (loop-top barrier); the second
           // barrier publishes the converted one
-          convert_tile(stages + s0 * kStageBytes);
+          convert_tile(stages + s0 * kStageBytes + kGTileBytes);
           __syncthreads();
-          step(t, lds, lds + G::kTileBytes);
+          step(t, stages + s0 * kStageBytes, lds);
         } else {
           step(t, stages + s0 * kStageBytes, stages + s0 * kStageBytes + kGTileBytes);
         }
@@ -722,7 +748,7 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
     float* xo = reinterpret_cast<float*>(lds);          // [WAVES / 2][kRegs / 4][64 lanes] x 4 floats
     float* xm = xo + (WAVES / 2) * kRegs * 64;          // [WAVES][64]
     float* xl = xm + WAVES * 64;                        // [WAVES / 2][64]
-    static_assert(((WAVES / 2) * kRegs * 64 + WAVES * 64 + (WAVES / 2) * 64) * 4 <= (int)sizeof(lds),
+    static_assert(((WAVES / 2) * kRegs * 64 + WAVES * 64 + (WAVES / 2) * 64) * 4 <= kTileBufBytes,
                   "the exchange area must fit the tile buffers");
     __syncthreads();  // every wave is done with the tiles
     xm[wave * 64 + lane] = m_run;
@@ -825,9 +851,9 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
     __syncthreads();
     if (tid == 0)
-      s_last = __hip_atomic_fetch_add(ticket, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == mi.nsplit - 1;
+      *s_last = __hip_atomic_fetch_add(ticket, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == mi.nsplit - 1;
     __syncthreads();
-    if (s_last) {
+    if (*s_last) {
       merge_rows<D, true>(p, mi, rq, tid, 64 * WAVES);
       if (tid == 0) __hip_atomic_store(ticket, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
@@ -905,8 +931,8 @@ void launch_kernel(int head_dim, bool wide, bool fp8, bool few_rows, dim3 grid, 
                    hipStream_t stream) {
 #define EFIM_ATTN_LAUNCH2(DD, F8, KP)                                                              \
   do {                                                                                             \
-    if (wide) extend_attention_kernel<DD, 8, 3, FUSED, F8, KP><<<grid, 512, 0, stream>>>(p);       \
-    else extend_attention_kernel<DD, 4, 2, FUSED, F8, KP><<<grid, 256, 0, stream>>>(p);            \
+    if (wide) extend_attention_kernel<DD, 8, F8 ? 4 : 3, FUSED, F8, KP><<<grid, 512, 0, stream>>>(p); \
+    else extend_attention_kernel<DD, 4, F8 ? 3 : 2, FUSED, F8, KP><<<grid, 256, 0, stream>>>(p);   \
   } while (0)
 #define EFIM_ATTN_LAUNCH(DD, F8)                                               \
   do {                                                                         \
