@@ -74,8 +74,12 @@ int stage_plan(const Plan& plan, StageSlot** slot_out, const char** dev_header) 
     s.capacity = cap;
   }
   char* h = static_cast<char*>(s.host);
-  std::memcpy(h + plan.off_reqs, plan.reqs.data(), plan.reqs.size() * sizeof(ReqInfo));
-  std::memcpy(h + plan.off_items, plan.items.data(), plan.items.size() * sizeof(WorkItem));
+  DevItem* items = reinterpret_cast<DevItem*>(h + plan.off_items);
+  for (size_t i = 0; i < plan.items.size(); ++i) {
+    const WorkItem& w = plan.items[i];
+    const ReqInfo& rq = plan.reqs[w.row_count > 0 ? w.req : 0];
+    items[i] = DevItem{w, rq.cached, rq.row_start, 0, 0};
+  }
   if (!plan.merges.empty())
     std::memcpy(h + plan.off_merges, plan.merges.data(), plan.merges.size() * sizeof(MergeItem));
   *slot_out = &s;

@@ -27,8 +27,19 @@ struct ReqInfo {
   int32_t pad;
 };
 
-// Device-side work item: identical fields to efim_work_item_t.
+// Work item as planned: identical fields to efim_work_item_t.
 using WorkItem = efim_work_item_t;
+
+// Work item as staged for the device: the planned fields plus what the kernel needs of the
+// item's request, so that a workgroup starts with ONE read of the staged work list (the list
+// lives in host memory, and every dependent read of it is a trip over the host link).
+struct DevItem {
+  WorkItem w;
+  int32_t cached;     // C_r
+  int32_t row_start;  // first packed new-token row of the request
+  int32_t pad0, pad1;
+};
+static_assert(sizeof(DevItem) == 48, "three 16-byte reads");
 
 // One query tile whose key range was split: `nsplit` partial results in consecutive slots.
 struct MergeItem {
@@ -38,7 +49,8 @@ struct MergeItem {
   int32_t row_count;
   int32_t first_slot;
   int32_t nsplit;
-  int32_t pad0, pad1;
+  int32_t row_start;  // first packed new-token row of the request
+  int32_t pad1;
 };
 
 struct Tuning {
@@ -59,8 +71,8 @@ struct Plan {
   std::vector<WorkItem> items;
   std::vector<MergeItem> merges;
   int64_t num_partial_slots = 0;
-  // byte offsets of reqs / items / merges inside the staged plan header
-  size_t off_reqs = 0, off_items = 0, off_merges = 0, header_bytes = 0;
+  // byte offsets of the items (as DevItem) and merges inside the staged plan header
+  size_t off_items = 0, off_merges = 0, header_bytes = 0;
   // byte offsets of the split-KV partial results inside the device workspace, and its size
   size_t off_part_o = 0, off_part_ml = 0, total_bytes = 0;
 };
@@ -84,7 +96,7 @@ int launch_rope_append(const efim_batch_t* b, int64_t total_new, void* q, const 
                        const void* v_new, void* k_cache, void* v_cache, const double* inv_freq,
                        int rotary_dim, int interleaved, const CacheFormat& fmt, hipStream_t stream);
 
-// `header` is the device-visible address of the staged plan header (reqs, items, merges at
+// `header` is the device-visible address of the staged plan header (items, merges at
 // the plan's offsets); `workspace` holds the split-KV partial results.
 // `stage_slot` is the index of the staging slot that holds the header: it selects the launch's
 // block of arrival counters.

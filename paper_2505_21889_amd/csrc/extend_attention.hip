@@ -49,8 +49,7 @@ typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 #define GLOBAL_PTR(T) __attribute__((address_space(1))) T*
 
 struct AttnParams {
-  const ReqInfo* reqs;
-  const WorkItem* items;
+  const DevItem* items;
   const uint16_t* q;
   const uint16_t* k_cache;
   const uint16_t* v_cache;
@@ -101,18 +100,29 @@ __device__ __forceinline__ float cross_half_sum(float v) {
   return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
-// Direct HBM -> LDS copy of 16 bytes per lane: lane l's data lands at lds_base + 16 * l
-// (lds_base is wave-uniform and travels in M0).  Issued as inline assembly so that the
+// Direct HBM -> LDS copy of 16 bytes per lane: lane l's data lands at lds_addr + 16 * l
+// (lds_addr, the wave-uniform LDS byte address, travels in M0).  Issued as inline assembly so that the
 // compiler does not order LDS reads of OTHER buffers behind it; completion is awaited
 // explicitly with s_waitcnt vmcnt before the workgroup barrier that publishes the buffer.
-__device__ __forceinline__ void load_to_lds_16(const void* gptr, const void* lds_base) {
-  const uint32_t lds_addr = (uint32_t)(uintptr_t)(LDS_PTR(const char))lds_base;
+__device__ __forceinline__ void load_to_lds_16(const void* gptr, uint32_t lds_addr) {
   asm volatile(
       "s_mov_b32 m0, %0\n\t"
       "s_nop 0\n\t"
       "global_load_lds_dwordx4 %1, off"
       :
       : "s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(gptr)
+      : "memory");
+}
+
+// The same with the address split into a wave-uniform base (scalar registers) and a 32-bit
+// per-lane offset: no vector arithmetic on 64-bit addresses in front of the load.
+__device__ __forceinline__ void load_to_lds_16(const void* base, uint32_t lane_off, uint32_t lds_addr) {
+  asm volatile(
+      "s_mov_b32 m0, %0\n\t"
+      "s_nop 0\n\t"
+      "global_load_lds_dwordx4 %1, %2"
+      :
+      : "s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(lane_off), "s"(base)
       : "memory");
 }
 
@@ -150,7 +160,7 @@ __device__ __forceinline__ void load_coherent(const float* at, float* a, float* 
 // round trip per group instead of one per split); a later group rescales the running sums.
 // COHERENT: the partial results were written by other workgroups of the same launch.
 template <int D, bool COHERENT = false>
-__device__ __forceinline__ void merge_rows(const AttnParams& p, const MergeItem& mi, const ReqInfo& rq, int t,
+__device__ __forceinline__ void merge_rows(const AttnParams& p, const MergeItem& mi, int t,
                                            int nthreads, int row_lo = 0, int row_hi = 1 << 30) {
   constexpr int VEC = D / 4;  // float4 columns per row
   constexpr int GROUP = 8;
@@ -200,7 +210,7 @@ __device__ __forceinline__ void merge_rows(const AttnParams& p, const MergeItem&
     const int row = mi.row_begin + lr;
     const int tok = row / g;
     const int hg = row - tok * g;
-    uint16_t* dst = p.out + ((int64_t)(rq.row_start + tok) * p.num_q_heads + mi.kv_head * g + hg) * D + dv;
+    uint16_t* dst = p.out + ((int64_t)(mi.row_start + tok) * p.num_q_heads + mi.kv_head * g + hg) * D + dv;
     bf16x4 o4;
 #pragma unroll
     for (int e = 0; e < 4; ++e) o4[e] = (__bf16)(acc[e] * inv);
@@ -258,9 +268,12 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
   // the "this workgroup merges" flag is only used once the tile buffers are dead
   int* const s_last = reinterpret_cast<int*>(lds);
 
-  const WorkItem it = p.items[blockIdx.x];
+  const DevItem staged = p.items[blockIdx.x];
+  const WorkItem it = staged.w;
   if (it.row_count == 0) return;
-  const ReqInfo rq = p.reqs[it.req];
+  struct { int32_t cached, row_start; } rq;
+  rq.cached = staged.cached;
+  rq.row_start = staged.row_start;
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -339,13 +352,25 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
   // awaited by hand.  (vmcnt(0), expcnt/lgkmcnt untouched)
   __builtin_amdgcn_s_waitcnt(0x0F70);
 
-  // --- gather of one 64-key tile: the 2 * kLoadsPerMatrix 1 KB loads are dealt to the waves
-  constexpr int kLoadsPerWave = 2 * kGLoadsPerMatrix / WAVES;
-  static_assert(kLoadsPerWave * WAVES == 2 * kGLoadsPerMatrix, "loads must divide evenly");
+  // --- gather of one 64-key tile: the 2 * kLoadsPerMatrix 1 KB loads are dealt to the waves.
+  // In the four-wave key-parallel kernel waves 0 and 1 do the products and waves 2 and 3, which
+  // have no rows, issue all the loads: per tile the two jobs then overlap instead of adding up.
+  constexpr bool kSplitRoles = KP && WAVES == 4;
+  constexpr int kIssuers = kSplitRoles ? 2 : WAVES;
+  constexpr int kLoadsPerWave = 2 * kGLoadsPerMatrix / kIssuers;
+  static_assert(kLoadsPerWave * kIssuers == 2 * kGLoadsPerMatrix, "loads must divide evenly");
+  const int issuer = kSplitRoles ? wave - 2 : wave;  // negative: this wave issues no loads
   const int g_key = lane / kGChunks;  // key within one 1 KB load
   const int g_pc = lane % kGChunks;   // physical 16-byte chunk this lane fills
-  auto issue_tile = [&](int t, char* kbuf, char* vbuf) {
+  // LDS byte address of the tile buffers (kept as an integer: the loads take addresses, not
+  // pointers)
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(LDS_PTR(char))lds;
+  auto issue_tile = [&](int t, int stage) {
+    if (issuer < 0) return;
+    const uint32_t kbuf = lds0 + kComputeBytes + stage * kStageBytes;
+    const uint32_t vbuf = kbuf + kGTileBytes;
     const int key0 = k_begin + t * kKeyTile;
+    const bool full_tile = key0 + kKeyTile <= k_end;  // no row of the tile lies past the key range
     const int tile_page = (first_off + t * kKeyTile) >> ps;  // first page of the tile, relative to first_page
     if ((tile_page >> 6) != pages_chunk) {
       // called right after the loop-top wait, so pages_next has arrived
@@ -357,11 +382,23 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
     const char* vc = reinterpret_cast<const char*>(p.v_cache);
 #pragma unroll
     for (int j = 0; j < kLoadsPerWave; ++j) {
-      const int load = wave * kLoadsPerWave + j;              // 0 .. 2*kGLoadsPerMatrix-1
+      const int load = issuer * kLoadsPerWave + j;            // 0 .. 2*kGLoadsPerMatrix-1
       const bool is_v = load >= kGLoadsPerMatrix;             // wave-uniform
       const int idx = is_v ? load - kGLoadsPerMatrix : load;
       const int row0 = idx * kGKeysPerLoad;                    // first tile row of this load
       const int tile_row = row0 + g_key;
+      const int swz = KV8 ? (is_v ? 0 : kswz8(tile_row)) : (is_v ? G::vswz(tile_row) : G::kswz(tile_row));
+      if constexpr (kGKeysPerLoad <= kMinPageSize) {
+        if (full_tile) {
+          // all rows of the load lie in one page and inside the range: page, head and first
+          // row make a wave-uniform base, the lane adds its row and (swizzled) chunk
+          const int64_t page = __builtin_amdgcn_readlane(pages_cur, ((first_off + t * kKeyTile + row0) >> ps) & 63);
+          const int64_t base = page * page_bytes + head_bytes + ((key0 + row0) & page_mask) * kGRowBytes;
+          load_to_lds_16((is_v ? vc : kc) + base, (uint32_t)(g_key * kGRowBytes + ((g_pc ^ swz) << 4)),
+                         (is_v ? vbuf : kbuf) + idx * 1024);
+          continue;
+        }
+      }
       // one load never spans two pages, except for the shortest rows on the smallest pages:
       // then every lane looks its own page up
       int64_t page;
@@ -371,8 +408,6 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
         page = __builtin_amdgcn_ds_bpermute((((first_off + t * kKeyTile + tile_row) >> ps) & 63) << 2, pages_cur);
       const int64_t in_off = page * page_bytes + head_bytes + ((key0 + tile_row) & page_mask) * kGRowBytes;
       const int64_t row_off = (key0 + tile_row < k_end) ? in_off : last_off;
-      // value codes stay row-major: the conversion pass applies their swizzle
-      const int swz = KV8 ? (is_v ? 0 : kswz8(tile_row)) : (is_v ? G::vswz(tile_row) : G::kswz(tile_row));
       const char* src = (is_v ? vc : kc) + row_off + ((g_pc ^ swz) << 4);
       load_to_lds_16(src, (is_v ? vbuf : kbuf) + idx * 1024);
     }
@@ -633,7 +668,7 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
 
 #pragma unroll
   for (int s0 = 0; s0 < STAGES - 1; ++s0)
-    if (s0 < ntiles) issue_tile(s0, stages + s0 * kStageBytes, stages + s0 * kStageBytes + kGTileBytes);
+    if (s0 < ntiles) issue_tile(s0, s0);
   if constexpr (FUSED) {
     // rotary embedding of the tile's query rows and of the new token's key at position C_r
     // (the request's only new token is packed row rq.row_start), same arithmetic as the
@@ -693,7 +728,7 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
         wait_tile(t);
         constexpr int kAhead = STAGES - 1;
         const int sl = (s0 + kAhead) % STAGES;  // static after unrolling
-        if (t + kAhead < ntiles) issue_tile(t + kAhead, stages + sl * kStageBytes, stages + sl * kStageBytes + kGTileBytes);
+        if (t + kAhead < ntiles) issue_tile(t + kAhead, sl);
         if constexpr (FUSED) {
           // The key range that ends with the new token: the cache slot of that token has not
           // been written yet, so its row of the landed tile and the rows behind it (which the
@@ -736,59 +771,52 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
     }
   }
 
-  // --- waves that shared the rows: combine their results in wave 0 ---------------------
-  // With M = max_w m_w every wave rescales its sums by 2^(m_w - M); then the upper half of the
-  // waves hands its sums to the lower half through LDS, halving until wave 0 holds the total.
+  // --- waves 0 and 1 shared the rows: combine their results in wave 0 --------------------
+  // With M = max(m_0, m_1) each of the two rescales its sums by 2^(m_w - M); then wave 1 hands
+  // its sums to wave 0 through LDS.
   if constexpr (KP) {
     // (no fused multiply-add here: whether the rescaling and the sums below end up fused would
     // depend on how each variant of the kernel is scheduled, and the variants must agree bit
     // for bit)
 #pragma clang fp contract(off)
     constexpr int kRegs = G::kDBlocks * 16;
-    float* xo = reinterpret_cast<float*>(lds);          // [WAVES / 2][kRegs / 4][64 lanes] x 4 floats
-    float* xm = xo + (WAVES / 2) * kRegs * 64;          // [WAVES][64]
-    float* xl = xm + WAVES * 64;                        // [WAVES / 2][64]
-    static_assert(((WAVES / 2) * kRegs * 64 + WAVES * 64 + (WAVES / 2) * 64) * 4 <= kTileBufBytes,
-                  "the exchange area must fit the tile buffers");
+    float* xo = reinterpret_cast<float*>(lds);  // [kRegs / 4][64 lanes] x 4 floats
+    float* xm = xo + kRegs * 64;                // [2][64]
+    float* xl = xm + 2 * 64;                    // [64]
+    static_assert((kRegs * 64 + 3 * 64) * 4 <= kTileBufBytes, "the exchange area must fit the tile buffers");
     __syncthreads();  // every wave is done with the tiles
-    xm[wave * 64 + lane] = m_run;
+    if (wave < 2) xm[wave * 64 + lane] = m_run;
     __syncthreads();
-    float m_all = xm[lane];
+    if (wave < 2) {
+      const float m_all = fmaxf(xm[lane], xm[64 + lane]);
+      const float sc = (m_run == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m_run - m_all);
+      l_run *= sc;
 #pragma unroll
-    for (int w = 1; w < WAVES; ++w) m_all = fmaxf(m_all, xm[w * 64 + lane]);
-    const float sc = (m_run == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m_run - m_all);
-    l_run *= sc;
+      for (int d = 0; d < G::kDBlocks; ++d)
 #pragma unroll
-    for (int d = 0; d < G::kDBlocks; ++d)
+        for (int r = 0; r < 16; ++r) o[d][r] *= sc;
+      m_run = m_all;
+    }
+    if (wave == 1) {
 #pragma unroll
-      for (int r = 0; r < 16; ++r) o[d][r] *= sc;
-    m_run = m_all;
+      for (int d = 0; d < G::kDBlocks; ++d)
 #pragma unroll
-    for (int half = WAVES / 2; half >= 1; half >>= 1) {
-      if (wave >= half && wave < 2 * half) {
-        float* dst = xo + (wave - half) * kRegs * 64;
+        for (int rr = 0; rr < 4; ++rr)
+          *reinterpret_cast<f32x4*>(xo + ((d * 4 + rr) * 64 + lane) * 4) =
+              f32x4{o[d][rr * 4], o[d][rr * 4 + 1], o[d][rr * 4 + 2], o[d][rr * 4 + 3]};
+      xl[lane] = l_run;
+    }
+    __syncthreads();
+    if (wave == 0) {
 #pragma unroll
-        for (int d = 0; d < G::kDBlocks; ++d)
+      for (int d = 0; d < G::kDBlocks; ++d)
 #pragma unroll
-          for (int rr = 0; rr < 4; ++rr)
-            *reinterpret_cast<f32x4*>(dst + ((d * 4 + rr) * 64 + lane) * 4) =
-                f32x4{o[d][rr * 4], o[d][rr * 4 + 1], o[d][rr * 4 + 2], o[d][rr * 4 + 3]};
-        xl[(wave - half) * 64 + lane] = l_run;
-      }
-      __syncthreads();
-      if (wave < half) {
-        const float* src = xo + wave * kRegs * 64;
+        for (int rr = 0; rr < 4; ++rr) {
+          const f32x4 v = *reinterpret_cast<const f32x4*>(xo + ((d * 4 + rr) * 64 + lane) * 4);
 #pragma unroll
-        for (int d = 0; d < G::kDBlocks; ++d)
-#pragma unroll
-          for (int rr = 0; rr < 4; ++rr) {
-            const f32x4 v = *reinterpret_cast<const f32x4*>(src + ((d * 4 + rr) * 64 + lane) * 4);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) o[d][rr * 4 + e] += v[e];
-          }
-        l_run += xl[wave * 64 + lane];
-      }
-      __syncthreads();
+          for (int e = 0; e < 4; ++e) o[d][rr * 4 + e] += v[e];
+        }
+      l_run += xl[lane];
     }
     wave_active = wave == 0;
   }
@@ -854,7 +882,7 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
       *s_last = __hip_atomic_fetch_add(ticket, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == mi.nsplit - 1;
     __syncthreads();
     if (*s_last) {
-      merge_rows<D, true>(p, mi, rq, tid, 64 * WAVES);
+      merge_rows<D, true>(p, mi, tid, 64 * WAVES);
       if (tid == 0) __hip_atomic_store(ticket, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
   }
@@ -867,7 +895,7 @@ __global__ __launch_bounds__(256) void merge_kernel(const AttnParams p, const Me
   // this workgroup's slice of the rows
   const int first = blockIdx.y * ROWS;
   if (first >= mi.row_count) return;
-  merge_rows<D>(p, mi, p.reqs[mi.req], threadIdx.x, 256, first, min(mi.row_count, first + ROWS));
+  merge_rows<D>(p, mi, threadIdx.x, 256, first, min(mi.row_count, first + ROWS));
 }
 
 }  // namespace
@@ -877,8 +905,7 @@ namespace {
 void fill_params(AttnParams* p, const efim_batch_t* b, const Plan& plan, const char* header, const void* q,
                  const void* k_cache, const void* v_cache, void* out, float sm_scale, const CacheFormat& fmt,
                  char* partials) {
-  p->reqs = reinterpret_cast<const ReqInfo*>(header + plan.off_reqs);
-  p->items = reinterpret_cast<const WorkItem*>(header + plan.off_items);
+  p->items = reinterpret_cast<const DevItem*>(header + plan.off_items);
   p->q = static_cast<const uint16_t*>(q);
   p->k_cache = static_cast<const uint16_t*>(k_cache);
   p->v_cache = static_cast<const uint16_t*>(v_cache);

@@ -211,7 +211,7 @@ void build_plan(const efim_batch_t* b, int num_slots, Plan* plan) {
       pend.push_back({w, t.ktiles + 4, group});
     } else {
       const int per = (t.ktiles + nsplit - 1) / nsplit;  // key tiles per chunk
-      MergeItem m{t.req, t.kv_head, t.row_begin, t.row_count, (int32_t)slot, 0, 0, 0};
+      MergeItem m{t.req, t.kv_head, t.row_begin, t.row_count, (int32_t)slot, 0, plan->reqs[t.req].row_start, 0};
       int made = 0;
       for (int s = 0; s < nsplit; ++s) {
         const int64_t kb = (int64_t)s * per * kKeyTile;
@@ -298,10 +298,8 @@ void build_plan(const efim_batch_t* b, int num_slots, Plan* plan) {
 
   // Layout of the staged header and of the device workspace.
   size_t off = 0;
-  plan->off_reqs = off;
-  off = align_up(off + plan->reqs.size() * sizeof(ReqInfo), 256);
   plan->off_items = off;
-  off = align_up(off + plan->items.size() * sizeof(WorkItem), 256);
+  off = align_up(off + plan->items.size() * sizeof(DevItem), 256);
   plan->off_merges = off;
   off = align_up(off + plan->merges.size() * sizeof(MergeItem), 256);
   plan->header_bytes = off;
