@@ -7,7 +7,7 @@ efim_extend_attention, i.e. one attention layer's worth of a serving step (no
 projections or MLP: those are not part of this path).  The headline workload is
 the mixed serving step (64 requests, half cache hits, half misses); the other
 workloads and the fixed-inc sweeps are reported in the same JSON line under
-"workloads".
+"workloads"; the service replay, the decode step and the 8-bit KV cache have sections of their own.
 
 Prints ONE JSON line.  All inputs are seeded and synthetic and resident in HBM
 before the timed region starts.
@@ -264,6 +264,61 @@ def decode_steps(torch, E, W, iters, shapes=("c2", "c3")):
     return out
 
 
+def fp8_cache(torch, E, W, iters, shapes=("c2", "c3")):
+    """The 8-bit (E4M3, per-tensor scale) KV cache on decode-like steps at the batch shapes of c2
+    and c3: the whole efim_extend_attention_fp8 call at one new token per request and the
+    single-launch efim_decode_step_fp8, next to their bf16 counterparts.  Bytes are the
+    algorithmic ones with one byte per cache element."""
+    out = {}
+    stream = torch.cuda.current_stream()
+    for base in shapes:
+        spec = W.make_batch(base, with_history=False, with_tensors=False)
+        d = DeviceBatch(torch, E, W, base, lengths=(spec.cached_len, np.ones_like(spec.new_len)), copies=3)
+        b = d.host
+        scale = 4.0 * b.sigma / 448.0   # four standard deviations reach the largest code
+        for s in d.sets:
+            for name in ("k_cache", "v_cache"):
+                s[name + "8"] = (s[name].float() / scale).clamp(-448, 448).to(torch.float8_e4m3fn).view(torch.uint8)
+        nbytes = E.efim_decode_workspace_bytes(d.desc)
+        ws = torch.empty(max(nbytes, d.ws_bytes, 256), dtype=torch.uint8, device="cuda")
+        e0, e1 = E.HipEvent(), E.HipEvent()
+
+        def queued(call, reps=5):
+            times = []
+            for _ in range(reps):
+                torch.cuda.synchronize()
+                e0.record(stream)
+                for it in range(iters):
+                    call(d.sets[it % len(d.sets)])
+                e1.record(stream)
+                e1.synchronize()
+                times.append(e0.elapsed_ms(e1) * 1e3 / iters)
+            return float(np.median(times[1:]))
+
+        a16 = queued(lambda s: E.efim_extend_attention(d.desc, s["q"], s["k_cache"], s["v_cache"], s["out"], 0.0,
+                                                       ws, d.ws_bytes, stream))
+        a8 = queued(lambda s: E.efim_extend_attention_fp8(d.desc, s["q"], s["k_cache8"], s["v_cache8"], s["out"], 0.0,
+                                                          scale, scale, ws, d.ws_bytes, stream))
+        s16 = queued(lambda s: E.efim_decode_step(d.desc, s["q_raw"], s["k_new"], s["v_new"], s["k_cache"],
+                                                  s["v_cache"], s["out"], b.rope_base, 0, 0.0, ws, nbytes, stream))
+        s8 = queued(lambda s: E.efim_decode_step_fp8(d.desc, s["q_raw"], s["k_new"], s["v_new"], s["k_cache8"],
+                                                     s["v_cache8"], s["out"], b.rope_base, 0, 0.0, scale, scale,
+                                                     ws, nbytes, stream))
+        bytes8 = W.attention_bytes(b, 1)
+        step8 = bytes8 + W.rope_append_bytes(b, 1)
+        out[base + "_inc1"] = {
+            "batch": b.batch,
+            "attn_call_us_bf16": round(a16, 2), "attn_call_us_fp8": round(a8, 2), "attn_speedup": round(a16 / a8, 3),
+            "attn_fp8_GBps": round(bytes8 / a8 / 1e3, 1), "attn_fp8_frac_hbm": round(bytes8 / a8 / 1e3 / PEAK_HBM_GBPS, 4),
+            "decode_step_us_bf16": round(s16, 2), "decode_step_us_fp8": round(s8, 2),
+            "decode_step_speedup": round(s16 / s8, 3),
+            "decode_step_fp8_frac_hbm": round(step8 / s8 / 1e3 / PEAK_HBM_GBPS, 4),
+        }
+        del d, ws
+        torch.cuda.empty_cache()
+    return out
+
+
 def recorded_traffic(name):
     import hashlib
     rec = MEASURED_TRAFFIC.get(name)
@@ -405,6 +460,7 @@ def main():
         result["workloads"] = extra
         result["service_replay"] = replay(torch, E, W, iters=max(5, args.extra_iters // 3))
         result["decode_step"] = decode_steps(torch, E, W, iters=args.extra_iters)
+        result["fp8_kv_cache"] = fp8_cache(torch, E, W, iters=args.extra_iters)
 
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(W, name)

@@ -255,3 +255,70 @@ def test_fp8_calls_reject_bad_scales(E):
             E.efim_extend_attention_fp8(desc, 1, 1, 1, 1, 0.0, 1.0, bad, 1, 256)
         with pytest.raises(E.EfimError):
             E.efim_decode_step_fp8(desc, 1, 1, 1, 1, 1, 1, 1e4, 0, 0.0, bad, 1.0, 1, 256)
+
+
+# ------------------------------------------------------------ random batches ----
+
+HEADS = [(1, 1), (4, 4), (4, 2), (8, 2), (6, 1), (14, 2), (12, 4)]
+EDGES = [0, 1, 15, 16, 17, 31, 32, 33, 63, 64, 65, 127, 128, 129, 255, 256, 1000]
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_fp8_random_batch(E, seed):
+    """Random ragged batches, head layouts, page sizes, scales and planner knobs through both
+    8-bit calls: codes byte-exact, attention within the bar."""
+    rng = np.random.default_rng(11000 + seed)
+    batch = int(rng.integers(1, 6))
+    cached = [int(rng.choice(EDGES)) if rng.random() < 0.6 else int(rng.integers(0, 1500)) for _ in range(batch)]
+    new = [int(rng.choice([0, 1, 2, 8, 16, 17, 32, 33, 64, 130])) if rng.random() < 0.7 else int(rng.integers(1, 200))
+           for _ in range(batch)]
+    if sum(new) == 0:
+        new[0] = 5
+    heads = HEADS[int(rng.integers(len(HEADS)))]
+    d = int(rng.choice([64, 128]))
+    inter = int(rng.integers(0, 2))
+    k_scale, v_scale = float(rng.choice([1.0, 0.5, 0.0123, 0.05])), float(rng.choice([1.0, 0.031, 0.02]))
+    b = W.make_batch("c1", seed=1200 + seed, lengths=(np.array(cached, dtype=np.int32), np.array(new, dtype=np.int32)),
+                     heads=heads, head_dim=d, page_size=int(rng.choice([8, 16, 16, 32, 64, 256])))
+    kc, vc = oracle_cache8(b, k_scale, v_scale)
+    q_ref, kc_ref, vc_ref, ref = oracle_step8(b, kc, vc, k_scale, v_scale, bool(inter))
+    E.efim_set_tuning(E.EFIM_TUNE_SPLIT_KV, int(rng.choice([-1, -1, 0, 64, 128])))
+    E.efim_set_tuning(E.EFIM_TUNE_ROW_TILE, int(rng.choice([0, 0, 128, 256])))
+    E.efim_set_tuning(E.EFIM_TUNE_FUSED_MERGE, int(rng.choice([-1, 0, 1])))
+    try:
+        q_got, kc_got, vc_got = gpu_append8(E, b, kc, vc, k_scale, v_scale, inter)
+        assert np.array_equal(q_got, q_ref) and np.array_equal(kc_got, kc_ref) and np.array_equal(vc_got, vc_ref)
+        # coarse scales quantise the values hard; what is compared is the attention over the
+        # SAME codes, so the usual bar applies (relative to the output size, as in the other
+        # random tests)
+        U.assert_close(gpu_attention8(E, b, q_ref, kc_ref, vc_ref, k_scale, v_scale), ref,
+                       "%s %s %s d%d" % (cached, new, heads, d), scale_abs_with_output=True)
+    finally:
+        E.efim_set_tuning(E.EFIM_TUNE_SPLIT_KV, -1)
+        E.efim_set_tuning(E.EFIM_TUNE_ROW_TILE, 0)
+        E.efim_set_tuning(E.EFIM_TUNE_FUSED_MERGE, -1)
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_fp8_random_decode_step(E, seed):
+    rng = np.random.default_rng(12000 + seed)
+    batch = int(rng.integers(1, 9))
+    cached = np.array([int(rng.choice(EDGES)) if rng.random() < 0.5 else int(rng.integers(0, 3000))
+                       for _ in range(batch)], dtype=np.int32)
+    heads = HEADS[int(rng.integers(len(HEADS)))]
+    d = int(rng.choice([64, 128]))
+    inter = int(rng.integers(0, 2))
+    k_scale, v_scale = float(rng.choice([1.0, 0.0123])), float(rng.choice([1.0, 0.031]))
+    b = W.make_batch("c1", seed=1300 + seed, lengths=(cached, np.ones_like(cached)), heads=heads, head_dim=d,
+                     page_size=int(rng.choice([8, 16, 16, 32, 128])))
+    kc, vc = oracle_cache8(b, k_scale, v_scale)
+    _, kc_ref, vc_ref, ref = oracle_step8(b, kc, vc, k_scale, v_scale, bool(inter))
+    E.efim_set_tuning(E.EFIM_TUNE_SPLIT_KV, int(rng.choice([-1, 64, 192, 0])))
+    E.efim_set_tuning(E.EFIM_TUNE_ROW_TILE, int(rng.choice([0, 0, 256])))
+    try:
+        got, kc_got, vc_got, _ = run_decode8(E, b, kc, vc, k_scale, v_scale, inter)
+    finally:
+        E.efim_set_tuning(E.EFIM_TUNE_SPLIT_KV, -1)
+        E.efim_set_tuning(E.EFIM_TUNE_ROW_TILE, 0)
+    assert np.array_equal(kc_got, kc_ref) and np.array_equal(vc_got, vc_ref)
+    U.assert_close(got, ref, "%s %s d%d" % (cached.tolist(), heads, d), scale_abs_with_output=True)
