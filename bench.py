@@ -32,7 +32,7 @@ if ROOT not in sys.path:
 # on: the digest of extend_attention.hip is recorded with it and checked at run time.
 MEASURED_TRAFFIC = {
     # workload: (bytes per launch, sha256 of csrc/extend_attention.hip when measured)
-    "c5": (2561617435, "a7543540db452f97e4a9990b671467eb4fece4c9f73f0a0313e6a82f7a59341b"),
+    "c5": (2562129076, "2ea60c70dee202598590d53d5784746fa8494b1d83f4e34cda113758708adbec"),
 }
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak
