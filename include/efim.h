@@ -212,6 +212,13 @@ size_t efim_decode_workspace_bytes(const efim_batch_t* batch);
 int efim_decode_step(const efim_batch_t* batch, const void* q, const void* k_new, const void* v_new,
                      void* k_cache, void* v_cache, void* out, double rope_base, int rope_interleaved,
                      float sm_scale, void* workspace, size_t workspace_bytes, void* stream);
+/* The same with the rotary variants of efim_rope_append_table (inv_freq: HOST double[rotary_dim / 2];
+ * rotary_dim a multiple of 16 in [16, head_dim]): what efim_rope_append_table followed by
+ * efim_extend_attention compute, in one launch. */
+int efim_decode_step_table(const efim_batch_t* batch, const void* q, const void* k_new, const void* v_new,
+                           void* k_cache, void* v_cache, void* out, const double* inv_freq, int rotary_dim,
+                           int rope_interleaved, float sm_scale, void* workspace, size_t workspace_bytes,
+                           void* stream);
 
 /* ---------------------------------------------------------------------------------------
  * 8-bit KV cache.  The paper serves unmodified models on a stock engine (Sec. 4.2) and does

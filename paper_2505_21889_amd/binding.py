@@ -88,6 +88,9 @@ def _load():
     lib.efim_decode_step.argtypes = [bp, vp, vp, vp, vp, vp, vp, ctypes.c_double, i32, ctypes.c_float, vp,
                                      ctypes.c_size_t, vp]
     lib.efim_decode_step.restype = i32
+    lib.efim_decode_step_table.argtypes = [bp, vp, vp, vp, vp, vp, vp, ctypes.POINTER(ctypes.c_double), i32, i32,
+                                           ctypes.c_float, vp, ctypes.c_size_t, vp]
+    lib.efim_decode_step_table.restype = i32
     f32 = ctypes.c_float
     lib.efim_rope_append_fp8.argtypes = [bp, vp, vp, vp, vp, vp, ctypes.c_double, i32, f32, f32, vp]
     lib.efim_rope_append_fp8.restype = i32
@@ -128,7 +131,7 @@ _lib = _load()
 LIBRARY_PATH = os.environ.get("EFIM_LIBRARY") or _build.LIB_PATH
 EXPORTED_SYMBOLS = (
     "efim_rope_append", "efim_rope_append_table", "efim_extend_workspace_bytes", "efim_extend_attention",
-    "efim_decode_workspace_bytes", "efim_decode_step",
+    "efim_decode_workspace_bytes", "efim_decode_step", "efim_decode_step_table",
     "efim_rope_append_fp8", "efim_extend_attention_fp8", "efim_decode_step_fp8",
     "efim_extend_plan_items", "efim_set_tuning", "efim_set_kernel_events", "efim_status_string",
     "efim_last_hip_error", "efim_version",
@@ -221,6 +224,17 @@ def efim_decode_step(batch, q, k_new, v_new, k_cache, v_cache, out, rope_base, r
                                  _ptr(v_cache), _ptr(out), float(rope_base), int(rope_interleaved), float(sm_scale),
                                  _ptr(workspace), int(workspace_bytes), _stream_ptr(stream)),
            "efim_decode_step")
+
+
+def efim_decode_step_table(batch, q, k_new, v_new, k_cache, v_cache, out, inv_freq, rotary_dim, rope_interleaved,
+                           sm_scale, workspace, workspace_bytes, stream=None):
+    table = np.ascontiguousarray(np.asarray(inv_freq, dtype=np.float64).reshape(-1))
+    assert table.size >= int(rotary_dim) // 2, "inv_freq needs rotary_dim / 2 entries"
+    _check(_lib.efim_decode_step_table(ctypes.byref(batch.c), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(k_cache),
+                                       _ptr(v_cache), _ptr(out), table.ctypes.data_as(ctypes.POINTER(ctypes.c_double)),
+                                       int(rotary_dim), int(rope_interleaved), float(sm_scale), _ptr(workspace),
+                                       int(workspace_bytes), _stream_ptr(stream)),
+           "efim_decode_step_table")
 
 
 def efim_rope_append_fp8(batch, q, k_new, v_new, k_cache, v_cache, rope_base, rope_interleaved, k_scale, v_scale,

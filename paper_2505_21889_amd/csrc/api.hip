@@ -288,15 +288,27 @@ size_t efim_decode_workspace_bytes(const efim_batch_t* batch) {
 
 namespace {
 
+// rope_base > 0: the plain table base^(-2j/D) over the whole head; otherwise the caller's table.
 int decode_step_base(const efim_batch_t* batch, const void* q, const void* k_new, const void* v_new,
-                     void* k_cache, void* v_cache, void* out, double rope_base, int rope_interleaved,
-                     float sm_scale, const CacheFormat& fmt, void* workspace, size_t workspace_bytes,
-                     void* stream) {
+                     void* k_cache, void* v_cache, void* out, double rope_base, const double* table,
+                     int rotary_dim, int rope_interleaved, float sm_scale, const CacheFormat& fmt,
+                     void* workspace, size_t workspace_bytes, void* stream) {
   int64_t total = 0;
   int rc = validate_decode_batch(batch, &total);
   if (rc != EFIM_OK) return rc;
-  if (!(sm_scale >= 0.f) || !(rope_base > 0.0) || (rope_interleaved != 0 && rope_interleaved != 1))
-    return EFIM_ERR_INVALID_ARG;
+  if (!(sm_scale >= 0.f) || (rope_interleaved != 0 && rope_interleaved != 1)) return EFIM_ERR_INVALID_ARG;
+  double inv_freq[64];
+  if (table) {
+    if (rotary_dim < 16 || rotary_dim > batch->head_dim || rotary_dim % 16 != 0) return EFIM_ERR_INVALID_ARG;
+    for (int j = 0; j < rotary_dim / 2; ++j) {
+      if (!(table[j] == table[j]) || table[j] - table[j] != 0.0) return EFIM_ERR_INVALID_ARG;  // NaN / inf
+      inv_freq[j] = table[j];
+    }
+  } else {
+    if (!(rope_base > 0.0)) return EFIM_ERR_INVALID_ARG;
+    rotary_dim = batch->head_dim;
+    for (int j = 0; j < rotary_dim / 2; ++j) inv_freq[j] = pow(rope_base, -2.0 * j / rotary_dim);
+  }
   if (total == 0) return EFIM_OK;
   if (!q || !k_new || !v_new || !k_cache || !v_cache || !out || q == out || out == k_cache || out == v_cache)
     return EFIM_ERR_INVALID_ARG;
@@ -315,7 +327,7 @@ int decode_step_base(const efim_batch_t* batch, const void* q, const void* k_new
   rc = stage_plan(plan, &slot, &header);
   if (rc != EFIM_OK) return rc;
   rc = launch_decode_step(batch, plan, header, (int)(slot - g_stage), q, k_new, v_new, k_cache, v_cache, out,
-                          rope_base, rope_interleaved, sm_scale, fmt, workspace, s);
+                          inv_freq, rotary_dim, rope_interleaved, sm_scale, fmt, workspace, s);
   if (hipEventRecord(slot->done, s) == hipSuccess) slot->in_flight = true;
   else (void)hipStreamSynchronize(s);
   return rc;
@@ -326,8 +338,18 @@ int decode_step_base(const efim_batch_t* batch, const void* q, const void* k_new
 int efim_decode_step(const efim_batch_t* batch, const void* q, const void* k_new, const void* v_new,
                      void* k_cache, void* v_cache, void* out, double rope_base, int rope_interleaved,
                      float sm_scale, void* workspace, size_t workspace_bytes, void* stream) {
-  return decode_step_base(batch, q, k_new, v_new, k_cache, v_cache, out, rope_base, rope_interleaved, sm_scale,
-                          CacheFormat(), workspace, workspace_bytes, stream);
+  if (!(rope_base > 0.0)) return EFIM_ERR_INVALID_ARG;
+  return decode_step_base(batch, q, k_new, v_new, k_cache, v_cache, out, rope_base, nullptr, 0, rope_interleaved,
+                          sm_scale, CacheFormat(), workspace, workspace_bytes, stream);
+}
+
+int efim_decode_step_table(const efim_batch_t* batch, const void* q, const void* k_new, const void* v_new,
+                           void* k_cache, void* v_cache, void* out, const double* inv_freq, int rotary_dim,
+                           int rope_interleaved, float sm_scale, void* workspace, size_t workspace_bytes,
+                           void* stream) {
+  if (!inv_freq) return EFIM_ERR_INVALID_ARG;
+  return decode_step_base(batch, q, k_new, v_new, k_cache, v_cache, out, 0.0, inv_freq, rotary_dim,
+                          rope_interleaved, sm_scale, CacheFormat(), workspace, workspace_bytes, stream);
 }
 
 int efim_decode_step_fp8(const efim_batch_t* batch, const void* q, const void* k_new, const void* v_new,
@@ -339,8 +361,9 @@ int efim_decode_step_fp8(const efim_batch_t* batch, const void* q, const void* k
   fmt.fp8 = true;
   fmt.k_scale = k_scale;
   fmt.v_scale = v_scale;
-  return decode_step_base(batch, q, k_new, v_new, k_cache, v_cache, out, rope_base, rope_interleaved, sm_scale,
-                          fmt, workspace, workspace_bytes, stream);
+  if (!(rope_base > 0.0)) return EFIM_ERR_INVALID_ARG;
+  return decode_step_base(batch, q, k_new, v_new, k_cache, v_cache, out, rope_base, nullptr, 0, rope_interleaved,
+                          sm_scale, fmt, workspace, workspace_bytes, stream);
 }
 
 int64_t efim_extend_plan_items(const efim_batch_t* batch, efim_work_item_t* items, int64_t capacity) {

@@ -106,11 +106,12 @@ int launch_extend_attention(const efim_batch_t* b, const Plan& plan, const char*
 
 // Fused decode step (every request has exactly one new token): one launch does the rotary
 // embedding, the cache append, the attention and the merge of split key ranges.
+// inv_freq / rotary_dim as for launch_rope_append.
 constexpr int kDecodeMaxGroup = 32;  // query heads per kv head the fused kernel handles
 int launch_decode_step(const efim_batch_t* b, const Plan& plan, const char* header, int stage_slot,
                        const void* q, const void* k_new, const void* v_new, void* k_cache, void* v_cache,
-                       void* out, double rope_base, int interleaved, float sm_scale, const CacheFormat& fmt,
-                       void* workspace, hipStream_t stream);
+                       void* out, const double* inv_freq, int rotary_dim, int interleaved, float sm_scale,
+                       const CacheFormat& fmt, void* workspace, hipStream_t stream);
 
 void set_last_hip_error(hipError_t e);
 

@@ -6,8 +6,8 @@
 // query rows of one (request, kv head) against a range of keys.  Rows are (token,
 // head-in-group) pairs so all query heads that share a kv head read its K/V once.  Per
 // 64-key tile:
-//   * the four 16-token pages are gathered through the block table straight from HBM into
-//     LDS (16 bytes per lane, 1 KB per wave instruction, XOR-swizzled 16-byte chunks), one or
+//   * the tile's pages are gathered through the block table straight from HBM into LDS
+//     (16 bytes per lane, 1 KB per wave instruction, XOR-swizzled 16-byte chunks), one or
 //     two tiles ahead of the one being consumed;
 //   * S^T = K Q^T with 32x32x16 bf16 MFMA: every lane ends up with 32 scores of ONE query
 //     row, so the running max / sum are per-lane scalars plus one cross-half exchange;
@@ -46,7 +46,6 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 
 #define LDS_PTR(T) __attribute__((address_space(3))) T*
-#define GLOBAL_PTR(T) __attribute__((address_space(1))) T*
 
 struct AttnParams {
   const DevItem* items;
@@ -76,7 +75,8 @@ struct AttnParams {
                           // key ranges are combined by merge_kernel in a second launch
   int32_t page_shift;     // log2 of the page size (tokens per page)
   int32_t interleaved;    // rotary pairing
-  double inv_freq[64];    // base^(-2j/D)
+  int32_t rotary_dim;     // leading elements of a head row that are rotated
+  double inv_freq[64];    // rotation frequency of pair j (rotary_dim / 2 entries)
 };
 
 
@@ -237,7 +237,8 @@ __device__ __forceinline__ void merge_rows(const AttnParams& p, const MergeItem&
 // KP ("key parallel"): every work item of the launch has at most 32 query rows (decode steps,
 // short increments).  One wave would be busy and the others idle: instead waves 0 and 1 both
 // take all the rows and one 32-key half of every key tile each, with their own running max and
-// sums, and their partial results are combined through LDS at the end.
+// sums, and their partial results are combined through LDS at the end.  In the four-wave
+// kernel the two waves without rows issue all the gathers.
 template <int D, int WAVES, int STAGES, bool FUSED, bool KV8, bool KP>
 __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const AttnParams p) {
   static_assert(KP || !FUSED, "the decode step has at most 32 rows per tile");
@@ -674,7 +675,8 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
     // (the request's only new token is packed row rq.row_start), same arithmetic as the
     // stand-alone append kernel
     const int pos = rq.cached;
-    if (tid < D / 2) {
+    const int rot_half = p.rotary_dim / 2;  // pairs per head row (D/2 when the whole row rotates)
+    if (tid < rot_half) {
       double sn, cs;
       sincos((double)pos * p.inv_freq[tid], &sn, &cs);
       s_cs[tid] = cs;
@@ -684,8 +686,10 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
     const int64_t kv_row = ((int64_t)rq.row_start * p.num_kv_heads + it.kv_head) * D;
     for (int idx = tid; idx < (it.row_count + 1) * (D / 2); idx += 64 * WAVES) {
       const int r = idx / (D / 2), j = idx - r * (D / 2);
-      const int e1 = p.interleaved ? 2 * j : j;
-      const int e2 = p.interleaved ? 2 * j + 1 : j + D / 2;
+      // pair j of the rotated part, or two neighbouring elements behind it (passed through)
+      const bool rotate = j < rot_half;
+      const int e1 = !rotate ? p.rotary_dim + 2 * (j - rot_half) : (p.interleaved ? 2 * j : j);
+      const int e2 = !rotate ? e1 + 1 : (p.interleaved ? 2 * j + 1 : j + rot_half);
       const uint16_t* src = p.k_new + kv_row;
       uint16_t* dst = s_kv;
       if (r < it.row_count) {
@@ -694,8 +698,8 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
         src = p.q + ((int64_t)(rq.row_start + t_) * p.num_q_heads + it.kv_head * g + (rr - t_ * g)) * D;
         dst = s_q + r * D;
       }
-      uint32_t y1, y2;
-      rotate_pair_bf16(src[e1], src[e2], s_cs[j], s_cs[64 + j], &y1, &y2);
+      uint32_t y1 = src[e1], y2 = src[e2];
+      if (rotate) rotate_pair_bf16(y1, y2, s_cs[j], s_cs[64 + j], &y1, &y2);
       if (KV8 && r == it.row_count) {
         // the key goes into the cache as a code: D bytes, the value's D bytes behind them
         uint8_t* codes = reinterpret_cast<uint8_t*>(s_kv);
@@ -935,6 +939,7 @@ void fill_params(AttnParams* p, const efim_batch_t* b, const Plan& plan, const c
   p->page_shift = 0;
   while ((1 << p->page_shift) < b->page_size) ++p->page_shift;
   p->interleaved = 0;
+  p->rotary_dim = b->head_dim;
   for (double& f : p->inv_freq) f = 0.0;
 }
 
@@ -1008,8 +1013,8 @@ int launch_extend_attention(const efim_batch_t* b, const Plan& plan, const char*
 
 int launch_decode_step(const efim_batch_t* b, const Plan& plan, const char* header, int stage_slot,
                        const void* q, const void* k_new, const void* v_new, void* k_cache, void* v_cache,
-                       void* out, double rope_base, int interleaved, float sm_scale, const CacheFormat& fmt,
-                       void* workspace, hipStream_t stream) {
+                       void* out, const double* inv_freq, int rotary_dim, int interleaved, float sm_scale,
+                       const CacheFormat& fmt, void* workspace, hipStream_t stream) {
   AttnParams p;
   fill_params(&p, b, plan, header, q, k_cache, v_cache, out, sm_scale, fmt, static_cast<char*>(workspace));
   if (use_tickets(plan, true)) p.ticket_base = stage_slot * kTicketsPerSlot;
@@ -1018,8 +1023,9 @@ int launch_decode_step(const efim_batch_t* b, const Plan& plan, const char* head
   p.k_cache_w = static_cast<uint16_t*>(k_cache);
   p.v_cache_w = static_cast<uint16_t*>(v_cache);
   p.interleaved = interleaved;
+  p.rotary_dim = rotary_dim;
   const int D = b->head_dim;
-  for (int j = 0; j < D / 2; ++j) p.inv_freq[j] = pow(rope_base, -2.0 * j / D);
+  for (int j = 0; j < rotary_dim / 2; ++j) p.inv_freq[j] = inv_freq[j];
 
   const dim3 grid((unsigned)plan.items.size());
   const Tuning& tn = tuning();

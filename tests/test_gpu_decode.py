@@ -226,3 +226,50 @@ def test_decode_step_rejects_other_batches(E):
     assert rc == E.EFIM_ERR_WORKSPACE
     rc = lib.efim_decode_step(ctypes.byref(desc1.c), fake, fake, fake, fake, fake, fake + 0x1000, 1e4, 2, 0.0, fake, need, None)
     assert rc == E.EFIM_ERR_INVALID_ARG
+
+
+@pytest.mark.parametrize("d,rotary_dim,interleaved,heads", [(128, 128, 0, (8, 2)), (128, 64, 0, (8, 2)), (128, 32, 1, (28, 4)),
+                                                           (64, 64, 1, (4, 4)), (64, 16, 0, (8, 4)), (128, 96, 1, (4, 1))])
+def test_decode_step_with_a_frequency_table(E, d, rotary_dim, interleaved, heads):
+    """efim_decode_step_table: a caller-given frequency table (the Llama 3.1 long-context scaling)
+    and rotation of the leading rotary_dim elements only -- caches bit for bit, output within the
+    bar and identical to efim_rope_append_table followed by efim_extend_attention."""
+    c = np.array([0, 31, 32, 63, 700, 2047, 4100], dtype=np.int32)
+    b = W.make_batch("c1", seed=95 + rotary_dim, lengths=(c, np.ones_like(c)), heads=heads, head_dim=d)
+    table = O.scaled_inv_freq(rotary_dim, 5.0e5, 8.0, 1.0, 4.0, 8192)
+    kc, vc = U.oracle_cache(b)
+    kc_ref, vc_ref = kc.copy(), vc.copy()
+    q_ref, _ = O.rope_append_table(b.cached_len, b.new_len, b.block_table, b.page_size, b.q_new, b.k_new, b.v_new,
+                                   kc_ref, vc_ref, table, rotary_dim, bool(interleaved))
+    ref = O.extend_attention(b.cached_len, b.new_len, b.block_table, b.page_size, q_ref, kc_ref, vc_ref)
+    tab = torch.from_numpy(b.block_table).cuda()
+    desc = U.make_desc(E, b, tab)
+    q, kcd, vcd = U.dev_bits(b.q_new), U.dev_bits(kc), U.dev_bits(vc)
+    out = torch.full(q.shape, 0x7FC1, dtype=torch.int16, device="cuda")
+    nbytes = E.efim_decode_workspace_bytes(desc)
+    ws = torch.full((nbytes,), 0xA5, dtype=torch.uint8, device="cuda")
+    E.efim_decode_step_table(desc, q, U.dev_bits(b.k_new), U.dev_bits(b.v_new), kcd, vcd, out, table, rotary_dim,
+                             interleaved, 0.0, ws, nbytes)
+    torch.cuda.synchronize()
+    assert np.array_equal(U.host_bits(q), b.q_new), "q must stay as given"
+    assert np.array_equal(U.host_bits(kcd), kc_ref) and np.array_equal(U.host_bits(vcd), vc_ref)
+    U.assert_close(U.host_bits(out), ref, "rotary_dim %d" % rotary_dim)
+    # the two-call path on the same inputs
+    q2, kc2, vc2 = U.dev_bits(b.q_new), U.dev_bits(kc), U.dev_bits(vc)
+    E.efim_rope_append_table(desc, q2, U.dev_bits(b.k_new), U.dev_bits(b.v_new), kc2, vc2, table, rotary_dim, interleaved)
+    out2 = torch.full(q.shape, 0x7FC1, dtype=torch.int16, device="cuda")
+    nb2 = E.efim_extend_workspace_bytes(desc)
+    ws2 = torch.empty(max(nb2, 256), dtype=torch.uint8, device="cuda")
+    E.efim_extend_attention(desc, q2, kc2, vc2, out2, 0.0, ws2, nb2)
+    torch.cuda.synchronize()
+    assert np.array_equal(U.host_bits(out), U.host_bits(out2)), "fused and two-call outputs differ"
+
+
+def test_decode_step_table_rejects_bad_tables(E):
+    c = np.array([10, 20], dtype=np.int32)
+    b = W.make_batch("c1", lengths=(c, np.ones_like(c)), heads=(4, 4), head_dim=64)
+    desc = U.make_desc(E, b, torch.from_numpy(b.block_table).cuda())
+    good = O.rope_inv_freq(64, 1e4)
+    for table, rotary_dim in ((good, 8), (good, 24), (np.ones(64), 128), (np.full(32, np.nan), 64), (np.full(32, np.inf), 64)):
+        with pytest.raises(E.EfimError):
+            E.efim_decode_step_table(desc, 1, 1, 1, 1, 1, 2, table, rotary_dim, 0, 0.0, 1, 256)
