@@ -335,9 +335,12 @@ class HipEvent:
             raise RuntimeError("hipEventSynchronize failed: %d" % rc)
 
     def __del__(self):
-        if getattr(self, "handle", None) and self.handle.value and self._hip is not None:
-            self._hip.hipEventDestroy(self.handle)
-            self.handle = ctypes.c_void_p()
+        # (at interpreter shutdown the module globals may already be gone: then the process is
+        # ending and the runtime reclaims the event)
+        handle = getattr(self, "handle", None)
+        if handle is not None and handle.value and self._hip is not None:
+            self._hip.hipEventDestroy(handle)
+            handle.value = None
 
     def elapsed_ms(self, end):
         ms = ctypes.c_float()
