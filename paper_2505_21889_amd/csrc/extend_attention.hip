@@ -17,11 +17,11 @@
 // for the decode step, by the workgroup that finishes last.
 //
 // 8-bit caches (E4M3 codes, one scale per tensor): the gather moves the codes (half the bytes).
-// Key codes are read from the landed tile as they are and converted to bf16 operands in
-// registers (eight codes per lane and MFMA); value codes, which the PV product needs
-// transposed, are converted once per workgroup into a bf16 tile of the usual swizzled layout.
-// The codes' values are exact in bf16; the key scale is folded into the softmax scale and the
-// value scale into the final normalisation.
+// Both operands are read from the landed code tile as they are -- key codes eight at a time
+// along the head dimension, value codes through the 8-bit transposing LDS read (eight keys of
+// one head-dim element per lane) -- and converted to bf16 operands in registers.  The codes'
+// values are exact in bf16; the key scale is folded into the softmax scale and the value
+// scale into the final normalisation.
 #include <type_traits>
 
 #include "efim_internal.h"
@@ -44,6 +44,7 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+typedef __attribute__((ext_vector_type(2))) int i32x2;
 
 #define LDS_PTR(T) __attribute__((address_space(3))) T*
 
@@ -231,8 +232,8 @@ __device__ __forceinline__ void merge_rows(const AttnParams& p, const MergeItem&
 // (global q stays raw), the workgroup whose key range ends with the new token rotates its key,
 // stores key and value into the paged cache and patches them into its LDS tile.
 //
-// KV8: the caches hold E4M3 codes.  The stages then hold code tiles (half the size, so one
-// more of them fits) and one bf16 V tile, in front of them, receives the converted values.
+// KV8: the caches hold E4M3 codes.  The stages then hold code tiles (half the size, so twice
+// as many of them fit).
 //
 // KP ("key parallel"): every work item of the launch has at most 32 query rows (decode steps,
 // short increments).  One wave would be busy and the others idle: instead waves 0 and 1 both
@@ -249,20 +250,26 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
   constexpr int kGTileBytes = kKeyTile * kGRowBytes;
   constexpr int kGKeysPerLoad = 1024 / kGRowBytes;      // keys moved by one 1 KB wave load
   constexpr int kGLoadsPerMatrix = kGTileBytes / 1024;  // wave loads per K (or V) tile
-  // stage s: K tile at s * kStageBytes behind the compute tile (if any), V tile right behind it
+  // stage s: K tile at s * kStageBytes, V tile right behind it
   constexpr int kStageBytes = 2 * kGTileBytes;
-  constexpr int kComputeBytes = KV8 ? G::kTileBytes : 0;  // bf16 V tile of the 8-bit variant
-  // chunk swizzle of a key-code row: the 8-byte operand reads of 32 keys spread over all banks
+  // chunk swizzles of code rows.  Keys: the 8-byte operand reads of 32 consecutive keys spread
+  // over all banks.  Values: a 16-lane block of the transposing read touches keys
+  // {0..3, 8..11} (or {4..7, 12..15}) of a 16-key group at one 16-byte chunk; bits 0, 1 and 3
+  // of the key (D = 128; bits 1 and 3 for the 64-byte rows of D = 64, where two rows share a
+  // bank cycle) tell those eight rows apart.
   auto kswz8 = [](int row) { return D == 128 ? (row & 7) : ((row >> 1) & 3); };
+  auto vswz8 = [](int row) {
+    return D == 128 ? ((row & 3) | (((row >> 3) & 1) << 2)) : (((row >> 1) & 1) | (((row >> 3) & 1) << 1));
+  };
   // fused decode step: the rotated query rows of the tile, the new token's rotated key and its
   // value, cos/sin of the token's position -- behind the tile buffers
   constexpr int kFusedRows = 32;
-  constexpr int kTileBufBytes = kComputeBytes + STAGES * kStageBytes;
+  constexpr int kTileBufBytes = STAGES * kStageBytes;
   constexpr int kFusedBytes = FUSED ? kFusedRows * D * 2 + 2 * D * 2 + 128 * 8 : 0;
   static_assert(STAGES >= 2 && kTileBufBytes + kFusedBytes <= 160 * 1024, "stages must fit the 160 KB LDS");
   // One array, carved by hand.
   __shared__ __attribute__((aligned(1024))) char lds[kTileBufBytes + kFusedBytes];
-  char* const stages = lds + kComputeBytes;
+  char* const stages = lds;
   uint16_t* const s_q = reinterpret_cast<uint16_t*>(lds + kTileBufBytes);
   uint16_t* const s_kv = s_q + kFusedRows * D;
   double* const s_cs = reinterpret_cast<double*>(s_kv + 2 * D);
@@ -368,7 +375,7 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
   const uint32_t lds0 = (uint32_t)(uintptr_t)(LDS_PTR(char))lds;
   auto issue_tile = [&](int t, int stage) {
     if (issuer < 0) return;
-    const uint32_t kbuf = lds0 + kComputeBytes + stage * kStageBytes;
+    const uint32_t kbuf = lds0 + stage * kStageBytes;
     const uint32_t vbuf = kbuf + kGTileBytes;
     const int key0 = k_begin + t * kKeyTile;
     const bool full_tile = key0 + kKeyTile <= k_end;  // no row of the tile lies past the key range
@@ -388,7 +395,7 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
       const int idx = is_v ? load - kGLoadsPerMatrix : load;
       const int row0 = idx * kGKeysPerLoad;                    // first tile row of this load
       const int tile_row = row0 + g_key;
-      const int swz = KV8 ? (is_v ? 0 : kswz8(tile_row)) : (is_v ? G::vswz(tile_row) : G::kswz(tile_row));
+      const int swz = KV8 ? (is_v ? vswz8(tile_row) : kswz8(tile_row)) : (is_v ? G::vswz(tile_row) : G::kswz(tile_row));
       if constexpr (kGKeysPerLoad <= kMinPageSize) {
         if (full_tile) {
           // all rows of the load lie in one page and inside the range: page, head and first
@@ -427,6 +434,7 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
     else
       return *reinterpret_cast<const u32x4*>(ks + k_row_off + kb * 32 * G::kRowBytes + (((2 * st + hi) ^ k_swz) << 4));
   };
+  // (the same conversion serves the value operands)
   auto k_operand = [&](KRaw raw) -> bf16x8 {
     if constexpr (KV8) {
       u32x4 v;
@@ -449,6 +457,30 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
   const int v_chunk = 2 * (blk & 1) + ((w16 & 3) >> 1);     // 16-byte chunk inside a 32-d block
   const int v_sub = (w16 & 1) * 8;
   const int v_swz = G::vswz(v_key);                         // same for v_key + 8, + 16, ...
+  // 8-bit values: a 16-lane block reads an 8-key x 16-d patch of codes; lanes 2e and 2e+1 of the
+  // block supply the two 8-byte halves of patch row e, lane w receives column w (one head-dim
+  // element, the 8 rows).  The rows are the keys whose probabilities this half of the wave
+  // holds in the B operand: {0..3, 8..11} + 4 * (lane / 32) of the 16-key group.
+  const int v8_e = w16 >> 1;
+  const int v8_key = (v8_e < 4 ? v8_e : v8_e + 4) + (blk >> 1) * 4;
+  const int v8_chunk = blk & 1;                             // 16-byte chunk inside a 32-d block
+  const int v8_sub = (w16 & 1) * 8;
+  const int v8_swz = vswz8(v8_key);                         // same for v8_key + 16, + 32, ...
+  // V^T operand of the 16-key group ks4 and head-dim block d: raw LDS data, then as bf16
+  using VRaw = KRaw;
+  auto& v_operand = k_operand;
+  auto read_v_raw = [&](const char* vs, int ks4, int d) -> VRaw {
+    if constexpr (KV8) {
+      const char* at = vs + (ks4 * 16 + v8_key) * D + (((d * 2 + v8_chunk) ^ v8_swz) << 4) + v8_sub;
+      return __builtin_bit_cast(u32x2, __builtin_amdgcn_ds_read_tr8_b64_v2i32((LDS_PTR(i32x2))(at)));
+    } else {
+      const char* vrow = vs + (ks4 * 16 + v_key) * G::kRowBytes + v_sub;
+      const int off = ((d * 4 + v_chunk) ^ v_swz) << 4;
+      const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))(vrow + off));
+      const bf16x4 hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))(vrow + 8 * G::kRowBytes + off));
+      return __builtin_bit_cast(u32x4, __builtin_shufflevector(lo, hi4, 0, 1, 2, 3, 4, 5, 6, 7));
+    }
+  };
 
   auto compute_tile = [&](int t, const char* ks, const char* vs) {
     const int key0 = k_begin + t * kKeyTile;
@@ -471,29 +503,26 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
       for (int st = 0; st < G::kSteps; ++st)
         s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k_operand(ka[kb][st]), qb[st], s[kb], 0, 0, 0);
     }
-    bf16x4 va[4][G::kDBlocks][2];
+    VRaw va[4][G::kDBlocks];
     auto read_v = [&](int ks4) {
-      const char* vrow = vs + (ks4 * 16 + v_key) * G::kRowBytes + v_sub;
 #pragma unroll
-      for (int d = 0; d < G::kDBlocks; ++d) {
-        const int off = ((d * 4 + v_chunk) ^ v_swz) << 4;
-        va[ks4][d][0] = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))(vrow + off));
-        va[ks4][d][1] = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))(vrow + 8 * G::kRowBytes + off));
-      }
+      for (int d = 0; d < G::kDBlocks; ++d) va[ks4][d] = read_v_raw(vs, ks4, d);
     };
     read_v(0);
     read_v(1);
-    // 0x100 = LDS read, 0x008 = MFMA
-    __builtin_amdgcn_sched_group_barrier(0x100, G::kSteps, 0);
+    if constexpr (!KV8) {
+      // 0x100 = LDS read, 0x008 = MFMA
+      __builtin_amdgcn_sched_group_barrier(0x100, G::kSteps, 0);
 #pragma unroll
-    for (int st = 0; st < G::kSteps; ++st) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-    }
+      for (int st = 0; st < G::kSteps; ++st) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      }
 #pragma unroll
-    for (int st = 0; st < G::kSteps; ++st) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x100, G::kDBlocks / 2, 0);
+      for (int st = 0; st < G::kSteps; ++st) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, G::kDBlocks / 2, 0);
+      }
     }
     // element r of block kb is key  key0 + kb*32 + (r/4)*8 + hi*4 + r%4  of row i32
     if (key0 + kKeyTile > wave_min_vis) {
@@ -548,36 +577,8 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
       if (ks4 < 2) read_v(ks4 + 2);
 #pragma unroll
       for (int d = 0; d < G::kDBlocks; ++d) {
-        const bf16x8 a = __builtin_shufflevector(va[ks4][d][0], va[ks4][d][1], 0, 1, 2, 3, 4, 5, 6, 7);
-        o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[ks4], o[d], 0, 0, 0);
+        o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v_operand(va[ks4][d]), pb[ks4], o[d], 0, 0, 0);
       }
-    }
-  };
-
-  // 8-bit caches: the landed value codes (row-major) become the bf16 V tile at the front of the
-  // LDS, in the swizzled layout the transposing reads expect.  A thread takes 16 codes at a
-  // time: one 16-byte read, eight two-at-a-time conversions, two 16-byte writes.
-  auto convert_tile = [&](const char* codes) {
-    constexpr int kUnits = kKeyTile * kGChunks;
-#pragma unroll
-    for (int u0 = 0; u0 < kUnits; u0 += 64 * WAVES) {
-      const int u = u0 + tid;
-      if (kUnits % (64 * WAVES) != 0 && u >= kUnits) break;
-      const int row = u / kGChunks;
-      const int c = u - row * kGChunks;
-      const u32x4 w = *reinterpret_cast<const u32x4*>(codes + u * 16);
-      u32x4 lo, hi4;
-#pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        lo[2 * j] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w[j], 1.0f, false));
-        lo[2 * j + 1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w[j], 1.0f, true));
-        hi4[2 * j] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w[2 + j], 1.0f, false));
-        hi4[2 * j + 1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w[2 + j], 1.0f, true));
-      }
-      const int swz = G::vswz(row);
-      char* dst = lds + row * G::kRowBytes;
-      *reinterpret_cast<u32x4*>(dst + (((2 * c) ^ swz) << 4)) = lo;
-      *reinterpret_cast<u32x4*>(dst + (((2 * c + 1) ^ swz) << 4)) = hi4;
     }
   };
 
@@ -594,17 +595,11 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
 #pragma unroll
     for (int st = 0; st < G::kSteps; ++st)
       sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k_operand(ka[st]), qb[st], sc, 0, 0, 0);
-    bf16x4 va[2][G::kDBlocks][2];
+    VRaw va[2][G::kDBlocks];
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      const char* vrow = vs + ((kb * 2 + h) * 16 + v_key) * G::kRowBytes + v_sub;
+    for (int h = 0; h < 2; ++h)
 #pragma unroll
-      for (int d = 0; d < G::kDBlocks; ++d) {
-        const int off = ((d * 4 + v_chunk) ^ v_swz) << 4;
-        va[h][d][0] = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))(vrow + off));
-        va[h][d][1] = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_PTR(bf16x4))(vrow + 8 * G::kRowBytes + off));
-      }
-    }
+      for (int d = 0; d < G::kDBlocks; ++d) va[h][d] = read_v_raw(vs, kb * 2 + h, d);
     if (key0 + 32 > wave_min_vis) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
@@ -642,8 +637,7 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
     for (int h = 0; h < 2; ++h)
 #pragma unroll
       for (int d = 0; d < G::kDBlocks; ++d) {
-        const bf16x8 a = __builtin_shufflevector(va[h][d][0], va[h][d][1], 0, 1, 2, 3, 4, 5, 6, 7);
-        o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[h], o[d], 0, 0, 0);
+        o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v_operand(va[h][d]), pb[h], o[d], 0, 0, 0);
       }
   };
 
@@ -749,7 +743,7 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
               const int c = is_v ? w - kGChunks : w;
               const u32x4 val =
                   *reinterpret_cast<const u32x4*>(reinterpret_cast<const char*>(s_kv) + (is_v ? kGRowBytes : 0) + c * 16);
-              const int swz = KV8 ? (is_v ? 0 : kswz8(row)) : (is_v ? G::vswz(row) : G::kswz(row));
+              const int swz = KV8 ? (is_v ? vswz8(row) : kswz8(row)) : (is_v ? G::vswz(row) : G::kswz(row));
               char* tile = stages + s0 * kStageBytes + (is_v ? kGTileBytes : 0);
               *reinterpret_cast<u32x4*>(tile + row * kGRowBytes + ((c ^ swz) << 4)) = val;
               if (row == prow) {
@@ -762,15 +756,7 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
             __syncthreads();
           }
         }
-        if constexpr (KV8) {
-          // every wave is done with the previous bf16 V tile (loop-top barrier); the second
-          // barrier publishes the converted one
-          convert_tile(stages + s0 * kStageBytes + kGTileBytes);
-          __syncthreads();
-          step(t, stages + s0 * kStageBytes, lds);
-        } else {
-          step(t, stages + s0 * kStageBytes, stages + s0 * kStageBytes + kGTileBytes);
-        }
+        step(t, stages + s0 * kStageBytes, stages + s0 * kStageBytes + kGTileBytes);
       }
     }
   }
@@ -963,8 +949,8 @@ void launch_kernel(int head_dim, bool wide, bool fp8, bool few_rows, dim3 grid, 
                    hipStream_t stream) {
 #define EFIM_ATTN_LAUNCH2(DD, F8, KP)                                                              \
   do {                                                                                             \
-    if (wide) extend_attention_kernel<DD, 8, F8 ? 4 : 3, FUSED, F8, KP><<<grid, 512, 0, stream>>>(p); \
-    else extend_attention_kernel<DD, 4, F8 ? 3 : 2, FUSED, F8, KP><<<grid, 256, 0, stream>>>(p);   \
+    if (wide) extend_attention_kernel<DD, 8, F8 ? 5 : 3, FUSED, F8, KP><<<grid, 512, 0, stream>>>(p); \
+    else extend_attention_kernel<DD, 4, F8 ? 4 : 2, FUSED, F8, KP><<<grid, 256, 0, stream>>>(p);   \
   } while (0)
 #define EFIM_ATTN_LAUNCH(DD, F8)                                               \
   do {                                                                         \
