@@ -60,7 +60,7 @@ struct Tuning {
   int xcd_grouping = 1;
   int num_slots = 0;
   int row_tile = 0;  // 0 automatic, 128 or 256 forced
-  int fused_merge = -1;  // split key ranges combined inside the main kernel: -1 decode step only, 0 never, 1 always
+  int fused_merge = -1;  // split key ranges combined inside the main kernel: -1 when all items have few rows, 0 never, 1 always
 };
 Tuning& tuning();
 

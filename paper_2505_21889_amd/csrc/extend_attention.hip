@@ -935,11 +935,12 @@ namespace {
 
 // Split key ranges are combined inside the main kernel or by merge_kernel in a second launch.
 // In-kernel merging sends the partial results through device-coherent (write-through) stores;
-// that pays for the few rows of a decode step, where it saves a launch, and costs more than
-// the launch once a tile has many rows, so by default only the decode step uses it.
-bool use_tickets(const Plan& plan, bool decode) {
+// that pays when every tile has few rows (decode steps, short increments), where it saves a
+// launch, and costs more than the launch once a tile has many rows, so by default it is used
+// when no work item has more than 32 query rows.
+bool use_tickets(const Plan& plan) {
   const int knob = tuning().fused_merge;
-  const bool want = knob < 0 ? decode : knob != 0;
+  const bool want = knob < 0 ? plan.max_item_rows <= 32 : knob != 0;
   return want && !plan.merges.empty() && plan.merges.size() <= (size_t)kTicketsPerSlot;
 }
 
@@ -983,7 +984,7 @@ int launch_extend_attention(const efim_batch_t* b, const Plan& plan, const char*
                             float sm_scale, const CacheFormat& fmt, void* workspace, hipStream_t stream) {
   AttnParams p;
   fill_params(&p, b, plan, header, q, k_cache, v_cache, out, sm_scale, fmt, static_cast<char*>(workspace));
-  if (use_tickets(plan, false)) p.ticket_base = stage_slot * kTicketsPerSlot;
+  if (use_tickets(plan)) p.ticket_base = stage_slot * kTicketsPerSlot;
 
   const dim3 grid((unsigned)plan.items.size());
   const Tuning& tn = tuning();
@@ -1003,7 +1004,7 @@ int launch_decode_step(const efim_batch_t* b, const Plan& plan, const char* head
                        const CacheFormat& fmt, void* workspace, hipStream_t stream) {
   AttnParams p;
   fill_params(&p, b, plan, header, q, k_cache, v_cache, out, sm_scale, fmt, static_cast<char*>(workspace));
-  if (use_tickets(plan, true)) p.ticket_base = stage_slot * kTicketsPerSlot;
+  if (use_tickets(plan)) p.ticket_base = stage_slot * kTicketsPerSlot;
   p.k_new = static_cast<const uint16_t*>(k_new);
   p.v_new = static_cast<const uint16_t*>(v_new);
   p.k_cache_w = static_cast<uint16_t*>(k_cache);
