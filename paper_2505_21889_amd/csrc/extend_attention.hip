@@ -935,12 +935,14 @@ namespace {
 
 // Split key ranges are combined inside the main kernel or by merge_kernel in a second launch.
 // In-kernel merging sends the partial results through device-coherent (write-through) stores;
-// that pays when every tile has few rows (decode steps, short increments), where it saves a
-// launch, and costs more than the launch once a tile has many rows, so by default it is used
-// when no work item has more than 32 query rows.
+// that pays when every tile has very few rows (decode steps of the usual head groupings),
+// where it saves a launch, and costs more than the launch as the rows grow (measured on a
+// 28/4-head step: 1.7 us gained at 7 rows per tile, 6 us lost at 28), so by default it is used
+// when no work item has more than 8 query rows.
+constexpr int kTicketMergeMaxRows = 8;
 bool use_tickets(const Plan& plan) {
   const int knob = tuning().fused_merge;
-  const bool want = knob < 0 ? plan.max_item_rows <= 32 : knob != 0;
+  const bool want = knob < 0 ? plan.max_item_rows <= kTicketMergeMaxRows : knob != 0;
   return want && !plan.merges.empty() && plan.merges.size() <= (size_t)kTicketsPerSlot;
 }
 
