@@ -322,3 +322,21 @@ def test_fp8_random_decode_step(E, seed):
         E.efim_set_tuning(E.EFIM_TUNE_ROW_TILE, 0)
     assert np.array_equal(kc_got, kc_ref) and np.array_equal(vc_got, vc_ref)
     U.assert_close(got, ref, "%s %s d%d" % (cached.tolist(), heads, d), scale_abs_with_output=True)
+
+
+@pytest.mark.parametrize("base", ["c2", "c3"])
+def test_fp8_benchmark_shapes(E, base):
+    """The decode-like steps the benchmark times on the 8-bit cache (batch shapes of c2 / c3,
+    one new token per request, default planner): attention call and single-launch decode step
+    against the oracle on the whole output, codes byte for byte."""
+    spec = W.make_batch(base, with_history=False, with_tensors=False)
+    b = W.make_batch(base, lengths=(spec.cached_len, np.ones_like(spec.new_len)))
+    scale = 4.0 * b.sigma / 448.0   # as in the benchmark
+    kc, vc = oracle_cache8(b, scale, scale)
+    q_ref, kc_ref, vc_ref, ref = oracle_step8(b, kc, vc, scale, scale)
+    got, kc_got, vc_got, _ = run_decode8(E, b, kc, vc, scale, scale)
+    assert np.array_equal(kc_got, kc_ref) and np.array_equal(vc_got, vc_ref)
+    max_abs, rel = U.assert_close(got, ref, base + " decode step")
+    print("%s fp8 decode step: max_abs %.3e rel_l2 %.3e" % (base, max_abs, rel))
+    max_abs, rel = U.assert_close(gpu_attention8(E, b, q_ref, kc_ref, vc_ref, scale, scale), ref, base + " attention")
+    print("%s fp8 attention:   max_abs %.3e rel_l2 %.3e" % (base, max_abs, rel))
