@@ -176,7 +176,8 @@ typedef enum efim_tuning_key {
   EFIM_TUNE_XCD_GROUPING = 1, /* 1 (default): items sharing K/V are placed on one XCD; 0: plain cost order */
   EFIM_TUNE_NUM_SLOTS = 2,  /* concurrent workgroup slots assumed by the planner; 0 = query the device */
   EFIM_TUNE_ROW_TILE = 3,   /* query rows per workgroup: 0 automatic (default), 128 or 256 */
-  EFIM_TUNE_FUSED_MERGE = 4 /* where split key ranges are combined: -1 (default) inside the kernel when no work item has more than 8 query rows (decode steps of the usual head groupings), by a second launch otherwise; 0 always a second launch; 1 always inside the kernel */
+  EFIM_TUNE_FUSED_MERGE = 4, /* where split key ranges are combined: -1 (default) inside the kernel when no work item has more than 8 query rows (decode steps of the usual head groupings), by a second launch otherwise; 0 always a second launch; 1 always inside the kernel */
+  EFIM_TUNE_DEVICE_PLAN = 5 /* 1 (default): from the second launch of an unchanged batch on, the kernels read their work list from a copy in device memory (work lists up to 2 MiB); 0: always from pinned host memory */
 } efim_tuning_key_t;
 
 int efim_set_tuning(int key, int value);

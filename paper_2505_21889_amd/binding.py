@@ -25,6 +25,7 @@ EFIM_TUNE_XCD_GROUPING = 1
 EFIM_TUNE_NUM_SLOTS = 2
 EFIM_TUNE_ROW_TILE = 3
 EFIM_TUNE_FUSED_MERGE = 4
+EFIM_TUNE_DEVICE_PLAN = 5
 
 
 class EfimBatch(ctypes.Structure):

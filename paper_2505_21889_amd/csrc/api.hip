@@ -54,8 +54,8 @@ std::mutex g_stage_mutex;
     }                                                   \
   } while (0)
 
-// Copies the plan header into the next free slot; *dev_header receives its device address.
-int stage_plan(const Plan& plan, StageSlot** slot_out, const char** dev_header) {
+// Takes the next slot of the ring, waiting for the launches that last used it.
+int acquire_slot(StageSlot** slot_out) {
   StageSlot& s = g_stage[g_stage_next];
   g_stage_next = (g_stage_next + 1) % kStageSlots;
   if (!s.done) EFIM_HIP(hipEventCreateWithFlags(&s.done, hipEventDisableTiming));
@@ -63,6 +63,13 @@ int stage_plan(const Plan& plan, StageSlot** slot_out, const char** dev_header) 
     EFIM_HIP(hipEventSynchronize(s.done));
     s.in_flight = false;
   }
+  *slot_out = &s;
+  return EFIM_OK;
+}
+
+// Writes the plan header into a slot; *dev_header receives its device address.
+int fill_slot(const Plan& plan, StageSlot* slot, const char** dev_header) {
+  StageSlot& s = *slot;
   if (s.capacity < plan.header_bytes) {
     if (s.host) (void)hipHostFree(s.host);
     s.host = s.dev = nullptr;
@@ -82,9 +89,110 @@ int stage_plan(const Plan& plan, StageSlot** slot_out, const char** dev_header) 
   }
   if (!plan.merges.empty())
     std::memcpy(h + plan.off_merges, plan.merges.data(), plan.merges.size() * sizeof(MergeItem));
-  *slot_out = &s;
   *dev_header = static_cast<const char*>(s.dev);
   return EFIM_OK;
+}
+
+// Device-resident copies of recently staged work lists.  A workgroup starts by reading its work
+// item; from pinned host memory that read crosses the host link and nothing else can begin
+// until it returns, so a plan that is launched again (an engine calls once per layer with the
+// same batch) is read from device memory from its second launch on.  The first launch of a plan
+// reads the pinned slot and enqueues the copy behind its kernels.  Two buffers, used in turn, so
+// that the copy of a new plan seldom has to wait for launches still reading an old one.
+constexpr int kPlanCopies = 2;
+constexpr size_t kPlanCopyBytes = size_t(2) << 20;  // larger work lists are read from the pinned slot
+__device__ __align__(256) unsigned char g_plan_copy_mem[kPlanCopies][kPlanCopyBytes];
+
+struct PlanCopy {
+  uint64_t plan_id = 0;          // 0: empty
+  hipStream_t stream = nullptr;  // stream the copy was enqueued on
+  hipEvent_t ready = nullptr;    // recorded behind the copy
+  hipEvent_t last_use = nullptr; // recorded behind the latest launch that reads the buffer
+};
+// ready and last_use point at the 'done' events of ring slots.  Such an event is recorded again
+// only after the host has waited for its previous record, so a wait on it at any later time
+// still implies that the work it was first recorded behind has finished.
+PlanCopy g_plan_copy[kPlanCopies];
+int g_plan_copy_next = 0;
+unsigned char* g_plan_copy_base = nullptr;
+int g_plan_copy_device = -1;
+
+// Device address of copy buffer i on the device that first used the library; nullptr on others.
+unsigned char* plan_copy_buffer(int i) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) return nullptr;
+  if (!g_plan_copy_base) {
+    void* base = nullptr;
+    if (hipGetSymbolAddress(&base, HIP_SYMBOL(g_plan_copy_mem)) != hipSuccess || !base) {
+      (void)hipGetLastError();
+      return nullptr;
+    }
+    g_plan_copy_base = static_cast<unsigned char*>(base);
+    g_plan_copy_device = dev;
+  }
+  if (dev != g_plan_copy_device) return nullptr;
+  return g_plan_copy_base + (size_t)i * kPlanCopyBytes;
+}
+
+// Chooses where the kernels of one call read the work list from.  *copy_out is the device copy
+// the call reads (to be marked used behind the launch) or, with *enqueue_copy set, the one to
+// fill from the slot behind the launch; nullptr when the call only uses the pinned slot.
+int stage_plan(const Plan& plan, hipStream_t stream, StageSlot** slot_out, const char** dev_header,
+               PlanCopy** copy_out, bool* enqueue_copy) {
+  *copy_out = nullptr;
+  *enqueue_copy = false;
+  int rc = acquire_slot(slot_out);
+  if (rc != EFIM_OK) return rc;
+  const bool want_copy = tuning().device_plan != 0 && plan.header_bytes <= kPlanCopyBytes;
+  if (want_copy) {
+    for (int i = 0; i < kPlanCopies; ++i) {
+      PlanCopy& c = g_plan_copy[i];
+      if (c.plan_id != plan.id) continue;
+      unsigned char* buf = plan_copy_buffer(i);
+      if (!buf) break;
+      if (c.stream != stream) EFIM_HIP(hipStreamWaitEvent(stream, c.ready, 0));
+      *dev_header = reinterpret_cast<const char*>(buf);
+      *copy_out = &c;
+      return EFIM_OK;
+    }
+  }
+  rc = fill_slot(plan, *slot_out, dev_header);
+  if (rc != EFIM_OK) return rc;
+  if (want_copy && plan_copy_buffer(0)) {
+    *copy_out = &g_plan_copy[g_plan_copy_next];
+    g_plan_copy_next = (g_plan_copy_next + 1) % kPlanCopies;
+    *enqueue_copy = true;
+  }
+  return EFIM_OK;
+}
+
+// Behind the launches of a call: fills or marks the device copy, then marks the slot busy until
+// everything enqueued so far on the stream has run.
+void finish_stage(const Plan& plan, hipStream_t stream, StageSlot* slot, PlanCopy* copy, bool enqueue_copy) {
+  bool copied = false;
+  if (copy && enqueue_copy) {
+    unsigned char* buf = plan_copy_buffer((int)(copy - g_plan_copy));
+    copy->plan_id = 0;
+    bool ok = buf != nullptr;
+    // launches on other streams may still read the plan this buffer held
+    if (ok && copy->last_use) ok = hipStreamWaitEvent(stream, copy->last_use, 0) == hipSuccess;
+    if (ok) ok = hipMemcpyAsync(buf, slot->host, plan.header_bytes, hipMemcpyHostToDevice, stream) == hipSuccess;
+    if (!ok) (void)hipGetLastError();
+    copied = ok;
+  }
+  if (hipEventRecord(slot->done, stream) == hipSuccess) {
+    slot->in_flight = true;
+    if (copied) {
+      copy->plan_id = plan.id;
+      copy->stream = stream;
+      copy->ready = slot->done;
+      copy->last_use = slot->done;
+    } else if (copy && !enqueue_copy) {
+      copy->last_use = slot->done;
+    }
+  } else {
+    (void)hipStreamSynchronize(stream);
+  }
 }
 
 // A serving engine calls efim_extend_attention once per layer with the same batch, so the last
@@ -92,6 +200,7 @@ int stage_plan(const Plan& plan, StageSlot** slot_out, const char** dev_header) 
 struct PlanCache {
   std::vector<int32_t> key;
   Plan plan;
+  uint64_t next_id = 0;
   bool valid = false;
 };
 PlanCache g_plan_cache;
@@ -120,6 +229,7 @@ const Plan& cached_plan(const efim_batch_t* b) {
   plan_key(b, slots, &key);
   if (!g_plan_cache.valid || g_plan_cache.key != key) {
     build_plan(b, slots, &g_plan_cache.plan);
+    g_plan_cache.plan.id = ++g_plan_cache.next_id;
     g_plan_cache.key = key;
     g_plan_cache.valid = true;
   }
@@ -232,13 +342,13 @@ int extend_attention_base(const efim_batch_t* batch, const void* q, const void* 
   std::lock_guard<std::mutex> stage_lock(g_stage_mutex);
   StageSlot* slot = nullptr;
   const char* header = nullptr;
-  rc = stage_plan(plan, &slot, &header);
+  PlanCopy* copy = nullptr;
+  bool enqueue_copy = false;
+  rc = stage_plan(plan, s, &slot, &header, &copy, &enqueue_copy);
   if (rc != EFIM_OK) return rc;
   rc = launch_extend_attention(batch, plan, header, (int)(slot - g_stage), q, k_cache, v_cache, out, sm_scale,
                                fmt, workspace, s);
-  // the slot is busy until everything enqueued so far on the stream has run
-  if (hipEventRecord(slot->done, s) == hipSuccess) slot->in_flight = true;
-  else (void)hipStreamSynchronize(s);
+  finish_stage(plan, s, slot, copy, enqueue_copy);
   return rc;
 }
 
@@ -324,12 +434,13 @@ int decode_step_base(const efim_batch_t* batch, const void* q, const void* k_new
   std::lock_guard<std::mutex> stage_lock(g_stage_mutex);
   StageSlot* slot = nullptr;
   const char* header = nullptr;
-  rc = stage_plan(plan, &slot, &header);
+  PlanCopy* copy = nullptr;
+  bool enqueue_copy = false;
+  rc = stage_plan(plan, s, &slot, &header, &copy, &enqueue_copy);
   if (rc != EFIM_OK) return rc;
   rc = launch_decode_step(batch, plan, header, (int)(slot - g_stage), q, k_new, v_new, k_cache, v_cache, out,
                           inv_freq, rotary_dim, rope_interleaved, sm_scale, fmt, workspace, s);
-  if (hipEventRecord(slot->done, s) == hipSuccess) slot->in_flight = true;
-  else (void)hipStreamSynchronize(s);
+  finish_stage(plan, s, slot, copy, enqueue_copy);
   return rc;
 }
 
@@ -399,6 +510,10 @@ int efim_set_tuning(int key, int value) {
     case EFIM_TUNE_FUSED_MERGE:
       if (value < -1 || value > 1) return EFIM_ERR_INVALID_ARG;
       tuning().fused_merge = value;
+      return EFIM_OK;
+    case EFIM_TUNE_DEVICE_PLAN:
+      if (value != 0 && value != 1) return EFIM_ERR_INVALID_ARG;
+      tuning().device_plan = value;
       return EFIM_OK;
     default:
       return EFIM_ERR_INVALID_ARG;

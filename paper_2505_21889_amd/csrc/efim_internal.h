@@ -61,10 +61,12 @@ struct Tuning {
   int num_slots = 0;
   int row_tile = 0;  // 0 automatic, 128 or 256 forced
   int fused_merge = -1;  // split key ranges combined inside the main kernel: -1 when all items have few rows, 0 never, 1 always
+  int device_plan = 1;   // repeated launches of a plan read the work list from a device-resident copy
 };
 Tuning& tuning();
 
 struct Plan {
+  uint64_t id = 0;          // distinct for every plan the cache has built
   int rows_per_item = 128;  // query rows per workgroup tile (32 per wave)
   int max_item_rows = 0;    // largest row_count of a work item
   std::vector<ReqInfo> reqs;
