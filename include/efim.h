@@ -250,6 +250,15 @@ int efim_decode_step_fp8(const efim_batch_t* batch, const void* q, const void* k
                          void* k_cache, void* v_cache, void* out, double rope_base, int rope_interleaved,
                          float sm_scale, float k_scale, float v_scale, void* workspace, size_t workspace_bytes,
                          void* stream);
+/* The 8-bit append and decode step with the caller's frequency table over the first rotary_dim
+ * features (arguments as efim_rope_append_table / efim_decode_step_table, scales as above). */
+int efim_rope_append_fp8_table(const efim_batch_t* batch, void* q, const void* k_new, const void* v_new,
+                               void* k_cache, void* v_cache, const double* inv_freq, int rotary_dim,
+                               int rope_interleaved, float k_scale, float v_scale, void* stream);
+int efim_decode_step_fp8_table(const efim_batch_t* batch, const void* q, const void* k_new, const void* v_new,
+                               void* k_cache, void* v_cache, void* out, const double* inv_freq, int rotary_dim,
+                               int rope_interleaved, float sm_scale, float k_scale, float v_scale,
+                               void* workspace, size_t workspace_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------------------
  * Session pool: the FIM -> EFIM prompt rewrite in front of the engine (Sec. 3.1, steps 1-5

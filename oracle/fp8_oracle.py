@@ -96,6 +96,29 @@ def rope_append_fp8(cached_len, new_len, block_table, page_size, q_new, k_new, v
     return q_roped, k_codes
 
 
+def rope_append_fp8_table(cached_len, new_len, block_table, page_size, q_new, k_new, v_new,
+                          k_cache, v_cache, inv_freq, rotary_dim, k_scale, v_scale, interleaved=False):
+    """rope_append_fp8 with a caller-given frequency table (rotary_dim/2 entries) and a rotation
+    of the leading rotary_dim elements only, as efim_oracle.rope_append_table rotates."""
+    pos = O.new_token_positions(cached_len, new_len)
+    cos, sin = O.rope_cos_sin_table(pos, inv_freq)
+    k_roped = O.f64_to_bf16(O.rope_rotate_leading(O.bf16_to_f64(k_new), cos, sin, rotary_dim, interleaved))
+    q_roped = None
+    if q_new is not None:
+        q_roped = O.f64_to_bf16(O.rope_rotate_leading(O.bf16_to_f64(q_new), cos, sin, rotary_dim, interleaved))
+    k_codes = quantize_bf16(k_roped, k_scale)
+    v_codes = quantize_bf16(v_new, v_scale)
+    row = 0
+    for r, (c, n) in enumerate(zip(cached_len, new_len)):
+        for i in range(int(n)):
+            p = int(c) + i
+            page = int(block_table[r, p // page_size])
+            k_cache[page, :, p % page_size, :] = k_codes[row]
+            v_cache[page, :, p % page_size, :] = v_codes[row]
+            row += 1
+    return q_roped, k_codes
+
+
 def extend_attention_rows_fp8(r, q_head, cached_len, new_len, block_table, page_size, q_roped,
                               k_cache, v_cache, k_scale, v_scale, sm_scale=None, rows=None):
     """efim_oracle.extend_attention_rows over E4M3 caches (fp64 [len(rows), D])."""

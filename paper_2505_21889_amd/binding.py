@@ -100,6 +100,12 @@ def _load():
     lib.efim_decode_step_fp8.argtypes = [bp, vp, vp, vp, vp, vp, vp, ctypes.c_double, i32, f32, f32, f32, vp,
                                          ctypes.c_size_t, vp]
     lib.efim_decode_step_fp8.restype = i32
+    f64p = ctypes.POINTER(ctypes.c_double)
+    lib.efim_rope_append_fp8_table.argtypes = [bp, vp, vp, vp, vp, vp, f64p, i32, i32, f32, f32, vp]
+    lib.efim_rope_append_fp8_table.restype = i32
+    lib.efim_decode_step_fp8_table.argtypes = [bp, vp, vp, vp, vp, vp, vp, f64p, i32, i32, f32, f32, f32, vp,
+                                               ctypes.c_size_t, vp]
+    lib.efim_decode_step_fp8_table.restype = i32
     lib.efim_extend_plan_items.argtypes = [bp, vp, i64]
     lib.efim_extend_plan_items.restype = i64
     lib.efim_set_tuning.argtypes = [i32, i32]
@@ -134,6 +140,7 @@ EXPORTED_SYMBOLS = (
     "efim_rope_append", "efim_rope_append_table", "efim_extend_workspace_bytes", "efim_extend_attention",
     "efim_decode_workspace_bytes", "efim_decode_step", "efim_decode_step_table",
     "efim_rope_append_fp8", "efim_extend_attention_fp8", "efim_decode_step_fp8",
+    "efim_rope_append_fp8_table", "efim_decode_step_fp8_table",
     "efim_extend_plan_items", "efim_set_tuning", "efim_set_kernel_events", "efim_status_string",
     "efim_last_hip_error", "efim_version",
     "efim_session_pool_create", "efim_session_pool_destroy", "efim_session_transform", "efim_session_prompt",
@@ -261,6 +268,35 @@ def efim_decode_step_fp8(batch, q, k_new, v_new, k_cache, v_cache, out, rope_bas
                                      float(sm_scale), float(k_scale), float(v_scale), _ptr(workspace),
                                      int(workspace_bytes), _stream_ptr(stream)),
            "efim_decode_step_fp8")
+
+
+def _freq_table(inv_freq, rotary_dim):
+    table = np.ascontiguousarray(np.asarray(inv_freq, dtype=np.float64).reshape(-1))
+    assert table.size >= int(rotary_dim) // 2, "inv_freq needs rotary_dim / 2 entries"
+    return table
+
+
+def efim_rope_append_fp8_table(batch, q, k_new, v_new, k_cache, v_cache, inv_freq, rotary_dim, rope_interleaved,
+                               k_scale, v_scale, stream=None):
+    table = _freq_table(inv_freq, rotary_dim)
+    _check(_lib.efim_rope_append_fp8_table(ctypes.byref(batch.c), _ptr(q), _ptr(k_new), _ptr(v_new),
+                                           _ptr(k_cache), _ptr(v_cache),
+                                           table.ctypes.data_as(ctypes.POINTER(ctypes.c_double)), int(rotary_dim),
+                                           int(rope_interleaved), float(k_scale), float(v_scale),
+                                           _stream_ptr(stream)),
+           "efim_rope_append_fp8_table")
+
+
+def efim_decode_step_fp8_table(batch, q, k_new, v_new, k_cache, v_cache, out, inv_freq, rotary_dim,
+                               rope_interleaved, sm_scale, k_scale, v_scale, workspace, workspace_bytes,
+                               stream=None):
+    table = _freq_table(inv_freq, rotary_dim)
+    _check(_lib.efim_decode_step_fp8_table(ctypes.byref(batch.c), _ptr(q), _ptr(k_new), _ptr(v_new),
+                                           _ptr(k_cache), _ptr(v_cache), _ptr(out),
+                                           table.ctypes.data_as(ctypes.POINTER(ctypes.c_double)), int(rotary_dim),
+                                           int(rope_interleaved), float(sm_scale), float(k_scale), float(v_scale),
+                                           _ptr(workspace), int(workspace_bytes), _stream_ptr(stream)),
+           "efim_decode_step_fp8_table")
 
 
 def efim_extend_plan_items(batch):

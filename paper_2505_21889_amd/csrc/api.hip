@@ -296,9 +296,11 @@ int efim_rope_append(const efim_batch_t* batch, void* q, const void* k_new, cons
                           CacheFormat());
 }
 
-int efim_rope_append_table(const efim_batch_t* batch, void* q, const void* k_new, const void* v_new,
+namespace {
+
+int rope_append_table_base(const efim_batch_t* batch, void* q, const void* k_new, const void* v_new,
                            void* k_cache, void* v_cache, const double* inv_freq, int rotary_dim,
-                           int rope_interleaved, void* stream) {
+                           int rope_interleaved, void* stream, const CacheFormat& fmt) {
   int64_t total = 0;
   int rc = validate_batch(batch, &total);
   if (rc != EFIM_OK) return rc;
@@ -307,7 +309,28 @@ int efim_rope_append_table(const efim_batch_t* batch, void* q, const void* k_new
   for (int j = 0; j < rotary_dim / 2; ++j)
     if (!(inv_freq[j] == inv_freq[j]) || inv_freq[j] - inv_freq[j] != 0.0) return EFIM_ERR_INVALID_ARG;  // NaN / inf
   return rope_append_checked(batch, q, k_new, v_new, k_cache, v_cache, inv_freq, rotary_dim, rope_interleaved,
-                             stream, total);
+                             stream, total, fmt);
+}
+
+}  // namespace
+
+int efim_rope_append_table(const efim_batch_t* batch, void* q, const void* k_new, const void* v_new,
+                           void* k_cache, void* v_cache, const double* inv_freq, int rotary_dim,
+                           int rope_interleaved, void* stream) {
+  return rope_append_table_base(batch, q, k_new, v_new, k_cache, v_cache, inv_freq, rotary_dim,
+                                rope_interleaved, stream, CacheFormat());
+}
+
+int efim_rope_append_fp8_table(const efim_batch_t* batch, void* q, const void* k_new, const void* v_new,
+                               void* k_cache, void* v_cache, const double* inv_freq, int rotary_dim,
+                               int rope_interleaved, float k_scale, float v_scale, void* stream) {
+  if (!scale_ok(k_scale) || !scale_ok(v_scale)) return EFIM_ERR_INVALID_ARG;
+  CacheFormat fmt;
+  fmt.fp8 = true;
+  fmt.k_scale = k_scale;
+  fmt.v_scale = v_scale;
+  return rope_append_table_base(batch, q, k_new, v_new, k_cache, v_cache, inv_freq, rotary_dim,
+                                rope_interleaved, stream, fmt);
 }
 
 size_t efim_extend_workspace_bytes(const efim_batch_t* batch) {
@@ -475,6 +498,19 @@ int efim_decode_step_fp8(const efim_batch_t* batch, const void* q, const void* k
   if (!(rope_base > 0.0)) return EFIM_ERR_INVALID_ARG;
   return decode_step_base(batch, q, k_new, v_new, k_cache, v_cache, out, rope_base, nullptr, 0, rope_interleaved,
                           sm_scale, fmt, workspace, workspace_bytes, stream);
+}
+
+int efim_decode_step_fp8_table(const efim_batch_t* batch, const void* q, const void* k_new, const void* v_new,
+                               void* k_cache, void* v_cache, void* out, const double* inv_freq, int rotary_dim,
+                               int rope_interleaved, float sm_scale, float k_scale, float v_scale,
+                               void* workspace, size_t workspace_bytes, void* stream) {
+  if (!inv_freq || !scale_ok(k_scale) || !scale_ok(v_scale)) return EFIM_ERR_INVALID_ARG;
+  CacheFormat fmt;
+  fmt.fp8 = true;
+  fmt.k_scale = k_scale;
+  fmt.v_scale = v_scale;
+  return decode_step_base(batch, q, k_new, v_new, k_cache, v_cache, out, 0.0, inv_freq, rotary_dim,
+                          rope_interleaved, sm_scale, fmt, workspace, workspace_bytes, stream);
 }
 
 int64_t efim_extend_plan_items(const efim_batch_t* batch, efim_work_item_t* items, int64_t capacity) {

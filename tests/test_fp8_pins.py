@@ -160,6 +160,38 @@ def test_rope_append_fp8_writes_the_codes_of_the_bf16_cache_and_nothing_else():
     assert k_codes.shape == b.k_new.shape
 
 
+def test_rope_append_fp8_table_reduces_to_the_plain_call_and_to_the_bf16_table_call():
+    b = _small_batch()
+    d = b.head_dim
+    # the plain table over the whole head: byte for byte the plain 8-bit append
+    kc_a = np.full(b.cache_shape(), 0x55, dtype=np.uint8)
+    vc_a = kc_a.copy()
+    kc_b, vc_b = kc_a.copy(), vc_a.copy()
+    q_a, _ = F.rope_append_fp8(b.cached_len, b.new_len, b.block_table, b.page_size, b.q_new.copy(), b.k_new,
+                               b.v_new, kc_a, vc_a, b.rope_base, 0.5, 0.25)
+    q_b, _ = F.rope_append_fp8_table(b.cached_len, b.new_len, b.block_table, b.page_size, b.q_new.copy(), b.k_new,
+                                     b.v_new, kc_b, vc_b, O.rope_inv_freq(d, b.rope_base), d, 0.5, 0.25)
+    assert np.array_equal(q_a, q_b) and np.array_equal(kc_a, kc_b) and np.array_equal(vc_a, vc_b)
+    # a partial rotation with another table: the codes of what the bf16 table call stores
+    rotary_dim = d // 2
+    table = O.scaled_inv_freq(rotary_dim, 5.0e5, 8.0, 1.0, 4.0, 8192)
+    kc16 = np.zeros(b.cache_shape(), dtype=np.uint16)
+    vc16 = np.zeros(b.cache_shape(), dtype=np.uint16)
+    q16, k16 = O.rope_append_table(b.cached_len, b.new_len, b.block_table, b.page_size, b.q_new.copy(), b.k_new,
+                                   b.v_new, kc16, vc16, table, rotary_dim, True)
+    kc8 = np.zeros(b.cache_shape(), dtype=np.uint8)
+    vc8 = np.zeros(b.cache_shape(), dtype=np.uint8)
+    q8, k_codes = F.rope_append_fp8_table(b.cached_len, b.new_len, b.block_table, b.page_size, b.q_new.copy(),
+                                          b.k_new, b.v_new, kc8, vc8, table, rotary_dim, 0.5, 0.25, True)
+    assert np.array_equal(q8, q16)
+    assert np.array_equal(k_codes, F.quantize_bf16(k16, 0.5))
+    assert np.array_equal(k_codes[..., rotary_dim:], F.quantize_bf16(b.k_new[..., rotary_dim:], 0.5)), \
+        "features past rotary_dim are stored unrotated"
+    assert not np.array_equal(k_codes[..., :rotary_dim], F.quantize_bf16(b.k_new[..., :rotary_dim], 0.5))
+    written = kc16 != 0
+    assert np.array_equal(kc8[written], F.quantize_bf16(kc16[written], 0.5))
+
+
 def test_fp8_attention_equals_bf16_attention_when_the_codes_are_bf16_values():
     # E4M3 values times a power-of-two scale are bf16 numbers: the 8-bit cache and a bf16 cache
     # holding the same numbers must give the same attention output.

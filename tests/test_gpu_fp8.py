@@ -244,6 +244,68 @@ def test_fp8_decode_sequence(E):
         U.assert_close(got, ref, "step %d" % s)
 
 
+@pytest.mark.parametrize("d,rotary_dim,interleaved,heads", [(128, 128, 0, (8, 2)), (128, 64, 1, (4, 4)),
+                                                            (64, 32, 0, (8, 4)), (128, 96, 0, (14, 2))])
+def test_fp8_calls_with_a_frequency_table(E, d, rotary_dim, interleaved, heads):
+    """efim_rope_append_fp8_table and efim_decode_step_fp8_table: a caller-given table (the long
+    context scaling of the bf16 table tests) over the leading rotary_dim features.  Codes byte for
+    byte, q rotated as by the bf16 table call, outputs within the bar and identical between the
+    single launch and the two calls."""
+    k_scale, v_scale = 0.017, 0.04
+    c = np.array([0, 31, 32, 63, 700, 2047, 4100], dtype=np.int32)
+    b = W.make_batch("c1", seed=195 + rotary_dim, lengths=(c, np.ones_like(c)), heads=heads, head_dim=d)
+    table = O.scaled_inv_freq(rotary_dim, 5.0e5, 8.0, 1.0, 4.0, 8192)
+    kc, vc = oracle_cache8(b, k_scale, v_scale)
+    kc_ref, vc_ref = kc.copy(), vc.copy()
+    q_ref, _ = F.rope_append_fp8_table(b.cached_len, b.new_len, b.block_table, b.page_size, b.q_new, b.k_new,
+                                       b.v_new, kc_ref, vc_ref, table, rotary_dim, k_scale, v_scale,
+                                       bool(interleaved))
+    ref = F.extend_attention_fp8(b.cached_len, b.new_len, b.block_table, b.page_size, q_ref, kc_ref, vc_ref,
+                                 k_scale, v_scale)
+    desc = U.make_desc(E, b, torch.from_numpy(b.block_table).cuda())
+    # two calls
+    q2, kc2, vc2 = U.dev_bits(b.q_new), dev_u8(kc), dev_u8(vc)
+    E.efim_rope_append_fp8_table(desc, q2, U.dev_bits(b.k_new), U.dev_bits(b.v_new), kc2, vc2, table, rotary_dim,
+                                 interleaved, k_scale, v_scale)
+    out2 = torch.full(q2.shape, 0x7FC1, dtype=torch.int16, device="cuda")
+    nb2 = E.efim_extend_workspace_bytes(desc)
+    ws2 = torch.empty(max(nb2, 256), dtype=torch.uint8, device="cuda")
+    E.efim_extend_attention_fp8(desc, q2, kc2, vc2, out2, 0.0, k_scale, v_scale, ws2, nb2)
+    torch.cuda.synchronize()
+    assert np.array_equal(U.host_bits(q2), q_ref), "roped q"
+    assert np.array_equal(kc2.cpu().numpy(), kc_ref) and np.array_equal(vc2.cpu().numpy(), vc_ref)
+    U.assert_close(U.host_bits(out2), ref, "two calls, rotary_dim %d" % rotary_dim)
+    # single launch
+    q, kcd, vcd = U.dev_bits(b.q_new), dev_u8(kc), dev_u8(vc)
+    out = torch.full(q.shape, 0x7FC1, dtype=torch.int16, device="cuda")
+    nbytes = E.efim_decode_workspace_bytes(desc)
+    ws = torch.full((max(nbytes, 256),), 0xA5, dtype=torch.uint8, device="cuda")
+    E.efim_decode_step_fp8_table(desc, q, U.dev_bits(b.k_new), U.dev_bits(b.v_new), kcd, vcd, out, table,
+                                 rotary_dim, interleaved, 0.0, k_scale, v_scale, ws, ws.numel())
+    torch.cuda.synchronize()
+    assert np.array_equal(U.host_bits(q), b.q_new), "q must stay as given"
+    assert np.array_equal(kcd.cpu().numpy(), kc_ref) and np.array_equal(vcd.cpu().numpy(), vc_ref)
+    U.assert_close(U.host_bits(out), ref, "single launch, rotary_dim %d" % rotary_dim)
+    assert np.array_equal(U.host_bits(out), U.host_bits(out2)), "single launch and two calls differ"
+
+
+def test_fp8_table_calls_reject_bad_arguments(E):
+    c = np.array([10, 20], dtype=np.int32)
+    b = W.make_batch("c1", lengths=(c, np.ones_like(c)), heads=(4, 4), head_dim=64)
+    desc = U.make_desc(E, b, torch.from_numpy(b.block_table).cuda())
+    good = O.rope_inv_freq(64, 1e4)
+    for table, rotary_dim in ((good, 8), (good, 24), (np.ones(64), 128), (np.full(32, np.nan), 64)):
+        with pytest.raises(E.EfimError):
+            E.efim_rope_append_fp8_table(desc, 1, 1, 1, 1, 1, table, rotary_dim, 0, 1.0, 1.0)
+        with pytest.raises(E.EfimError):
+            E.efim_decode_step_fp8_table(desc, 1, 1, 1, 1, 1, 2, table, rotary_dim, 0, 0.0, 1.0, 1.0, 1, 256)
+    for bad in (0.0, float("inf")):
+        with pytest.raises(E.EfimError):
+            E.efim_rope_append_fp8_table(desc, 1, 1, 1, 1, 1, good, 64, 0, bad, 1.0)
+        with pytest.raises(E.EfimError):
+            E.efim_decode_step_fp8_table(desc, 1, 1, 1, 1, 1, 2, good, 64, 0, 0.0, 1.0, bad, 1, 256)
+
+
 def test_fp8_calls_reject_bad_scales(E):
     b = W.make_batch("c1", lengths=(np.array([4], dtype=np.int32), np.array([1], dtype=np.int32)), heads=(4, 4), head_dim=64)
     table = torch.from_numpy(b.block_table).cuda()
