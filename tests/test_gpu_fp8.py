@@ -402,3 +402,18 @@ def test_fp8_benchmark_shapes(E, base):
     print("%s fp8 decode step: max_abs %.3e rel_l2 %.3e" % (base, max_abs, rel))
     max_abs, rel = U.assert_close(gpu_attention8(E, b, q_ref, kc_ref, vc_ref, scale, scale), ref, base + " attention")
     print("%s fp8 attention:   max_abs %.3e rel_l2 %.3e" % (base, max_abs, rel))
+
+
+def test_fp8_one_very_long_context(E):
+    """131072 cached tokens behind one request next to a short one, one new token each: the decode
+    step over the codes, whole output against the oracle."""
+    c = np.array([131072, 300], dtype=np.int32)
+    b = W.make_batch("c1", seed=132, lengths=(c, np.ones_like(c)), heads=(4, 1), head_dim=128)
+    scale = 4.0 * b.sigma / 448.0
+    kc, vc = oracle_cache8(b, scale, scale)
+    q_ref, kc_ref, vc_ref, ref = oracle_step8(b, kc, vc, scale, scale)
+    got, kc_got, vc_got, _ = run_decode8(E, b, kc, vc, scale, scale)
+    assert np.array_equal(kc_got, kc_ref) and np.array_equal(vc_got, vc_ref)
+    max_abs, rel = U.assert_close(got, ref, "long context decode step")
+    print("fp8 long context: max_abs %.3e rel_l2 %.3e" % (max_abs, rel))
+    U.assert_close(gpu_attention8(E, b, q_ref, kc_ref, vc_ref, scale, scale), ref, "long context attention")

@@ -71,3 +71,17 @@ def test_c5_rope_append_bit_exact_on_sampled_requests(E):
         pages = b.block_table[r, : -(-int(b.cached_len[r] + b.new_len[r]) // b.page_size)]
         assert np.array_equal(kc_gpu[pages], kc_ref[pages])
         assert np.array_equal(vc_gpu[pages], vc_ref[pages])
+
+
+@pytest.mark.parametrize("heads,d,new", [((4, 1), 128, [3, 40]), ((2, 2), 64, [1, 1])])
+def test_one_very_long_context(E, heads, d, new):
+    """131072 cached tokens behind one request (2048 key tiles cut into many ranges, a block table
+    of 8192 pages) next to a short one; sampled rows (first, middle and last always) of a query
+    head per kv head against the oracle."""
+    c = np.array([131072, 300], dtype=np.int32)
+    b = W.make_batch("c1", seed=131, lengths=(c, np.array(new, dtype=np.int32)), heads=heads, head_dim=d)
+    assert b.block_table.shape[1] >= 8192
+    items = E.efim_extend_plan_items(U.make_desc(E, b, torch.from_numpy(b.block_table).cuda()))
+    assert len(items) > 64, "the long request is expected to be cut into many key ranges"
+    worst, rel = U.sampled_check(E, b, heads_per_req=heads[1], rows_per_head=max(new), seed=9)
+    print("long context: max_abs %.3e rel_l2 %.3e" % (worst, rel))
