@@ -85,6 +85,23 @@ constexpr float kSlack = 8.f;  // log2 units by which a row max may outgrow its 
 
 // Plain nested maxima: the compiler turns them into three-operand max instructions itself and,
 // unlike for hand-written assembly, inserts the wait states a read of fresh MFMA results needs.
+// Sum of sixteen bf16 probabilities (as rounded for the PV product, so the normaliser matches the
+// weights the product uses): two-element dot products with ones, one instruction per pair.
+__device__ __forceinline__ float sum_pairs(bf16x8 a, bf16x8 b) {
+  typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+  const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+  float acc = 0.f;
+  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(a, a, 0, 1), ones, acc, false);
+  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(a, a, 2, 3), ones, acc, false);
+  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(a, a, 4, 5), ones, acc, false);
+  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(a, a, 6, 7), ones, acc, false);
+  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(b, b, 0, 1), ones, acc, false);
+  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(b, b, 2, 3), ones, acc, false);
+  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(b, b, 4, 5), ones, acc, false);
+  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(b, b, 6, 7), ones, acc, false);
+  return acc;
+}
+
 __device__ __forceinline__ float max3(float a, float b, float c) {
   return __builtin_fmaxf(__builtin_fmaxf(a, b), c);
 }
@@ -526,13 +543,12 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
     }
     // element r of block kb is key  key0 + kb*32 + (r/4)*8 + hi*4 + r%4  of row i32
     if (key0 + kKeyTile > wave_min_vis) {
+      const int lim = n_vis - key0 - hi * 4;  // visible keys counted from this lane's first key of the tile
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int key = key0 + kb * 32 + (r >> 2) * 8 + hi * 4 + (r & 3);
-          if (key >= n_vis) s[kb][r] = -INFINITY;
-        }
+        for (int r = 0; r < 16; ++r)
+          if (kb * 32 + (r >> 2) * 8 + (r & 3) >= lim) s[kb][r] = -INFINITY;
     }
     // ---- online softmax (per-lane row statistics) ------------------------------------
     // m_run is a reference value, not necessarily the exact running max: it is only moved
@@ -558,17 +574,13 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
       m_run = m_next;
     }
     const float m_use = (m_run == -INFINITY) ? 0.f : m_run;
-    float psum = 0.f;
     bf16x8 pb[4];
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const float e = __builtin_amdgcn_exp2f(s[kb][r] * p.scale_log2 - m_use);
-        psum += e;
-        pb[kb * 2 + (r >> 3)][r & 7] = (__bf16)e;
-      }
-    l_run += psum;
+      for (int r = 0; r < 16; ++r)
+        pb[kb * 2 + (r >> 3)][r & 7] = (__bf16)__builtin_amdgcn_exp2f(s[kb][r] * p.scale_log2 - m_use);
+    l_run += sum_pairs(pb[0], pb[1]) + sum_pairs(pb[2], pb[3]);
 
     // ---- O^T[d][row] += sum_key V[key][d] P[row][key] ---------------------------------
     // the V^T operands of keys 32..63 stream in under the MFMAs of keys 0..31
@@ -601,11 +613,10 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
 #pragma unroll
       for (int d = 0; d < G::kDBlocks; ++d) va[h][d] = read_v_raw(vs, kb * 2 + h, d);
     if (key0 + 32 > wave_min_vis) {
+      const int lim = n_vis - key0 - hi * 4;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int key = key0 + (r >> 2) * 8 + hi * 4 + (r & 3);
-        if (key >= n_vis) sc[r] = -INFINITY;
-      }
+      for (int r = 0; r < 16; ++r)
+        if ((r >> 2) * 8 + (r & 3) >= lim) sc[r] = -INFINITY;
     }
     float tmax = max3(sc[0], sc[1], sc[2]);
 #pragma unroll
@@ -624,15 +635,10 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
       m_run = m_next;
     }
     const float m_use = (m_run == -INFINITY) ? 0.f : m_run;
-    float psum = 0.f;
     bf16x8 pb[2];
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const float e = __builtin_amdgcn_exp2f(sc[r] * p.scale_log2 - m_use);
-      psum += e;
-      pb[r >> 3][r & 7] = (__bf16)e;
-    }
-    l_run += psum;
+    for (int r = 0; r < 16; ++r) pb[r >> 3][r & 7] = (__bf16)__builtin_amdgcn_exp2f(sc[r] * p.scale_log2 - m_use);
+    l_run += sum_pairs(pb[0], pb[1]);
 #pragma unroll
     for (int h = 0; h < 2; ++h)
 #pragma unroll
