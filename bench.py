@@ -51,6 +51,9 @@ def parse_args():
     ap.add_argument("--decode-only", action="store_true",
                     help="run only the decode-step section (used to profile that kernel on its own; "
                          "--workload c2 or c3 restricts it to that batch shape)")
+    ap.add_argument("--fp8-only", action="store_true",
+                    help="run only the 8-bit KV cache section (to profile those kernels on their own; "
+                         "--workload c2 or c3 restricts it to that batch shape)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="first run a plain 1 GiB device copy (reference dispatch for the HBM byte counters)")
     return ap.parse_args()
@@ -387,6 +390,11 @@ def main():
     if args.decode_only:
         shapes = (args.workload,) if args.workload in ("c2", "c3") else ("c2", "c3")
         print(json.dumps({"decode_step": decode_steps(torch, E, W, iters=args.extra_iters, shapes=shapes)}))
+        return
+
+    if args.fp8_only:
+        shapes = (args.workload,) if args.workload in ("c2", "c3") else ("c2", "c3")
+        print(json.dumps({"fp8_kv_cache": fp8_cache(torch, E, W, iters=args.extra_iters, shapes=shapes)}))
         return
 
     name = args.workload

@@ -30,21 +30,6 @@ int num_slots() {
   return cached;
 }
 
-// Ring of pinned, device-mapped host buffers holding work lists.  The kernels read their
-// (small) work items straight from this memory, so no copy sits between planning and launch.
-// A slot is reused only after the kernels that read it have finished (event recorded behind
-// the last launch of the call).
-struct StageSlot {
-  void* host = nullptr;
-  void* dev = nullptr;  // device-side address of the same memory
-  size_t capacity = 0;
-  hipEvent_t done = nullptr;
-  bool in_flight = false;
-};
-StageSlot g_stage[kStageSlots];
-int g_stage_next = 0;
-std::mutex g_stage_mutex;
-
 #define EFIM_HIP(expr)                                  \
   do {                                                  \
     hipError_t e_ = (expr);                             \
@@ -54,22 +39,119 @@ std::mutex g_stage_mutex;
     }                                                   \
   } while (0)
 
-// Takes the next slot of the ring, waiting for the launches that last used it.
-int acquire_slot(StageSlot** slot_out) {
-  StageSlot& s = g_stage[g_stage_next];
-  g_stage_next = (g_stage_next + 1) % kStageSlots;
-  if (!s.done) EFIM_HIP(hipEventCreateWithFlags(&s.done, hipEventDisableTiming));
-  if (s.in_flight) {
-    EFIM_HIP(hipEventSynchronize(s.done));
-    s.in_flight = false;
-  }
-  *slot_out = &s;
+// --- completion tracking --------------------------------------------------------------
+// Whatever a launch borrows (a pinned work-list buffer, a block of arrival counters, a
+// device copy of a plan) may be reused once the launch has run.  Recording an event behind
+// every call costs 2-3 us of device time per call (the marker sits between two kernels that
+// would otherwise run back to back), so calls are grouped into epochs: consecutive calls on
+// one stream, at most kEpochCalls of them, share one event, recorded on their stream when
+// the epoch closes -- when it is full, when a call arrives on another stream, or when
+// somebody needs to wait for it.  Borrowed things are handed out from rings much longer than
+// an epoch, so by the time one comes round again its epoch has long been closed.
+constexpr int kEpochCalls = 8;
+constexpr int kEpochs = 16;
+struct Epoch {
+  uint64_t id = 0;  // 0: never used
+  hipEvent_t ev = nullptr;
+  hipStream_t stream = nullptr;
+  int calls = 0;
+  bool recorded = false;
+};
+Epoch g_epochs[kEpochs];
+uint64_t g_epoch_id = 0;  // id of the open epoch (0: none yet)
+std::mutex g_stage_mutex;  // guards everything from here to finish_stage
+
+Epoch& epoch_entry(uint64_t id) { return g_epochs[id % kEpochs]; }
+
+// Records the open epoch's event behind everything enqueued on its stream so far.
+int close_epoch() {
+  if (g_epoch_id == 0) return EFIM_OK;
+  Epoch& e = epoch_entry(g_epoch_id);
+  if (e.recorded || e.calls == 0) return EFIM_OK;
+  EFIM_HIP(hipEventRecord(e.ev, e.stream));
+  e.recorded = true;
   return EFIM_OK;
 }
 
-// Writes the plan header into a slot; *dev_header receives its device address.
-int fill_slot(const Plan& plan, StageSlot* slot, const char** dev_header) {
-  StageSlot& s = *slot;
+// Makes sure an epoch is open that a call on `stream` can join.
+int open_epoch(hipStream_t stream) {
+  if (g_epoch_id != 0) {
+    Epoch& cur = epoch_entry(g_epoch_id);
+    if (!cur.recorded && (cur.calls == 0 || (cur.stream == stream && cur.calls < kEpochCalls))) {
+      cur.stream = stream;
+      return EFIM_OK;
+    }
+    int rc = close_epoch();
+    if (rc != EFIM_OK) return rc;
+  }
+  Epoch& e = epoch_entry(g_epoch_id + 1);
+  if (!e.ev) EFIM_HIP(hipEventCreateWithFlags(&e.ev, hipEventDisableTiming));
+  // the entry's previous epoch: wait it out, so that "entry recycled" always means "finished"
+  if (e.id != 0 && e.recorded) EFIM_HIP(hipEventSynchronize(e.ev));
+  e.id = ++g_epoch_id;
+  e.stream = stream;
+  e.calls = 0;
+  e.recorded = false;
+  return EFIM_OK;
+}
+
+// Host waits until every call of the epoch has run.
+int sync_epoch(uint64_t id) {
+  if (id == 0) return EFIM_OK;
+  Epoch& e = epoch_entry(id);
+  if (e.id != id) return EFIM_OK;  // recycled: finished
+  if (!e.recorded) {
+    int rc = close_epoch();  // an unrecorded epoch is the open one
+    if (rc != EFIM_OK) return rc;
+  }
+  EFIM_HIP(hipEventSynchronize(e.ev));
+  return EFIM_OK;
+}
+
+// Work enqueued on `stream` from now on runs after every call of the epoch.
+int stream_wait_epoch(hipStream_t stream, uint64_t id) {
+  if (id == 0) return EFIM_OK;
+  Epoch& e = epoch_entry(id);
+  if (e.id != id) return EFIM_OK;
+  if (e.stream == stream) return EFIM_OK;  // same stream: in order anyway
+  if (!e.recorded) {
+    int rc = close_epoch();
+    if (rc != EFIM_OK) return rc;
+  }
+  EFIM_HIP(hipStreamWaitEvent(stream, e.ev, 0));
+  return EFIM_OK;
+}
+
+// --- what a launch borrows --------------------------------------------------------------
+// Launch tokens: one per call, kStageSlots of them in turn; the token's index selects the
+// launch's block of arrival counters.
+struct Token {
+  uint64_t epoch = 0;
+};
+Token g_tokens[kStageSlots];
+int g_token_next = 0;
+
+// Pinned, device-mapped host buffers holding work lists.  The kernels of a plan's first launch
+// read their (small) work items straight from this memory, so no copy sits between planning
+// and launch.
+constexpr int kPinnedBuffers = 2 * kEpochCalls;  // one comes round again only after its epoch was closed
+struct StageSlot {
+  void* host = nullptr;
+  void* dev = nullptr;  // device-side address of the same memory
+  size_t capacity = 0;
+  uint64_t epoch = 0;   // of the call that last filled it
+};
+StageSlot g_stage[kPinnedBuffers];
+int g_stage_next = 0;
+
+// Takes the next pinned buffer (waiting for the launch that last read it) and writes the plan
+// header into it; *dev_header receives its device address.
+int fill_slot(const Plan& plan, StageSlot** slot_out, const char** dev_header) {
+  StageSlot& s = g_stage[g_stage_next];
+  g_stage_next = (g_stage_next + 1) % kPinnedBuffers;
+  int rc = sync_epoch(s.epoch);
+  if (rc != EFIM_OK) return rc;
+  s.epoch = 0;
   if (s.capacity < plan.header_bytes) {
     if (s.host) (void)hipHostFree(s.host);
     s.host = s.dev = nullptr;
@@ -89,6 +171,7 @@ int fill_slot(const Plan& plan, StageSlot* slot, const char** dev_header) {
   }
   if (!plan.merges.empty())
     std::memcpy(h + plan.off_merges, plan.merges.data(), plan.merges.size() * sizeof(MergeItem));
+  *slot_out = &s;
   *dev_header = static_cast<const char*>(s.dev);
   return EFIM_OK;
 }
@@ -97,21 +180,17 @@ int fill_slot(const Plan& plan, StageSlot* slot, const char** dev_header) {
 // item; from pinned host memory that read crosses the host link and nothing else can begin
 // until it returns, so a plan that is launched again (an engine calls once per layer with the
 // same batch) is read from device memory from its second launch on.  The first launch of a plan
-// reads the pinned slot and enqueues the copy behind its kernels.  Two buffers, used in turn, so
-// that the copy of a new plan seldom has to wait for launches still reading an old one.
+// reads the pinned buffer and enqueues the copy behind its kernels.  Two buffers, used in turn,
+// so that the copy of a new plan seldom has to wait for launches still reading an old one.
 constexpr int kPlanCopies = 2;
-constexpr size_t kPlanCopyBytes = size_t(2) << 20;  // larger work lists are read from the pinned slot
+constexpr size_t kPlanCopyBytes = size_t(2) << 20;  // larger work lists are read from the pinned buffer
 __device__ __align__(256) unsigned char g_plan_copy_mem[kPlanCopies][kPlanCopyBytes];
 
 struct PlanCopy {
-  uint64_t plan_id = 0;          // 0: empty
-  hipStream_t stream = nullptr;  // stream the copy was enqueued on
-  hipEvent_t ready = nullptr;    // recorded behind the copy
-  hipEvent_t last_use = nullptr; // recorded behind the latest launch that reads the buffer
+  uint64_t plan_id = 0;     // 0: empty
+  uint64_t ready = 0;       // epoch of the call that enqueued the copy
+  uint64_t last_use = 0;    // epoch of the latest call that reads the buffer
 };
-// ready and last_use point at the 'done' events of ring slots.  Such an event is recorded again
-// only after the host has waited for its previous record, so a wait on it at any later time
-// still implies that the work it was first recorded behind has finished.
 PlanCopy g_plan_copy[kPlanCopies];
 int g_plan_copy_next = 0;
 unsigned char* g_plan_copy_base = nullptr;
@@ -134,14 +213,26 @@ unsigned char* plan_copy_buffer(int i) {
   return g_plan_copy_base + (size_t)i * kPlanCopyBytes;
 }
 
-// Chooses where the kernels of one call read the work list from.  *copy_out is the device copy
-// the call reads (to be marked used behind the launch) or, with *enqueue_copy set, the one to
-// fill from the slot behind the launch; nullptr when the call only uses the pinned slot.
-int stage_plan(const Plan& plan, hipStream_t stream, StageSlot** slot_out, const char** dev_header,
-               PlanCopy** copy_out, bool* enqueue_copy) {
-  *copy_out = nullptr;
-  *enqueue_copy = false;
-  int rc = acquire_slot(slot_out);
+// What one call holds between stage_plan and finish_stage.
+struct Staged {
+  int token = 0;               // index into g_tokens: selects the block of arrival counters
+  const char* header = nullptr;  // device address of the work list the kernels read
+  StageSlot* slot = nullptr;   // pinned buffer the header was written to, if any
+  PlanCopy* copy = nullptr;    // device copy the kernels read, or (fill_copy) the one to fill
+  bool fill_copy = false;
+};
+
+// Joins the call to an epoch, takes a launch token and chooses where the kernels read the work
+// list from.
+int stage_plan(const Plan& plan, hipStream_t stream, Staged* st) {
+  int rc = open_epoch(stream);
+  if (rc != EFIM_OK) return rc;
+  st->token = g_token_next;
+  g_token_next = (g_token_next + 1) % kStageSlots;
+  rc = sync_epoch(g_tokens[st->token].epoch);  // the launch that last had this token has run
+  if (rc != EFIM_OK) return rc;
+  // (the wait may have closed the open epoch)
+  rc = open_epoch(stream);
   if (rc != EFIM_OK) return rc;
   const bool want_copy = tuning().device_plan != 0 && plan.header_bytes <= kPlanCopyBytes;
   if (want_copy) {
@@ -150,48 +241,56 @@ int stage_plan(const Plan& plan, hipStream_t stream, StageSlot** slot_out, const
       if (c.plan_id != plan.id) continue;
       unsigned char* buf = plan_copy_buffer(i);
       if (!buf) break;
-      if (c.stream != stream) EFIM_HIP(hipStreamWaitEvent(stream, c.ready, 0));
-      *dev_header = reinterpret_cast<const char*>(buf);
-      *copy_out = &c;
+      rc = stream_wait_epoch(stream, c.ready);
+      if (rc != EFIM_OK) return rc;
+      rc = open_epoch(stream);
+      if (rc != EFIM_OK) return rc;
+      st->header = reinterpret_cast<const char*>(buf);
+      st->copy = &c;
       return EFIM_OK;
     }
   }
-  rc = fill_slot(plan, *slot_out, dev_header);
+  rc = fill_slot(plan, &st->slot, &st->header);
+  if (rc != EFIM_OK) return rc;
+  rc = open_epoch(stream);
   if (rc != EFIM_OK) return rc;
   if (want_copy && plan_copy_buffer(0)) {
-    *copy_out = &g_plan_copy[g_plan_copy_next];
+    st->copy = &g_plan_copy[g_plan_copy_next];
     g_plan_copy_next = (g_plan_copy_next + 1) % kPlanCopies;
-    *enqueue_copy = true;
+    st->fill_copy = true;
   }
   return EFIM_OK;
 }
 
-// Behind the launches of a call: fills or marks the device copy, then marks the slot busy until
-// everything enqueued so far on the stream has run.
-void finish_stage(const Plan& plan, hipStream_t stream, StageSlot* slot, PlanCopy* copy, bool enqueue_copy) {
+// Behind the launches of a call: fills the device copy if this was a plan's first launch, and
+// books everything the call borrowed on the open epoch.
+void finish_stage(const Plan& plan, hipStream_t stream, const Staged& st) {
   bool copied = false;
-  if (copy && enqueue_copy) {
-    unsigned char* buf = plan_copy_buffer((int)(copy - g_plan_copy));
-    copy->plan_id = 0;
-    bool ok = buf != nullptr;
+  if (st.copy && st.fill_copy) {
+    PlanCopy& c = *st.copy;
+    unsigned char* buf = plan_copy_buffer((int)(st.copy - g_plan_copy));
+    c.plan_id = 0;
     // launches on other streams may still read the plan this buffer held
-    if (ok && copy->last_use) ok = hipStreamWaitEvent(stream, copy->last_use, 0) == hipSuccess;
-    if (ok) ok = hipMemcpyAsync(buf, slot->host, plan.header_bytes, hipMemcpyHostToDevice, stream) == hipSuccess;
+    bool ok = buf != nullptr && stream_wait_epoch(stream, c.last_use) == EFIM_OK && open_epoch(stream) == EFIM_OK;
+    if (ok) ok = hipMemcpyAsync(buf, st.slot->host, plan.header_bytes, hipMemcpyHostToDevice, stream) == hipSuccess;
     if (!ok) (void)hipGetLastError();
     copied = ok;
   }
-  if (hipEventRecord(slot->done, stream) == hipSuccess) {
-    slot->in_flight = true;
-    if (copied) {
-      copy->plan_id = plan.id;
-      copy->stream = stream;
-      copy->ready = slot->done;
-      copy->last_use = slot->done;
-    } else if (copy && !enqueue_copy) {
-      copy->last_use = slot->done;
-    }
-  } else {
+  if (open_epoch(stream) != EFIM_OK) {
+    // no way to track the launch: wait for it here
     (void)hipStreamSynchronize(stream);
+    return;
+  }
+  Epoch& e = epoch_entry(g_epoch_id);
+  e.calls += 1;
+  g_tokens[st.token].epoch = e.id;
+  if (st.slot) st.slot->epoch = e.id;
+  if (copied) {
+    st.copy->plan_id = plan.id;
+    st.copy->ready = e.id;
+    st.copy->last_use = e.id;
+  } else if (st.copy && !st.fill_copy) {
+    st.copy->last_use = e.id;
   }
 }
 
@@ -363,15 +462,12 @@ int extend_attention_base(const efim_batch_t* batch, const void* q, const void* 
   if (sm_scale == 0.f) sm_scale = 1.0f / sqrtf((float)batch->head_dim);
   hipStream_t s = static_cast<hipStream_t>(stream);
   std::lock_guard<std::mutex> stage_lock(g_stage_mutex);
-  StageSlot* slot = nullptr;
-  const char* header = nullptr;
-  PlanCopy* copy = nullptr;
-  bool enqueue_copy = false;
-  rc = stage_plan(plan, s, &slot, &header, &copy, &enqueue_copy);
+  Staged st;
+  rc = stage_plan(plan, s, &st);
   if (rc != EFIM_OK) return rc;
-  rc = launch_extend_attention(batch, plan, header, (int)(slot - g_stage), q, k_cache, v_cache, out, sm_scale,
-                               fmt, workspace, s);
-  finish_stage(plan, s, slot, copy, enqueue_copy);
+  rc = launch_extend_attention(batch, plan, st.header, st.token, q, k_cache, v_cache, out, sm_scale, fmt,
+                               workspace, s);
+  finish_stage(plan, s, st);
   return rc;
 }
 
@@ -455,15 +551,12 @@ int decode_step_base(const efim_batch_t* batch, const void* q, const void* k_new
   if (sm_scale == 0.f) sm_scale = 1.0f / sqrtf((float)batch->head_dim);
   hipStream_t s = static_cast<hipStream_t>(stream);
   std::lock_guard<std::mutex> stage_lock(g_stage_mutex);
-  StageSlot* slot = nullptr;
-  const char* header = nullptr;
-  PlanCopy* copy = nullptr;
-  bool enqueue_copy = false;
-  rc = stage_plan(plan, s, &slot, &header, &copy, &enqueue_copy);
+  Staged st;
+  rc = stage_plan(plan, s, &st);
   if (rc != EFIM_OK) return rc;
-  rc = launch_decode_step(batch, plan, header, (int)(slot - g_stage), q, k_new, v_new, k_cache, v_cache, out,
-                          inv_freq, rotary_dim, rope_interleaved, sm_scale, fmt, workspace, s);
-  finish_stage(plan, s, slot, copy, enqueue_copy);
+  rc = launch_decode_step(batch, plan, st.header, st.token, q, k_new, v_new, k_cache, v_cache, out, inv_freq,
+                          rotary_dim, rope_interleaved, sm_scale, fmt, workspace, s);
+  finish_stage(plan, s, st);
   return rc;
 }
 

@@ -15,7 +15,7 @@ constexpr int kMaxPageSize = 256;
 constexpr int kKeyTile = 64;          // keys staged in LDS per main-loop iteration
 constexpr int kWavesPerGroup = 4;     // wavefronts per attention workgroup
 constexpr int kMaxRowsPerItem = 256;  // largest query-row tile of one workgroup
-constexpr int kStageSlots = 8;        // work lists (= launches) that can be in flight at once
+constexpr int kStageSlots = 64;       // launch tokens in turn: a token comes round again after this many calls
 constexpr int kTicketSlots = kStageSlots;
 constexpr int kTicketsPerSlot = 8192; // split query tiles one launch can combine in-kernel
 
@@ -100,8 +100,8 @@ int launch_rope_append(const efim_batch_t* b, int64_t total_new, void* q, const 
 
 // `header` is the device-visible address of the staged plan header (items, merges at
 // the plan's offsets); `workspace` holds the split-KV partial results.
-// `stage_slot` is the index of the staging slot that holds the header: it selects the launch's
-// block of arrival counters.
+// `stage_slot` is the index of the call's launch token (0 .. kStageSlots-1): it selects the
+// launch's block of arrival counters.
 int launch_extend_attention(const efim_batch_t* b, const Plan& plan, const char* header, int stage_slot,
                             const void* q, const void* k_cache, const void* v_cache, void* out,
                             float sm_scale, const CacheFormat& fmt, void* workspace, hipStream_t stream);

@@ -92,6 +92,30 @@ def test_launches_without_waiting_in_between(E, cases):
         assert np.array_equal(U.host_bits(out), want[i]), "queued launch %d (batch %d) differs" % (n, i)
 
 
+def test_many_queued_launches_on_two_streams(E, cases):
+    """160 launches queued without waiting, more than the library keeps launch tokens for: the
+    batch changes every 7 calls and the stream every 5, so completion events are shared by runs
+    of calls of different lengths and tokens, pinned buffers and device copies all come round
+    several times."""
+    want = [c.baseline(E) for c in cases]
+    main, side = torch.cuda.current_stream(), torch.cuda.Stream()
+    side.wait_stream(main)
+    outs = []
+    for n in range(160):
+        i = (n // 7) % len(cases)
+        st = side if (n // 5) % 2 else main
+        c = cases[i]
+        with torch.cuda.stream(st):
+            out = torch.full(c.q.shape, 0x7FC1, dtype=torch.int16, device="cuda")
+            nbytes = E.efim_extend_workspace_bytes(c.desc)
+            ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device="cuda")
+            E.efim_extend_attention(c.desc, c.q, c.kc, c.vc, out, 0.0, ws, nbytes, st)
+        outs.append((i, out, ws))
+    torch.cuda.synchronize()
+    for n, (i, out, _) in enumerate(outs):
+        assert np.array_equal(U.host_bits(out), want[i]), "queued launch %d (batch %d) differs" % (n, i)
+
+
 def test_a_second_stream_reads_the_copy(E, cases):
     c = cases[0]
     want = c.baseline(E)
