@@ -21,10 +21,13 @@
  *  - All device buffers are owned by the caller.  The library allocates no device
  *    memory at run time.  It keeps a small ring of pinned host staging buffers (host
  *    memory only) for the work list it sends to the device, and its code object carries
- *    256 KiB of arrival counters (static device memory, one block per staging buffer)
- *    with which the workgroups of a split key range elect the one that combines them.
- *    If a kernel is killed half-way (device fault, reset) these counters may be left
+ *    static device memory: 2 MiB of arrival counters (one block per launch in flight) with
+ *    which the workgroups of a split key range elect the one that combines them, and two
+ *    2 MiB buffers that hold the work lists of batches launched more than once.
+ *    If a kernel is killed half-way (device fault, reset) the counters may be left
  *    non-zero; after such an event the process should not keep using the library.
+ *  - Calls may not be captured into a HIP graph: every call rotates host-side state
+ *    (staging buffers, counters blocks, completion events).
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
  *    enqueue work and return; they do not wait for the device.
  *  - Host arrays named in efim_batch_t are read before the call returns and may be
