@@ -32,7 +32,7 @@ if ROOT not in sys.path:
 # on: the digest of extend_attention.hip is recorded with it and checked at run time.
 MEASURED_TRAFFIC = {
     # workload: (bytes per launch, sha256 of csrc/extend_attention.hip when measured)
-    "c5": (2560684438, "6381ab5c168769959acbd5416c73674255ef939733d78c8a25954b69211904c5"),
+    "c5": (2569417709, "6b759701a5f7e623cb9fa263c74f564c3359f71c9c34ec3fd79e67594782ae18"),
 }
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak

@@ -144,6 +144,33 @@ __device__ __forceinline__ void load_to_lds_16(const void* base, uint32_t lane_o
       : "memory");
 }
 
+// Four such loads of consecutive 1 KB pieces: the instruction's offset field moves both the
+// global address and the LDS address, so one base and one M0 serve all four.
+__device__ __forceinline__ void load_to_lds_4x16(const void* base, uint32_t off0, uint32_t off1, uint32_t off2,
+                                                 uint32_t off3, uint32_t lds_addr) {
+  asm volatile(
+      "s_mov_b32 m0, %0\n\t"
+      "s_nop 0\n\t"
+      "global_load_lds_dwordx4 %1, %5\n\t"
+      "global_load_lds_dwordx4 %2, %5 offset:1024\n\t"
+      "global_load_lds_dwordx4 %3, %5 offset:2048\n\t"
+      "global_load_lds_dwordx4 %4, %5 offset:3072"
+      :
+      : "s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(off0), "v"(off1), "v"(off2), "v"(off3), "s"(base)
+      : "memory");
+}
+
+__device__ __forceinline__ void load_to_lds_2x16(const void* base, uint32_t off0, uint32_t off1, uint32_t lds_addr) {
+  asm volatile(
+      "s_mov_b32 m0, %0\n\t"
+      "s_nop 0\n\t"
+      "global_load_lds_dwordx4 %1, %3\n\t"
+      "global_load_lds_dwordx4 %2, %3 offset:1024"
+      :
+      : "s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(off0), "v"(off1), "s"(base)
+      : "memory");
+}
+
 template <int D>
 struct Geometry {
   static constexpr int kRowBytes = D * 2;            // one key/value row
@@ -367,6 +394,8 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
   int pages_next = last_chunk > 0 ? load_pages(1) : 0;
   const int64_t page_bytes = ((int64_t)p.num_kv_heads * kGRowBytes) << ps;
   const int64_t head_bytes = ((int64_t)it.kv_head * kGRowBytes) << ps;
+  const bool offsets_fit_32 = page_bytes < ((int64_t)1 << 32);  // offsets inside a page, that is
+  const int page_loads = (1 << ps) / kGKeysPerLoad;  // 1 KB loads that one page of one head holds
   // Rows of a tile past the end of the key range are fetched from the last key of the range
   // instead: every tile then issues the same number of loads, pages that may not exist are
   // never touched, and LDS only ever holds finite data (the scores of those rows are masked).
@@ -405,6 +434,72 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
     }
     const char* kc = reinterpret_cast<const char*>(p.k_cache);
     const char* vc = reinterpret_cast<const char*>(p.v_cache);
+    // (not in the eight-wave key-parallel kernel over bf16 caches: measured 1.5-2.5 % slower there
+    // -- that kernel is bound by HBM alone, and its loads do better spaced out)
+    constexpr bool kGroupedIssue = !(KP && WAVES == 8 && !KV8);
+    if constexpr (kGroupedIssue && kGKeysPerLoad <= kMinPageSize && kGLoadsPerMatrix % kLoadsPerWave == 0) {
+      if (full_tile && offsets_fit_32) {
+        // Every row lies inside the key range and a load never spans two pages: page, head and
+        // first row make a wave-uniform base (scalar registers), the lane adds its row and
+        // (swizzled) chunk.  This wave's loads are consecutive rows of ONE matrix, so the base
+        // is looked up and multiplied out only where a load starts a new page; inside a page
+        // the next load is 1 KB further on.
+        const int load0 = issuer * kLoadsPerWave;
+        const bool is_v = load0 >= kGLoadsPerMatrix;  // wave-uniform
+        const int idx0 = is_v ? load0 - kGLoadsPerMatrix : load0;
+        const char* mat = is_v ? vc : kc;
+        const uint32_t buf = (is_v ? vbuf : kbuf) + idx0 * 1024;
+        // GS loads (GS KB of consecutive rows inside one page) at a time: one page lookup, one
+        // base, one M0
+        auto grouped = [&](auto gs_c) {
+          constexpr int GS = decltype(gs_c)::value;
+#pragma unroll
+          for (int j = 0; j < kLoadsPerWave; j += GS) {
+            const int row0 = (idx0 + j) * kGKeysPerLoad;
+            const uint32_t in_page = (uint32_t)(key0 + row0) & (uint32_t)page_mask;
+            const uint32_t page = (uint32_t)__builtin_amdgcn_readlane(pages_cur, ((first_off + t * kKeyTile + row0) >> ps) & 63);
+            const uint64_t gbase = (uint64_t)page * (uint32_t)page_bytes + (uint32_t)head_bytes + in_page * kGRowBytes;
+            uint32_t off[GS];
+#pragma unroll
+            for (int q = 0; q < GS; ++q) {
+              const int tile_row = row0 + q * kGKeysPerLoad + g_key;
+              const int swz = KV8 ? (is_v ? vswz8(tile_row) : kswz8(tile_row)) : (is_v ? G::vswz(tile_row) : G::kswz(tile_row));
+              off[q] = (uint32_t)(g_key * kGRowBytes + ((g_pc ^ swz) << 4));
+            }
+            if constexpr (GS == 4) load_to_lds_4x16(mat + gbase, off[0], off[1], off[2], off[3], buf + j * 1024);
+            else load_to_lds_2x16(mat + gbase, off[0], off[1], buf + j * 1024);
+          }
+        };
+        if constexpr (kLoadsPerWave % 4 == 0) {
+          if (page_loads >= 4) {
+            grouped(std::integral_constant<int, 4>{});
+            return;
+          }
+        }
+        if constexpr (kLoadsPerWave % 2 == 0) {
+          if (page_loads >= 2) {
+            grouped(std::integral_constant<int, 2>{});
+            return;
+          }
+        }
+        uint64_t base = 0;
+#pragma unroll
+        for (int j = 0; j < kLoadsPerWave; ++j) {
+          const int row0 = (idx0 + j) * kGKeysPerLoad;  // first tile row of this load
+          const int tile_row = row0 + g_key;
+          const int swz = KV8 ? (is_v ? vswz8(tile_row) : kswz8(tile_row)) : (is_v ? G::vswz(tile_row) : G::kswz(tile_row));
+          const uint32_t in_page = (uint32_t)(key0 + row0) & (uint32_t)page_mask;
+          if (j == 0 || in_page == 0) {
+            const uint32_t page = (uint32_t)__builtin_amdgcn_readlane(pages_cur, ((first_off + t * kKeyTile + row0) >> ps) & 63);
+            base = (uint64_t)page * (uint32_t)page_bytes + (uint32_t)head_bytes + in_page * kGRowBytes;
+          } else {
+            base += 1024;
+          }
+          load_to_lds_16(mat + base, (uint32_t)(g_key * kGRowBytes + ((g_pc ^ swz) << 4)), buf + j * 1024);
+        }
+        return;
+      }
+    }
 #pragma unroll
     for (int j = 0; j < kLoadsPerWave; ++j) {
       const int load = issuer * kLoadsPerWave + j;            // 0 .. 2*kGLoadsPerMatrix-1
@@ -415,8 +510,7 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
       const int swz = KV8 ? (is_v ? vswz8(tile_row) : kswz8(tile_row)) : (is_v ? G::vswz(tile_row) : G::kswz(tile_row));
       if constexpr (kGKeysPerLoad <= kMinPageSize) {
         if (full_tile) {
-          // all rows of the load lie in one page and inside the range: page, head and first
-          // row make a wave-uniform base, the lane adds its row and (swizzled) chunk
+          // all rows of the load lie in one page and inside the range
           const int64_t page = __builtin_amdgcn_readlane(pages_cur, ((first_off + t * kKeyTile + row0) >> ps) & 63);
           const int64_t base = page * page_bytes + head_bytes + ((key0 + row0) & page_mask) * kGRowBytes;
           load_to_lds_16((is_v ? vc : kc) + base, (uint32_t)(g_key * kGRowBytes + ((g_pc ^ swz) << 4)),
