@@ -32,7 +32,7 @@ if ROOT not in sys.path:
 # on: the digest of extend_attention.hip is recorded with it and checked at run time.
 MEASURED_TRAFFIC = {
     # workload: (bytes per launch, sha256 of csrc/extend_attention.hip when measured)
-    "c5": (2569417709, "6b759701a5f7e623cb9fa263c74f564c3359f71c9c34ec3fd79e67594782ae18"),
+    "c5": (2570978062, "17f8f13c375b3c8f8612ce67ca9e0f7a907d012a2f327d0c2b76a7d342973f89"),
 }
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak

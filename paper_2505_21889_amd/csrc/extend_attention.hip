@@ -276,8 +276,8 @@ __device__ __forceinline__ void merge_rows(const AttnParams& p, const MergeItem&
 // (global q stays raw), the workgroup whose key range ends with the new token rotates its key,
 // stores key and value into the paged cache and patches them into its LDS tile.
 //
-// KV8: the caches hold E4M3 codes.  The stages then hold code tiles (half the size, so twice
-// as many of them fit).
+// KV8: the caches hold E4M3 codes.  The stages then hold code tiles (half the size); both
+// configurations run with three of them -- more tiles in flight measured slower, not faster.
 //
 // KP ("key parallel"): every work item of the launch has at most 32 query rows (decode steps,
 // short increments).  One wave would be busy and the others idle: instead waves 0 and 1 both
@@ -380,18 +380,18 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
   const int page_mask = (1 << ps) - 1;
   const int last_page = (k_end - 1) >> ps;
 
-  // Block-table entries are fetched 64 pages (a "chunk") at a time: lane l holds the page id
-  // of page (first page of the key range + 64 * chunk + l); the wave-uniform page id of a load
-  // is then a cross-lane read instead of a dependent memory load in front of every gather.
-  // A tile never straddles two chunks: pages of up to 64 tokens tile the 64-key tiles evenly,
-  // larger pages hold whole tiles.
+  // Page ids come from the block table through SCALAR loads (constant address space, wave
+  // uniform index): they wait on their own counter.  A vector load of page ids inside the tile
+  // loop would make the compiler put an s_waitcnt vmcnt(0) in front of its use -- it cannot see
+  // how many of the hand-issued gathers are still in flight -- and that wait drains every tile
+  // the loop means to keep in flight.
   const int first_page = k_begin >> ps;
   const int first_off = k_begin & page_mask;  // nonzero only for pages larger than a tile
-  auto load_pages = [&](int chunk) { return bt[min(first_page + chunk * 64 + lane, last_page)]; };
-  const int last_chunk = (last_page - first_page) >> 6;
-  int pages_chunk = 0;
-  int pages_cur = load_pages(0);
-  int pages_next = last_chunk > 0 ? load_pages(1) : 0;
+  const auto* btc = (const __attribute__((address_space(4))) int32_t*)(uintptr_t)bt;
+  // page id of the page that holds key (k_begin - first_off + rel), rel wave-uniform
+  auto page_of = [&](int rel) -> uint32_t {
+    return (uint32_t)btc[__builtin_amdgcn_readfirstlane(min(first_page + (rel >> ps), last_page))];
+  };
   const int64_t page_bytes = ((int64_t)p.num_kv_heads * kGRowBytes) << ps;
   const int64_t head_bytes = ((int64_t)it.kv_head * kGRowBytes) << ps;
   const bool offsets_fit_32 = page_bytes < ((int64_t)1 << 32);  // offsets inside a page, that is
@@ -419,19 +419,24 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
   // LDS byte address of the tile buffers (kept as an integer: the loads take addresses, not
   // pointers)
   const uint32_t lds0 = (uint32_t)(uintptr_t)(LDS_PTR(char))lds;
-  auto issue_tile = [&](int t, int stage) {
+  // Page ids of this wave's groups of four loads of tile t, fetched ahead of the loop-top wait so
+  // that the scalar loads' latency passes behind the barrier.
+  constexpr int kGroups4 = kLoadsPerWave % 4 == 0 ? kLoadsPerWave / 4 : 1;
+  struct TilePages { uint32_t id[kGroups4]; };
+  auto fetch_pages = [&](int t) -> TilePages {
+    TilePages tp;
+    const int load0 = issuer < 0 ? 0 : issuer * kLoadsPerWave;
+    const int idx0 = load0 >= kGLoadsPerMatrix ? load0 - kGLoadsPerMatrix : load0;
+#pragma unroll
+    for (int g4 = 0; g4 < kGroups4; ++g4) tp.id[g4] = page_of(first_off + t * kKeyTile + (idx0 + 4 * g4) * kGKeysPerLoad);
+    return tp;
+  };
+  auto issue_tile = [&](int t, int stage, const TilePages& pages) {
     if (issuer < 0) return;
     const uint32_t kbuf = lds0 + stage * kStageBytes;
     const uint32_t vbuf = kbuf + kGTileBytes;
     const int key0 = k_begin + t * kKeyTile;
     const bool full_tile = key0 + kKeyTile <= k_end;  // no row of the tile lies past the key range
-    const int tile_page = (first_off + t * kKeyTile) >> ps;  // first page of the tile, relative to first_page
-    if ((tile_page >> 6) != pages_chunk) {
-      // called right after the loop-top wait, so pages_next has arrived
-      pages_cur = pages_next;
-      pages_chunk = tile_page >> 6;
-      if (pages_chunk < last_chunk) pages_next = load_pages(pages_chunk + 1);
-    }
     const char* kc = reinterpret_cast<const char*>(p.k_cache);
     const char* vc = reinterpret_cast<const char*>(p.v_cache);
     // (not in the eight-wave key-parallel kernel over bf16 caches: measured 1.5-2.5 % slower there
@@ -457,7 +462,7 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
           for (int j = 0; j < kLoadsPerWave; j += GS) {
             const int row0 = (idx0 + j) * kGKeysPerLoad;
             const uint32_t in_page = (uint32_t)(key0 + row0) & (uint32_t)page_mask;
-            const uint32_t page = (uint32_t)__builtin_amdgcn_readlane(pages_cur, ((first_off + t * kKeyTile + row0) >> ps) & 63);
+            const uint32_t page = GS == 4 ? pages.id[j / 4] : page_of(first_off + t * kKeyTile + row0);
             const uint64_t gbase = (uint64_t)page * (uint32_t)page_bytes + (uint32_t)head_bytes + in_page * kGRowBytes;
             uint32_t off[GS];
 #pragma unroll
@@ -490,7 +495,7 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
           const int swz = KV8 ? (is_v ? vswz8(tile_row) : kswz8(tile_row)) : (is_v ? G::vswz(tile_row) : G::kswz(tile_row));
           const uint32_t in_page = (uint32_t)(key0 + row0) & (uint32_t)page_mask;
           if (j == 0 || in_page == 0) {
-            const uint32_t page = (uint32_t)__builtin_amdgcn_readlane(pages_cur, ((first_off + t * kKeyTile + row0) >> ps) & 63);
+            const uint32_t page = page_of(first_off + t * kKeyTile + row0);
             base = (uint64_t)page * (uint32_t)page_bytes + (uint32_t)head_bytes + in_page * kGRowBytes;
           } else {
             base += 1024;
@@ -511,7 +516,7 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
       if constexpr (kGKeysPerLoad <= kMinPageSize) {
         if (full_tile) {
           // all rows of the load lie in one page and inside the range
-          const int64_t page = __builtin_amdgcn_readlane(pages_cur, ((first_off + t * kKeyTile + row0) >> ps) & 63);
+          const int64_t page = page_of(first_off + t * kKeyTile + row0);
           const int64_t base = page * page_bytes + head_bytes + ((key0 + row0) & page_mask) * kGRowBytes;
           load_to_lds_16((is_v ? vc : kc) + base, (uint32_t)(g_key * kGRowBytes + ((g_pc ^ swz) << 4)),
                          (is_v ? vbuf : kbuf) + idx * 1024);
@@ -522,9 +527,9 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
       // then every lane looks its own page up
       int64_t page;
       if constexpr (kGKeysPerLoad <= kMinPageSize)
-        page = __builtin_amdgcn_readlane(pages_cur, ((first_off + t * kKeyTile + row0) >> ps) & 63);
+        page = page_of(first_off + t * kKeyTile + row0);
       else
-        page = __builtin_amdgcn_ds_bpermute((((first_off + t * kKeyTile + tile_row) >> ps) & 63) << 2, pages_cur);
+        page = bt[min(first_page + ((first_off + t * kKeyTile + tile_row) >> ps), last_page)];  // per lane
       const int64_t in_off = page * page_bytes + head_bytes + ((key0 + tile_row) & page_mask) * kGRowBytes;
       const int64_t row_off = (key0 + tile_row < k_end) ? in_off : last_off;
       const char* src = (is_v ? vc : kc) + row_off + ((g_pc ^ swz) << 4);
@@ -763,7 +768,7 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
 
 #pragma unroll
   for (int s0 = 0; s0 < STAGES - 1; ++s0)
-    if (s0 < ntiles) issue_tile(s0, s0);
+    if (s0 < ntiles) issue_tile(s0, s0, fetch_pages(s0));
   if constexpr (FUSED) {
     // rotary embedding of the tile's query rows and of the new token's key at position C_r
     // (the request's only new token is packed row rq.row_start), same arithmetic as the
@@ -823,10 +828,11 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
     for (int s0 = 0; s0 < STAGES; ++s0) {
       const int t = t0 + s0;
       if (t < ntiles) {
-        wait_tile(t);
         constexpr int kAhead = STAGES - 1;
         const int sl = (s0 + kAhead) % STAGES;  // static after unrolling
-        if (t + kAhead < ntiles) issue_tile(t + kAhead, sl);
+        const TilePages pages = fetch_pages(min(t + kAhead, ntiles - 1));
+        wait_tile(t);
+        if (t + kAhead < ntiles) issue_tile(t + kAhead, sl, pages);
         if constexpr (FUSED) {
           // The key range that ends with the new token: the cache slot of that token has not
           // been written yet, so its row of the landed tile and the rows behind it (which the
@@ -1052,8 +1058,8 @@ void launch_kernel(int head_dim, bool wide, bool fp8, bool few_rows, dim3 grid, 
                    hipStream_t stream) {
 #define EFIM_ATTN_LAUNCH2(DD, F8, KP)                                                              \
   do {                                                                                             \
-    if (wide) extend_attention_kernel<DD, 8, F8 ? 5 : 3, FUSED, F8, KP><<<grid, 512, 0, stream>>>(p); \
-    else extend_attention_kernel<DD, 4, F8 ? 4 : 2, FUSED, F8, KP><<<grid, 256, 0, stream>>>(p);   \
+    if (wide) extend_attention_kernel<DD, 8, 3, FUSED, F8, KP><<<grid, 512, 0, stream>>>(p); \
+    else extend_attention_kernel<DD, 4, F8 ? 3 : 2, FUSED, F8, KP><<<grid, 256, 0, stream>>>(p);   \
   } while (0)
 #define EFIM_ATTN_LAUNCH(DD, F8)                                               \
   do {                                                                         \
