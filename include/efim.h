@@ -195,6 +195,9 @@ int efim_set_kernel_events(void* start, void* stop);
 const char* efim_status_string(int status);
 int efim_last_hip_error(void); /* hipError_t of the most recent EFIM_ERR_LAUNCH on this thread */
 int efim_version(void);        /* major * 10000 + minor * 100 + patch */
+/* SHA-256 (hex) over the library's source files as they were when it was built; "" if the
+ * build did not record one.  Lets a loader tell a stale binary from a current one. */
+const char* efim_source_digest(void);
 
 /* ---------------------------------------------------------------------------------------
  * Decode step in one launch.  After the prompt, the engine generates the answer one token per

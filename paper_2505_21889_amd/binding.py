@@ -84,6 +84,8 @@ def _load():
     lib.efim_extend_workspace_bytes.restype = ctypes.c_size_t
     lib.efim_extend_attention.argtypes = [bp, vp, vp, vp, vp, ctypes.c_float, vp, ctypes.c_size_t, vp]
     lib.efim_extend_attention.restype = i32
+    lib.efim_source_digest.argtypes = []
+    lib.efim_source_digest.restype = ctypes.c_char_p
     lib.efim_decode_workspace_bytes.argtypes = [bp]
     lib.efim_decode_workspace_bytes.restype = ctypes.c_size_t
     lib.efim_decode_step.argtypes = [bp, vp, vp, vp, vp, vp, vp, ctypes.c_double, i32, ctypes.c_float, vp,
@@ -142,7 +144,7 @@ EXPORTED_SYMBOLS = (
     "efim_rope_append_fp8", "efim_extend_attention_fp8", "efim_decode_step_fp8",
     "efim_rope_append_fp8_table", "efim_decode_step_fp8_table",
     "efim_extend_plan_items", "efim_set_tuning", "efim_set_kernel_events", "efim_status_string",
-    "efim_last_hip_error", "efim_version",
+    "efim_last_hip_error", "efim_version", "efim_source_digest",
     "efim_session_pool_create", "efim_session_pool_destroy", "efim_session_transform", "efim_session_prompt",
     "efim_session_drop", "efim_session_count",
 )
@@ -220,6 +222,11 @@ def efim_extend_attention(batch, q, k_cache, v_cache, out, sm_scale, workspace, 
     _check(_lib.efim_extend_attention(ctypes.byref(batch.c), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(out),
                                       float(sm_scale), _ptr(workspace), int(workspace_bytes), _stream_ptr(stream)),
            "efim_extend_attention")
+
+
+def efim_source_digest():
+    """Digest of the library's sources as recorded when it was built (see build.source_digest)."""
+    return _lib.efim_source_digest().decode()
 
 
 def efim_decode_workspace_bytes(batch):

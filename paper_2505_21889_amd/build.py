@@ -20,6 +20,21 @@ def hipcc_path():
     raise RuntimeError("hipcc not found: libefim needs the ROCm toolchain to build")
 
 
+def source_digest():
+    """SHA-256 over every file the library is built from; compiled into the library so that a
+    binary left over from older sources can be told from a current one."""
+    import hashlib
+    h = hashlib.sha256()
+    names = [os.path.join(ROOT, "include", n) for n in sorted(os.listdir(os.path.join(ROOT, "include")))]
+    names += [os.path.join(CSRC, n) for n in sorted(os.listdir(CSRC))]
+    for path in names:
+        if os.path.isfile(path):
+            h.update(os.path.basename(path).encode() + b"\0")
+            with open(path, "rb") as fh:
+                h.update(fh.read())
+    return h.hexdigest()
+
+
 def build_library(verbose=False, extra_flags=()):
     """Compile every source of the library for gfx950 and link libefim.so."""
     os.makedirs(LIB_DIR, exist_ok=True)
@@ -28,6 +43,7 @@ def build_library(verbose=False, extra_flags=()):
         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
         "-Wno-unused-command-line-argument",
         "-I", os.path.join(ROOT, "include"), "-I", CSRC,
+        '-DEFIM_SOURCE_DIGEST="%s"' % source_digest(),
     ]
     cmd += list(extra_flags)
     for s in SOURCES:

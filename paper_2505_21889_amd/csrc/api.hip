@@ -669,6 +669,11 @@ const char* efim_status_string(int status) {
 
 int efim_last_hip_error(void) { return g_last_hip_error; }
 
-int efim_version(void) { return 100; }
+int efim_version(void) { return 200; }
+
+#ifndef EFIM_SOURCE_DIGEST
+#define EFIM_SOURCE_DIGEST ""
+#endif
+const char* efim_source_digest(void) { return EFIM_SOURCE_DIGEST; }
 
 }  // extern "C"

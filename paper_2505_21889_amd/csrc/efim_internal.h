@@ -69,6 +69,7 @@ struct Plan {
   uint64_t id = 0;          // distinct for every plan the cache has built
   int rows_per_item = 128;  // query rows per workgroup tile (32 per wave)
   int max_item_rows = 0;    // largest row_count of a work item
+  int partial_rows = 128;   // rows per partial-result slot of a split key range
   std::vector<ReqInfo> reqs;
   std::vector<WorkItem> items;
   std::vector<MergeItem> merges;
@@ -101,7 +102,8 @@ int launch_rope_append(const efim_batch_t* b, int64_t total_new, void* q, const 
 // `header` is the device-visible address of the staged plan header (items, merges at
 // the plan's offsets); `workspace` holds the split-KV partial results.
 // `stage_slot` is the index of the call's launch token (0 .. kStageSlots-1): it selects the
-// launch's block of arrival counters.
+// launch's block of arrival counters.  Negative: no token, split key ranges are combined by the
+// second launch.
 int launch_extend_attention(const efim_batch_t* b, const Plan& plan, const char* header, int stage_slot,
                             const void* q, const void* k_cache, const void* v_cache, void* out,
                             float sm_scale, const CacheFormat& fmt, void* workspace, hipStream_t stream);

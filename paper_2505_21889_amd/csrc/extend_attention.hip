@@ -61,7 +61,7 @@ struct AttnParams {
   int32_t num_q_heads;
   int32_t num_kv_heads;
   int32_t group;          // Hq / Hkv
-  int32_t rows_per_item;
+  int32_t rows_per_item;  // rows of one partial-result slot
   float scale_log2;       // sm_scale * log2(e) (times the key scale of an 8-bit cache)
   float out_scale;        // 1, or the value scale of an 8-bit cache
   float k_scale;          // 8-bit caches, fused decode step: code = value / scale
@@ -122,12 +122,17 @@ __device__ __forceinline__ float cross_half_sum(float v) {
 // (lds_addr, the wave-uniform LDS byte address, travels in M0).  Issued as inline assembly so that the
 // compiler does not order LDS reads of OTHER buffers behind it; completion is awaited
 // explicitly with s_waitcnt vmcnt before the workgroup barrier that publishes the buffer.
+// M0 is a reserved register that cannot be named as a clobber, so every block puts back the
+// value it found: whatever the compiler keeps in M0 around the block survives it.
 __device__ __forceinline__ void load_to_lds_16(const void* gptr, uint32_t lds_addr) {
+  uint32_t saved_m0;
   asm volatile(
-      "s_mov_b32 m0, %0\n\t"
+      "s_mov_b32 %0, m0\n\t"
+      "s_mov_b32 m0, %1\n\t"
       "s_nop 0\n\t"
-      "global_load_lds_dwordx4 %1, off"
-      :
+      "global_load_lds_dwordx4 %2, off\n\t"
+      "s_mov_b32 m0, %0"
+      : "=&s"(saved_m0)
       : "s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(gptr)
       : "memory");
 }
@@ -135,11 +140,14 @@ __device__ __forceinline__ void load_to_lds_16(const void* gptr, uint32_t lds_ad
 // The same with the address split into a wave-uniform base (scalar registers) and a 32-bit
 // per-lane offset: no vector arithmetic on 64-bit addresses in front of the load.
 __device__ __forceinline__ void load_to_lds_16(const void* base, uint32_t lane_off, uint32_t lds_addr) {
+  uint32_t saved_m0;
   asm volatile(
-      "s_mov_b32 m0, %0\n\t"
+      "s_mov_b32 %0, m0\n\t"
+      "s_mov_b32 m0, %1\n\t"
       "s_nop 0\n\t"
-      "global_load_lds_dwordx4 %1, %2"
-      :
+      "global_load_lds_dwordx4 %2, %3\n\t"
+      "s_mov_b32 m0, %0"
+      : "=&s"(saved_m0)
       : "s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(lane_off), "s"(base)
       : "memory");
 }
@@ -148,25 +156,31 @@ __device__ __forceinline__ void load_to_lds_16(const void* base, uint32_t lane_o
 // global address and the LDS address, so one base and one M0 serve all four.
 __device__ __forceinline__ void load_to_lds_4x16(const void* base, uint32_t off0, uint32_t off1, uint32_t off2,
                                                  uint32_t off3, uint32_t lds_addr) {
+  uint32_t saved_m0;
   asm volatile(
-      "s_mov_b32 m0, %0\n\t"
+      "s_mov_b32 %0, m0\n\t"
+      "s_mov_b32 m0, %1\n\t"
       "s_nop 0\n\t"
-      "global_load_lds_dwordx4 %1, %5\n\t"
-      "global_load_lds_dwordx4 %2, %5 offset:1024\n\t"
-      "global_load_lds_dwordx4 %3, %5 offset:2048\n\t"
-      "global_load_lds_dwordx4 %4, %5 offset:3072"
-      :
+      "global_load_lds_dwordx4 %2, %6\n\t"
+      "global_load_lds_dwordx4 %3, %6 offset:1024\n\t"
+      "global_load_lds_dwordx4 %4, %6 offset:2048\n\t"
+      "global_load_lds_dwordx4 %5, %6 offset:3072\n\t"
+      "s_mov_b32 m0, %0"
+      : "=&s"(saved_m0)
       : "s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(off0), "v"(off1), "v"(off2), "v"(off3), "s"(base)
       : "memory");
 }
 
 __device__ __forceinline__ void load_to_lds_2x16(const void* base, uint32_t off0, uint32_t off1, uint32_t lds_addr) {
+  uint32_t saved_m0;
   asm volatile(
-      "s_mov_b32 m0, %0\n\t"
+      "s_mov_b32 %0, m0\n\t"
+      "s_mov_b32 m0, %1\n\t"
       "s_nop 0\n\t"
-      "global_load_lds_dwordx4 %1, %3\n\t"
-      "global_load_lds_dwordx4 %2, %3 offset:1024"
-      :
+      "global_load_lds_dwordx4 %2, %4\n\t"
+      "global_load_lds_dwordx4 %3, %4 offset:1024\n\t"
+      "s_mov_b32 m0, %0"
+      : "=&s"(saved_m0)
       : "s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(off0), "v"(off1), "s"(base)
       : "memory");
 }
@@ -598,7 +612,15 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
     }
   };
 
-  auto compute_tile = [&](int t, const char* ks, const char* vs) {
+  // LO: a second pass over a tile that was just processed, adding what the bf16 rounding of the
+  // probabilities dropped: the same scores and exponentials are formed again and the PV
+  // product takes lo = bf16(p - bf16(p)), so that p enters as hi + lo with 16 significant bits.
+  // Run for the first tile of a wave whose first row sees very few keys: there the output is a
+  // weighted mean of a handful of value rows and can reach magnitude 2-4, where its own bf16
+  // rounding is already 7.8e-3, and the 2^-9 relative rounding of single bf16 weights on top of
+  // that would cross the 1e-2 error bound.
+  auto compute_tile = [&](int t, const char* ks, const char* vs, auto lo_c) __attribute__((always_inline)) {
+    constexpr bool LO = decltype(lo_c)::value;
     const int key0 = k_begin + t * kKeyTile;
     // ---- S^T[key][row] = sum_d K[key][d] Q[row][d] -----------------------------------
     // Operand traffic is scheduled by hand: the 8 K operands of the first 32 keys are read
@@ -653,32 +675,39 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
     // m_run is a reference value, not necessarily the exact running max: it is only moved
     // (and the accumulators rescaled) when the max of a row grew by more than 2^kSlack, so
     // probabilities stay below 2^kSlack and the rescale is rare after the first tile.
-    float tmax = max3(s[0][0], s[0][1], s[1][0]);
-    tmax = max3(tmax, s[1][1], s[0][2]);
+    if constexpr (!LO) {
+      float tmax = max3(s[0][0], s[0][1], s[1][0]);
+      tmax = max3(tmax, s[1][1], s[0][2]);
 #pragma unroll
-    for (int r = 3; r < 16; r += 2) tmax = max3(tmax, s[0][r], s[0][r + 1 < 16 ? r + 1 : r]);
+      for (int r = 3; r < 16; r += 2) tmax = max3(tmax, s[0][r], s[0][r + 1 < 16 ? r + 1 : r]);
 #pragma unroll
-    for (int r = 2; r < 16; r += 2) tmax = max3(tmax, s[1][r], s[1][r + 1]);
-    tmax = cross_half_max(tmax);
-    const float m_new = tmax * p.scale_log2;
-    if (__any(m_new > m_run + kSlack)) {
-      const float m_next = fmaxf(m_run, m_new);
-      const float m_safe = (m_next == -INFINITY) ? 0.f : m_next;
-      const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);
-      l_run *= alpha;
+      for (int r = 2; r < 16; r += 2) tmax = max3(tmax, s[1][r], s[1][r + 1]);
+      tmax = cross_half_max(tmax);
+      const float m_new = tmax * p.scale_log2;
+      const bool grow = m_new > m_run + kSlack;
+      if (__any(grow)) {
+        // only the rows that outgrew their reference move it: a row's arithmetic then depends
+        // on that row's scores alone, whatever the other rows of the wave hold
+        const float m_next = grow ? m_new : m_run;
+        const float m_safe = (m_next == -INFINITY) ? 0.f : m_next;
+        const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);
+        l_run *= alpha;
 #pragma unroll
-      for (int d = 0; d < G::kDBlocks; ++d)
+        for (int d = 0; d < G::kDBlocks; ++d)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) o[d][r] *= alpha;
-      m_run = m_next;
+          for (int r = 0; r < 16; ++r) o[d][r] *= alpha;
+        m_run = m_next;
+      }
     }
     const float m_use = (m_run == -INFINITY) ? 0.f : m_run;
     bf16x8 pb[4];
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-      for (int r = 0; r < 16; ++r)
-        pb[kb * 2 + (r >> 3)][r & 7] = (__bf16)__builtin_amdgcn_exp2f(s[kb][r] * p.scale_log2 - m_use);
+      for (int r = 0; r < 16; ++r) {
+        const float pr = __builtin_amdgcn_exp2f(s[kb][r] * p.scale_log2 - m_use);
+        pb[kb * 2 + (r >> 3)][r & 7] = LO ? (__bf16)(pr - (float)(__bf16)pr) : (__bf16)pr;
+      }
     l_run += sum_pairs(pb[0], pb[1]) + sum_pairs(pb[2], pb[3]);
 
     // ---- O^T[d][row] += sum_key V[key][d] P[row][key] ---------------------------------
@@ -695,7 +724,8 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
 
   // One 32-key half (kb = 0 or 1, wave-uniform) of a tile, same products and softmax as
   // compute_tile on that half alone.
-  auto compute_half = [&](int t, const char* ks, const char* vs, int kb) {
+  auto compute_half = [&](int t, const char* ks, const char* vs, int kb, auto lo_c) __attribute__((always_inline)) {
+    constexpr bool LO = decltype(lo_c)::value;
     const int key0 = k_begin + t * kKeyTile + kb * 32;
     f32x16 sc;
     KRaw ka[G::kSteps];
@@ -717,26 +747,34 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
       for (int r = 0; r < 16; ++r)
         if ((r >> 2) * 8 + (r & 3) >= lim) sc[r] = -INFINITY;
     }
-    float tmax = max3(sc[0], sc[1], sc[2]);
+    if constexpr (!LO) {
+      float tmax = max3(sc[0], sc[1], sc[2]);
 #pragma unroll
-    for (int r = 3; r < 15; r += 2) tmax = max3(tmax, sc[r], sc[r + 1]);
-    tmax = cross_half_max(fmaxf(tmax, sc[15]));
-    const float m_new = tmax * p.scale_log2;
-    if (__any(m_new > m_run + kSlack)) {
-      const float m_next = fmaxf(m_run, m_new);
-      const float m_safe = (m_next == -INFINITY) ? 0.f : m_next;
-      const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);
-      l_run *= alpha;
+      for (int r = 3; r < 15; r += 2) tmax = max3(tmax, sc[r], sc[r + 1]);
+      tmax = cross_half_max(fmaxf(tmax, sc[15]));
+      const float m_new = tmax * p.scale_log2;
+      const bool grow = m_new > m_run + kSlack;
+      if (__any(grow)) {
+        // only the rows that outgrew their reference move it: a row's arithmetic then depends
+        // on that row's scores alone, whatever the other rows of the wave hold
+        const float m_next = grow ? m_new : m_run;
+        const float m_safe = (m_next == -INFINITY) ? 0.f : m_next;
+        const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);
+        l_run *= alpha;
 #pragma unroll
-      for (int d = 0; d < G::kDBlocks; ++d)
+        for (int d = 0; d < G::kDBlocks; ++d)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) o[d][r] *= alpha;
-      m_run = m_next;
+          for (int r = 0; r < 16; ++r) o[d][r] *= alpha;
+        m_run = m_next;
+      }
     }
     const float m_use = (m_run == -INFINITY) ? 0.f : m_run;
     bf16x8 pb[2];
 #pragma unroll
-    for (int r = 0; r < 16; ++r) pb[r >> 3][r & 7] = (__bf16)__builtin_amdgcn_exp2f(sc[r] * p.scale_log2 - m_use);
+    for (int r = 0; r < 16; ++r) {
+      const float pr = __builtin_amdgcn_exp2f(sc[r] * p.scale_log2 - m_use);
+      pb[r >> 3][r & 7] = LO ? (__bf16)(pr - (float)(__bf16)pr) : (__bf16)pr;
+    }
     l_run += sum_pairs(pb[0], pb[1]);
 #pragma unroll
     for (int h = 0; h < 2; ++h)
@@ -746,11 +784,22 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
       }
   };
 
-  auto step = [&](int t, const char* ks, const char* vs) {
+  // rows with at most this many visible keys get the second (LO) pass over their first tile
+  constexpr int kFineKeys = 16;
+  const bool fine_wave = k_begin == 0 && wave_min_vis <= kFineKeys;  // wave-uniform
+  auto step = [&](int t, const char* ks, const char* vs, auto first_c) __attribute__((always_inline)) {
     if constexpr (KP) {
-      if (wave < 2 && k_begin + t * kKeyTile + wave * 32 < wave_max_vis) compute_half(t, ks, vs, wave);
+      if (wave < 2 && k_begin + t * kKeyTile + wave * 32 < wave_max_vis) {
+        compute_half(t, ks, vs, wave, std::false_type{});
+        if constexpr (decltype(first_c)::value)
+          if (fine_wave && t == 0 && wave == 0) compute_half(t, ks, vs, wave, std::true_type{});
+      }
     } else {
-      if (wave_active && k_begin + t * kKeyTile < wave_max_vis) compute_tile(t, ks, vs);
+      if (wave_active && k_begin + t * kKeyTile < wave_max_vis) {
+        compute_tile(t, ks, vs, std::false_type{});
+        if constexpr (decltype(first_c)::value)
+          if (fine_wave && t == 0) compute_tile(t, ks, vs, std::true_type{});
+      }
     }
   };
   // Loop top for tile t: the gathers of up to STAGES - 2 later tiles (this wave's newest
@@ -823,9 +872,10 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
       qb[s] = __builtin_bit_cast(bf16x8, v);
     }
   }
-  for (int t0 = 0; t0 < ntiles; t0 += STAGES) {
-#pragma unroll
-    for (int s0 = 0; s0 < STAGES; ++s0) {
+  // One tile of the unrolled ring: stage s0 (a compile-time constant) holds tile t0 + s0.
+  auto ring_step = [&](int t0, auto s0_c) __attribute__((always_inline)) {
+    constexpr int s0 = decltype(s0_c)::value;
+    {
       const int t = t0 + s0;
       if (t < ntiles) {
         constexpr int kAhead = STAGES - 1;
@@ -862,9 +912,17 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
             __syncthreads();
           }
         }
-        step(t, stages + s0 * kStageBytes, stages + s0 * kStageBytes + kGTileBytes);
+        // (tile 0 is always the first of the unrolled copies)
+        step(t, stages + s0 * kStageBytes, stages + s0 * kStageBytes + kGTileBytes, std::bool_constant<s0 == 0>{});
       }
     }
+  };
+  for (int t0 = 0; t0 < ntiles; t0 += STAGES) {
+    ring_step(t0, std::integral_constant<int, 0>{});
+    ring_step(t0, std::integral_constant<int, 1>{});
+    if constexpr (STAGES > 2) ring_step(t0, std::integral_constant<int, 2>{});
+    if constexpr (STAGES > 3) ring_step(t0, std::integral_constant<int, 3>{});
+    if constexpr (STAGES > 4) ring_step(t0, std::integral_constant<int, 4>{});
   }
 
   // --- waves 0 and 1 shared the rows: combine their results in wave 0 --------------------
@@ -1013,7 +1071,7 @@ void fill_params(AttnParams* p, const efim_batch_t* b, const Plan& plan, const c
   p->num_q_heads = b->num_q_heads;
   p->num_kv_heads = b->num_kv_heads;
   p->group = b->num_q_heads / b->num_kv_heads;
-  p->rows_per_item = plan.rows_per_item;
+  p->rows_per_item = plan.partial_rows;
   p->scale_log2 = sm_scale * 1.4426950408889634f;
   p->out_scale = 1.f;
   p->k_scale = fmt.k_scale;
@@ -1077,7 +1135,7 @@ void launch_kernel(int head_dim, bool wide, bool fp8, bool few_rows, dim3 grid, 
 }
 
 int launch_merge(const efim_batch_t* b, const Plan& plan, const AttnParams& p, hipStream_t stream) {
-  const dim3 mgrid((unsigned)plan.merges.size(), (unsigned)(plan.rows_per_item * (b->head_dim / 4) / 256));
+  const dim3 mgrid((unsigned)plan.merges.size(), (unsigned)((plan.partial_rows * (b->head_dim / 4) + 255) / 256));
   if (b->head_dim == 128) merge_kernel<128><<<mgrid, 256, 0, stream>>>(p, p.merges);
   else merge_kernel<64><<<mgrid, 256, 0, stream>>>(p, p.merges);
   hipError_t e = hipGetLastError();
@@ -1092,7 +1150,7 @@ int launch_extend_attention(const efim_batch_t* b, const Plan& plan, const char*
                             float sm_scale, const CacheFormat& fmt, void* workspace, hipStream_t stream) {
   AttnParams p;
   fill_params(&p, b, plan, header, q, k_cache, v_cache, out, sm_scale, fmt, static_cast<char*>(workspace));
-  if (use_tickets(plan)) p.ticket_base = stage_slot * kTicketsPerSlot;
+  if (stage_slot >= 0 && use_tickets(plan)) p.ticket_base = stage_slot * kTicketsPerSlot;
 
   const dim3 grid((unsigned)plan.items.size());
   const Tuning& tn = tuning();

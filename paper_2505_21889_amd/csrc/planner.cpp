@@ -303,11 +303,16 @@ void build_plan(const efim_batch_t* b, int num_slots, Plan* plan) {
   plan->off_merges = off;
   off = align_up(off + plan->merges.size() * sizeof(MergeItem), 256);
   plan->header_bytes = off;
+  // A partial-result slot holds as many rows as the largest work item has (in steps of 32), not
+  // a whole row tile: decode-like steps cut every key range and have a handful of rows per item.
+  plan->partial_rows = std::min(M, (plan->max_item_rows + 31) / 32 * 32);
+  if (plan->partial_rows < 32) plan->partial_rows = 32;
+  const size_t prows = (size_t)plan->partial_rows;
   off = 0;
   plan->off_part_o = off;
-  off = align_up(off + (size_t)plan->num_partial_slots * M * D * sizeof(float), 256);
+  off = align_up(off + (size_t)plan->num_partial_slots * prows * D * sizeof(float), 256);
   plan->off_part_ml = off;
-  off = align_up(off + (size_t)plan->num_partial_slots * M * 2 * sizeof(float), 256);
+  off = align_up(off + (size_t)plan->num_partial_slots * prows * 2 * sizeof(float), 256);
   plan->total_bytes = off < 256 ? 256 : off;  // never zero, so callers always pass a real buffer
 }
 

@@ -70,15 +70,34 @@ def errors(got_bits, ref):
     return max_abs, rel_l2
 
 
-def assert_close(got_bits, ref, what="", scale_abs_with_output=False):
-    """max abs <= 1e-2 and relative L2 <= 5e-3.  The absolute bound is stated for outputs of
-    order one (N(0,1) values averaged by a softmax at the default scale).  A test that sharpens
-    the softmax on purpose gets outputs of magnitude up to ~4, whose bf16 rounding alone is up
-    to 2^-7 = 7.8e-3; such a test sets scale_abs_with_output and the bound scales with max|ref|."""
-    assert np.all(np.isfinite(O.bf16_to_f64(got_bits))), what + ": non-finite output"
+def elementwise_abs_bound(ref, value_scale=1.0):
+    """Per-element absolute bound: 1e-2 for outputs of magnitude up to 2, and 1e-2 * |ref| / 2
+    above.  An output element is a bf16 number: for 2 <= |o| < 4 its rounding alone is up to
+    2^-7 = 7.8e-3, for 4 <= |o| < 8 up to 2^-6 = 1.56e-2, so a flat 1e-2 cannot hold there for
+    any implementation; the bound grows with the element itself, never with other elements.
+    value_scale: standard deviation of the value rows when it is above one.  The output is
+    linear in V (out = sum_j p_j v_j), so are its rounding errors; the 1e-2 is stated for
+    values of unit scale and is applied in units of that scale."""
+    s = max(1.0, float(value_scale))
+    return MAX_ABS_TOL * np.maximum(s, np.abs(ref) / 2.0)
+
+
+def assert_close(got_bits, ref, what="", large_outputs=False, value_scale=1.0):
+    """max abs <= 1e-2 and relative L2 <= 5e-3 over the whole tensor.  Tests whose inputs give
+    outputs of magnitude above 2 (a sharpened softmax, rows with a handful of visible keys,
+    values of more than unit scale) pass large_outputs: the absolute bound is then taken element
+    by element (elementwise_abs_bound), which is the flat 1e-2 wherever |ref| <= 2 and the
+    values have unit scale."""
+    got = O.bf16_to_f64(got_bits)
+    assert np.all(np.isfinite(got)), what + ": non-finite output"
     max_abs, rel_l2 = errors(got_bits, ref)
-    abs_tol = MAX_ABS_TOL * (max(1.0, float(np.abs(ref).max())) if scale_abs_with_output else 1.0)
-    assert max_abs <= abs_tol and rel_l2 <= REL_L2_TOL, "%s: max_abs %.3e rel_l2 %.3e" % (what, max_abs, rel_l2)
+    if large_outputs:
+        over = np.abs(got - ref) - elementwise_abs_bound(ref, value_scale)
+        worst = float(over.max()) if over.size else -1.0
+        assert worst <= 0.0, "%s: an element exceeds its bound by %.3e (max_abs %.3e)" % (what, worst, max_abs)
+    else:
+        assert max_abs <= MAX_ABS_TOL, "%s: max_abs %.3e rel_l2 %.3e" % (what, max_abs, rel_l2)
+    assert rel_l2 <= REL_L2_TOL, "%s: max_abs %.3e rel_l2 %.3e" % (what, max_abs, rel_l2)
     return max_abs, rel_l2
 
 
@@ -88,6 +107,57 @@ def oracle_inputs(b):
     q_roped, _ = O.rope_append(b.cached_len, b.new_len, b.block_table, b.page_size, b.q_new, b.k_new,
                                b.v_new, kc, vc, b.rope_base)
     return q_roped, kc, vc
+
+
+def progress(msg):
+    """A line on the real stdout (past pytest's capture) and in gpurun_out/test_progress.log: the
+    oracle needs minutes for the largest workloads and the run must be seen to be alive."""
+    import os
+    import sys
+    import time
+    line = "[%s] %s\n" % (time.strftime("%H:%M:%S"), msg)
+    try:
+        os.write(sys.__stdout__.fileno(), line.encode())
+    except (OSError, ValueError, AttributeError):
+        pass
+    try:
+        os.makedirs("gpurun_out", exist_ok=True)
+        with open(os.path.join("gpurun_out", "test_progress.log"), "a") as fh:
+            fh.write(line)
+    except OSError:
+        pass
+
+
+def full_check(E, b, what, every_s=20.0):
+    """Library output of the whole batch against the oracle on EVERY element: the oracle goes
+    request by request and head by head (the same function extend_attention calls), so that
+    progress can be reported in between.  Returns (max_abs, rel_l2) over the whole tensor."""
+    import time
+    q_roped, kc, vc = oracle_inputs(b)
+    progress("%s: oracle inputs built, library call" % what)
+    got_bits = gpu_extend_attention(E, b, q_roped, kc, vc)
+    got = O.bf16_to_f64(got_bits)
+    assert np.all(np.isfinite(got)), what + ": a row was left unwritten or is not finite"
+    num = den = worst = 0.0
+    start = 0
+    last = time.time()
+    for r in range(b.batch):
+        n = int(b.new_len[r])
+        for a in range(b.num_q_heads if n else 0):
+            ref = O.extend_attention_rows(r, a, b.cached_len, b.new_len, b.block_table, b.page_size,
+                                          q_roped, kc, vc)
+            d = got[start:start + n, a, :] - ref
+            worst = max(worst, float(np.abs(d).max()))
+            num += float((d * d).sum())
+            den += float((ref * ref).sum())
+            if time.time() - last > every_s:
+                last = time.time()
+                progress("%s: request %d/%d head %d, max_abs so far %.3e" % (what, r, b.batch, a, worst))
+        start += n
+    rel = (num / den) ** 0.5 if den > 0 else 0.0
+    progress("%s: all %d elements compared, max_abs %.3e rel_l2 %.3e" % (what, got.size, worst, rel))
+    assert worst <= MAX_ABS_TOL and rel <= REL_L2_TOL, "%s: max_abs %.3e rel_l2 %.3e" % (what, worst, rel)
+    return worst, rel
 
 
 def sampled_check(E, b, heads_per_req, rows_per_head, seed):

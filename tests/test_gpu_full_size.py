@@ -1,7 +1,7 @@
 """GPU parity at the full sizes of the benchmark workloads, in the launch configuration the
-benchmark times (default planner settings).  Where the oracle finishes in seconds the whole
-output is compared; for the large workloads every request is checked on sampled (head, row)
-outputs that the oracle computes one by one, plus properties that hold at any size."""
+benchmark times (default planner settings).  The whole output of every benchmark workload is
+compared; only the 131072-token context is checked on sampled (head, row) outputs that the
+oracle computes one by one."""
 import numpy as np
 import pytest
 import torch
@@ -22,26 +22,14 @@ def E():
     return binding
 
 
-@pytest.mark.parametrize("name", ["c2", "c3"])
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("name", ["c2", "c3", "c4", "c5"])
 def test_full_output_matches_oracle(E, name):
+    """Every element of the output of every benchmark workload, the headline mixed step
+    included, against the oracle at the flat bar (max abs 1e-2, relative L2 5e-3)."""
     b = W.make_batch(name)
-    q_roped, kc, vc = U.oracle_inputs(b)
-    got = U.gpu_extend_attention(E, b, q_roped, kc, vc)
-    ref = O.extend_attention(b.cached_len, b.new_len, b.block_table, b.page_size, q_roped, kc, vc)
-    max_abs, rel = U.assert_close(got, ref, name)
+    max_abs, rel = U.full_check(E, b, name)
     print("%s: max_abs %.3e rel_l2 %.3e" % (name, max_abs, rel))
-
-
-def test_c4_sampled_outputs_match_oracle(E):
-    b = W.make_batch("c4")
-    worst, rel = U.sampled_check(E, b, heads_per_req=4, rows_per_head=40, seed=7)
-    print("c4 sampled: max_abs %.3e rel_l2 %.3e" % (worst, rel))
-
-
-def test_c5_sampled_outputs_match_oracle(E):
-    b = W.make_batch("c5")
-    worst, rel = U.sampled_check(E, b, heads_per_req=2, rows_per_head=24, seed=8)
-    print("c5 sampled: max_abs %.3e rel_l2 %.3e" % (worst, rel))
 
 
 def test_c5_rope_append_bit_exact_on_sampled_requests(E):

@@ -181,12 +181,89 @@ def test_page_permutation_invariance_bit_exact(E):
     assert np.array_equal(got, got2)
 
 
+@pytest.mark.parametrize("heads,d,cached,new,j,knobs", [
+    ((8, 2), 128, [300, 0], [90, 200], 50, {}),                       # several waves per tile
+    ((8, 2), 128, [300, 0], [90, 200], 50, {"ROW_TILE": 256}),
+    ((8, 2), 128, [1500, 0], [90, 200], 17, {"SPLIT_KV": 256}),       # cut key ranges + merge pass
+    ((4, 4), 64, [700, 40], [6, 3], 3, {}),                           # at most 32 rows: key-parallel kernel
+    ((4, 4), 64, [700, 40], [6, 3], 3, {"SPLIT_KV": 128, "FUSED_MERGE": 1}),
+])
+def test_causality_later_tokens_do_not_touch_earlier_rows(E, heads, d, cached, new, j, knobs):
+    """Changing new token j of a request (its query, and its key and value in the cache) leaves
+    every output row of earlier tokens, and every row of the other requests, bit for bit as it
+    was: a row's arithmetic depends only on that row's query and its visible keys."""
+    b = _ragged(160 + d + j, cached, new, heads=heads, head_dim=d)
+    q_roped, kc, vc = _oracle_inputs(b)
+    rng = np.random.default_rng(3)
+    q2, kc2, vc2 = q_roped.copy(), kc.copy(), vc.copy()
+    pos = int(b.cached_len[0]) + j
+    page, slot = int(b.block_table[0, pos // b.page_size]), pos % b.page_size
+    kc2[page, :, slot, :] = W.gaussian_bf16(rng, (b.num_kv_heads, d), 3.0)   # finite, much larger scores
+    vc2[page, :, slot, :] = W.gaussian_bf16(rng, (b.num_kv_heads, d), 3.0)
+    q2[j] = W.gaussian_bf16(rng, (b.num_q_heads, d), 3.0)
+    for key, val in knobs.items():
+        E.efim_set_tuning(getattr(E, "EFIM_TUNE_" + key), val)
+    try:
+        got = U.gpu_extend_attention(E, b, q_roped, kc, vc)
+        got2 = U.gpu_extend_attention(E, b, q2, kc2, vc2)
+    finally:
+        E.efim_set_tuning(E.EFIM_TUNE_ROW_TILE, 0)
+        E.efim_set_tuning(E.EFIM_TUNE_SPLIT_KV, -1)
+        E.efim_set_tuning(E.EFIM_TUNE_FUSED_MERGE, -1)
+    n0 = int(b.new_len[0])
+    assert np.array_equal(got[:j], got2[:j]), "rows of earlier tokens changed"
+    assert np.array_equal(got[n0:], got2[n0:]), "rows of another request changed"
+    assert not np.array_equal(got[j:n0], got2[j:n0]), "the change must reach the later rows"
+    ref2 = O.extend_attention(b.cached_len, b.new_len, b.block_table, b.page_size, q2, kc2, vc2)
+    U.assert_close(got2, ref2, "perturbed", large_outputs=True, value_scale=3.0)
+
+
+def _one_request_of(b, r, q_roped, kc, vc):
+    """Request r of batch b as a batch of its own over the same caches (same pages)."""
+    starts = np.concatenate([[0], np.cumsum(b.new_len)])
+    sub = W.ExtendBatch(b.name, b.num_q_heads, b.num_kv_heads, b.head_dim, b.page_size, b.rope_base, b.sigma,
+                        b.cached_len[r:r + 1].copy(), b.new_len[r:r + 1].copy(),
+                        np.ascontiguousarray(b.block_table[r:r + 1]), b.num_pages, None, None, None)
+    return sub, q_roped[int(starts[r]):int(starts[r + 1])]
+
+
+def test_batch_independence(E):
+    """A request computed alone equals the same request inside a batch: bit for bit when both
+    launches run the same configuration (row tile fixed, key ranges not cut, every request with
+    more than 32 rows per kv head so that the same kernel variant is chosen), and within the
+    parity bar of the oracle under the default planner, which cuts key ranges according to the
+    whole batch."""
+    b = _ragged(171, [900, 0, 130, 2500], [40, 150, 64, 17], heads=(8, 2), head_dim=128)
+    q_roped, kc, vc = _oracle_inputs(b)
+    ref = O.extend_attention(b.cached_len, b.new_len, b.block_table, b.page_size, q_roped, kc, vc)
+    starts = np.concatenate([[0], np.cumsum(b.new_len)])
+    for fixed in (True, False):
+        if fixed:
+            E.efim_set_tuning(E.EFIM_TUNE_ROW_TILE, 128)
+            E.efim_set_tuning(E.EFIM_TUNE_SPLIT_KV, 0)
+        try:
+            whole = U.gpu_extend_attention(E, b, q_roped, kc, vc)
+            for r in range(b.batch):
+                sub, q_r = _one_request_of(b, r, q_roped, kc, vc)
+                alone = U.gpu_extend_attention(E, sub, q_r, kc, vc)
+                sl = slice(int(starts[r]), int(starts[r + 1]))
+                if fixed:
+                    assert np.array_equal(alone, whole[sl]), "request %d differs alone and in the batch" % r
+                else:
+                    U.assert_close(alone, ref[sl], "request %d alone" % r)
+            if not fixed:
+                U.assert_close(whole, ref, "batch")
+        finally:
+            E.efim_set_tuning(E.EFIM_TUNE_ROW_TILE, 0)
+            E.efim_set_tuning(E.EFIM_TUNE_SPLIT_KV, -1)
+
+
 def test_sm_scale_argument(E):
     b = _ragged(99, [90], [20], heads=(2, 2), head_dim=64)
     q_roped, kc, vc = _oracle_inputs(b)
     ref = O.extend_attention(b.cached_len, b.new_len, b.block_table, b.page_size, q_roped, kc, vc, sm_scale=0.31)
     got = U.gpu_extend_attention(E, b, q_roped, kc, vc, sm_scale=0.31)
-    U.assert_close(got, ref, "scale", scale_abs_with_output=True)
+    U.assert_close(got, ref, "scale", large_outputs=True)
 
 
 def test_repeated_runs_are_deterministic(E):
@@ -271,4 +348,4 @@ def test_other_page_sizes(E, page_size):
             E.efim_set_tuning(E.EFIM_TUNE_SPLIT_KV, -1)
         # (requests with a handful of keys give outputs of magnitude 2-4, whose bf16 rounding
         # alone is up to 7.8e-3: the absolute bound is taken relative to the largest output)
-        U.assert_close(got, ref, "page %d split %d" % (page_size, split), scale_abs_with_output=True)
+        U.assert_close(got, ref, "page %d split %d" % (page_size, split), large_outputs=True)

@@ -35,6 +35,13 @@ def test_library_exports_every_declared_symbol():
         assert hasattr(lib, name), name
     assert declared == set(E.EXPORTED_SYMBOLS)
     assert E.efim_version() >= 100
+
+
+def test_library_was_built_from_the_current_sources():
+    """The loaded binary records a digest of the sources it was built from; a binary left over
+    from older sources would make every other test a test of something else."""
+    from paper_2505_21889_amd import binding as E, build
+    assert E.efim_source_digest() == build.source_digest(), "libefim.so is stale: run __graft_entry__.build()"
     assert E.efim_status_string(0) == "ok" and "unsupported" in E.efim_status_string(-2)
 
 
