@@ -148,6 +148,27 @@ int efim_extend_attention(const efim_batch_t* batch, const void* q, const void* 
                           size_t workspace_bytes, void* stream);
 
 /*
+ * efim_extend_attention_static -- efim_extend_attention for callers that cannot allocate device
+ * memory or hold a workspace: code running under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments without the workspace, same result bit for
+ * bit.  The work list and the partial results of split key ranges live in a fixed 32 MiB array
+ * inside the library's code object (held by every device the library runs on until the process
+ * ends); the call allocates nothing -- no hipMalloc, hipHostMalloc or hipFree -- after its
+ * first use on a device has looked the array's address up.
+ * Limits: the batch's work list must fit 2 MiB and its partial results
+ * efim_extend_static_limit_bytes() (30 MiB; efim_extend_workspace_bytes(batch) tells what a
+ * batch needs); otherwise EFIM_ERR_WORKSPACE and nothing is launched -- use
+ * efim_extend_attention then.
+ * All calls on one device share the array: calls that overlap on a device (different streams,
+ * no ordering between them) race; calls on one stream, or ordered by events, do not.  A change
+ * of batch waits on the host for the previous upload of a work list (a few microseconds of
+ * copy), never for a kernel.  Other errors as efim_extend_attention.
+ */
+size_t efim_extend_static_limit_bytes(void);
+int efim_extend_attention_static(const efim_batch_t* batch, const void* q, const void* k_cache,
+                                 const void* v_cache, void* out, float sm_scale, void* stream);
+
+/*
  * Work-list introspection (pure host; used by tests and tools).
  * One item = one workgroup's job: rows [row_begin, row_begin + row_count) of the
  * (request, kv head) row space -- row = token * (Hq/Hkv) + head-in-group -- against keys

@@ -84,6 +84,10 @@ def _load():
     lib.efim_extend_workspace_bytes.restype = ctypes.c_size_t
     lib.efim_extend_attention.argtypes = [bp, vp, vp, vp, vp, ctypes.c_float, vp, ctypes.c_size_t, vp]
     lib.efim_extend_attention.restype = i32
+    lib.efim_extend_static_limit_bytes.argtypes = []
+    lib.efim_extend_static_limit_bytes.restype = ctypes.c_size_t
+    lib.efim_extend_attention_static.argtypes = [bp, vp, vp, vp, vp, ctypes.c_float, vp]
+    lib.efim_extend_attention_static.restype = i32
     lib.efim_source_digest.argtypes = []
     lib.efim_source_digest.restype = ctypes.c_char_p
     lib.efim_decode_workspace_bytes.argtypes = [bp]
@@ -140,6 +144,7 @@ _lib = _load()
 LIBRARY_PATH = os.environ.get("EFIM_LIBRARY") or _build.LIB_PATH
 EXPORTED_SYMBOLS = (
     "efim_rope_append", "efim_rope_append_table", "efim_extend_workspace_bytes", "efim_extend_attention",
+    "efim_extend_static_limit_bytes", "efim_extend_attention_static",
     "efim_decode_workspace_bytes", "efim_decode_step", "efim_decode_step_table",
     "efim_rope_append_fp8", "efim_extend_attention_fp8", "efim_decode_step_fp8",
     "efim_rope_append_fp8_table", "efim_decode_step_fp8_table",
@@ -222,6 +227,16 @@ def efim_extend_attention(batch, q, k_cache, v_cache, out, sm_scale, workspace, 
     _check(_lib.efim_extend_attention(ctypes.byref(batch.c), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(out),
                                       float(sm_scale), _ptr(workspace), int(workspace_bytes), _stream_ptr(stream)),
            "efim_extend_attention")
+
+
+def efim_extend_static_limit_bytes():
+    return int(_lib.efim_extend_static_limit_bytes())
+
+
+def efim_extend_attention_static(batch, q, k_cache, v_cache, out, sm_scale, stream=None):
+    _check(_lib.efim_extend_attention_static(ctypes.byref(batch.c), _ptr(q), _ptr(k_cache), _ptr(v_cache),
+                                             _ptr(out), float(sm_scale), _stream_ptr(stream)),
+           "efim_extend_attention_static")
 
 
 def efim_source_digest():

@@ -4,6 +4,15 @@
 
 #include "efim_internal.h"
 
+// Fixed device memory of efim_extend_attention_static (below): 2 MiB for the work list, 30 MiB
+// for the partial results of split key ranges.  Every device the library runs on holds its own
+// copy until the process ends.  In host code this name is only a handle for
+// hipGetSymbolAddress, never an address.
+constexpr size_t kScratchListBytes = size_t(2) << 20;
+constexpr size_t kScratchPartialBytes = size_t(30) << 20;
+constexpr size_t kScratchBytes = kScratchListBytes + kScratchPartialBytes;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
 namespace efim {
 namespace {
 
@@ -478,6 +487,90 @@ int efim_extend_attention(const efim_batch_t* batch, const void* q, const void* 
                           size_t workspace_bytes, void* stream) {
   return extend_attention_base(batch, q, k_cache, v_cache, out, sm_scale, CacheFormat(), workspace,
                                workspace_bytes, stream);
+}
+
+// --- efim_extend_attention_static ----------------------------------------------------------
+// For callers that cannot allocate: the work list and the partial results of split key ranges
+// live in a fixed array inside the library's code object instead of a caller's workspace and the
+// pinned staging ring.
+namespace {
+
+// One per device: the array's address on that device (every device holds its own copy of the
+// array at its own address) and what the last call left in it.
+constexpr int kMaxDevices = 64;
+struct ScratchState {
+  unsigned char* ptr = nullptr;  // device address of `scratch`; the array's name is not one in host code
+  uint64_t plan_id = 0;          // plan whose work list the array holds (0: none)
+  hipEvent_t copied = nullptr;   // recorded behind the last upload of a work list
+  std::vector<unsigned char> list;  // host image of that work list, kept while the upload may read it
+};
+ScratchState g_scratch[kMaxDevices];
+std::mutex g_scratch_mutex;
+
+// Set-up, once per device, with that device current.
+int scratch_setup(int dev, ScratchState** out) {
+  if (dev < 0 || dev >= kMaxDevices) return EFIM_ERR_UNSUPPORTED;
+  ScratchState& st = g_scratch[dev];
+  if (!st.ptr) {
+    unsigned char* ptr = nullptr;
+    EFIM_HIP(hipGetSymbolAddress((void**)&ptr, HIP_SYMBOL(scratch)));
+    if (!ptr) return EFIM_ERR_LAUNCH;
+    EFIM_HIP(hipEventCreateWithFlags(&st.copied, hipEventDisableTiming));
+    st.ptr = ptr;
+  }
+  *out = &st;
+  return EFIM_OK;
+}
+
+}  // namespace
+
+size_t efim_extend_static_limit_bytes(void) { return kScratchPartialBytes; }
+
+int efim_extend_attention_static(const efim_batch_t* batch, const void* q, const void* k_cache,
+                                 const void* v_cache, void* out, float sm_scale, void* stream) {
+  int64_t total = 0;
+  int rc = validate_batch(batch, &total);
+  if (rc != EFIM_OK) return rc;
+  if (!(sm_scale >= 0.f)) return EFIM_ERR_INVALID_ARG;
+  if (total == 0) return EFIM_OK;
+  if (!q || !k_cache || !v_cache || !out || q == out || out == k_cache || out == v_cache)
+    return EFIM_ERR_INVALID_ARG;
+  if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(out) ||
+      (reinterpret_cast<uintptr_t>(batch->block_table) & 3u))
+    return EFIM_ERR_INVALID_ARG;
+  std::lock_guard<std::mutex> lock(g_plan_mutex);
+  const Plan& plan = cached_plan(batch);
+  // sizes beyond the fixed array: the caller has to use efim_extend_attention with a workspace
+  if (plan.header_bytes > kScratchListBytes || plan.total_bytes > kScratchPartialBytes) return EFIM_ERR_WORKSPACE;
+  if (sm_scale == 0.f) sm_scale = 1.0f / sqrtf((float)batch->head_dim);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  std::lock_guard<std::mutex> scratch_lock(g_scratch_mutex);
+  int dev = -1;
+  EFIM_HIP(hipGetDevice(&dev));
+  ScratchState* st = nullptr;
+  rc = scratch_setup(dev, &st);
+  if (rc != EFIM_OK) return rc;
+  if (st->plan_id != plan.id) {
+    // the previous upload may still be reading the host image
+    if (st->plan_id != 0) EFIM_HIP(hipEventSynchronize(st->copied));
+    st->plan_id = 0;
+    st->list.assign(plan.header_bytes, 0);  // host memory only
+    DevItem* items = reinterpret_cast<DevItem*>(st->list.data() + plan.off_items);
+    for (size_t i = 0; i < plan.items.size(); ++i) {
+      const WorkItem& w = plan.items[i];
+      const ReqInfo& rq = plan.reqs[w.row_count > 0 ? w.req : 0];
+      items[i] = DevItem{w, rq.cached, rq.row_start, 0, 0};
+    }
+    if (!plan.merges.empty())
+      std::memcpy(st->list.data() + plan.off_merges, plan.merges.data(), plan.merges.size() * sizeof(MergeItem));
+    EFIM_HIP(hipMemcpyAsync(st->ptr, st->list.data(), plan.header_bytes, hipMemcpyHostToDevice, s));
+    EFIM_HIP(hipEventRecord(st->copied, s));
+    st->plan_id = plan.id;
+  }
+  // (no launch token: split key ranges are combined by the second launch, which needs no
+  // arrival counters)
+  return launch_extend_attention(batch, plan, reinterpret_cast<const char*>(st->ptr), -1, q, k_cache, v_cache, out,
+                                 sm_scale, CacheFormat(), st->ptr + kScratchListBytes, s);
 }
 
 int efim_extend_attention_fp8(const efim_batch_t* batch, const void* q, const void* k_cache,

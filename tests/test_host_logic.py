@@ -262,3 +262,14 @@ def test_bench_refuses_more_than_one_gpu():
                          capture_output=True, text=True, timeout=120)
     assert res.returncode != 0
     assert "ONE GPU" in res.stderr
+
+
+def test_static_call_refuses_batches_beyond_its_fixed_array():
+    """efim_extend_attention_static checks the sizes on the host, before any device call."""
+    b = W.make_batch("c3", with_history=False, with_tensors=False)
+    desc = E.BatchDesc(b.cached_len, b.new_len, FAKE_DEV, b.num_q_heads, b.num_kv_heads, b.head_dim, b.page_size,
+                       b.num_pages, b.max_pages_per_req)
+    assert E.efim_extend_workspace_bytes(desc) > E.efim_extend_static_limit_bytes() == 30 << 20
+    with pytest.raises(E.EfimError) as err:
+        E.efim_extend_attention_static(desc, 1 << 20, 2 << 20, 3 << 20, 4 << 20, 0.0)
+    assert err.value.status == E.EFIM_ERR_WORKSPACE
