@@ -45,15 +45,21 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="c5", help="headline workload (c2..c5)")
+    ap.add_argument("--inc", type=int, default=0,
+                    help="give every request of the headline workload this many new tokens (the fixed-inc sweeps: "
+                         "1, 8, 16 on c2/c3; 256, 1024 on c4); 0 keeps the workload's own draw")
     ap.add_argument("--no-extra", action="store_true", help="skip the other workloads and sweeps")
+    ap.add_argument("--no-ceilings", action="store_true", help="skip the measured-ceiling kernels")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--extra-iters", type=int, default=30)
+    ap.add_argument("--extra-iters", type=int, default=100)
     ap.add_argument("--decode-only", action="store_true",
                     help="run only the decode-step section (used to profile that kernel on its own; "
                          "--workload c2 or c3 restricts it to that batch shape)")
     ap.add_argument("--fp8-only", action="store_true",
                     help="run only the 8-bit KV cache section (to profile those kernels on their own; "
                          "--workload c2 or c3 restricts it to that batch shape)")
+    ap.add_argument("--ceilings-only", action="store_true",
+                    help="run only the measured-ceiling kernels (dense MFMA loop, streaming read, copy)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="first run a plain 1 GiB device copy (reference dispatch for the HBM byte counters)")
     return ap.parse_args()
@@ -322,6 +328,66 @@ def fp8_cache(torch, E, W, iters, shapes=("c2", "c3")):
     return out
 
 
+def measure_ceilings(torch, E, reps=7):
+    """What kernels that do nothing but the bound operation reach on this device (the kernels
+    of libefim_ceilings.so, which is not part of the library): dense bf16 MFMA from registers on
+    N(0,1) operands with every SIMD busy, a streaming read and a streaming copy of 2 GiB.
+    Device times from HIP events around each launch; the median of `reps` launches."""
+    import ctypes
+    from paper_2505_21889_amd import build as _build
+    if not os.path.exists(_build.CEILINGS_PATH):
+        _build.build_ceilings()
+    lib = ctypes.CDLL(_build.CEILINGS_PATH)
+    vp = ctypes.c_void_p
+    lib.efim_ceiling_mfma_operand_bytes.argtypes = [ctypes.c_int]
+    lib.efim_ceiling_mfma_operand_bytes.restype = ctypes.c_size_t
+    lib.efim_ceiling_mfma_flops.argtypes = [ctypes.c_int, ctypes.c_int]
+    lib.efim_ceiling_mfma_flops.restype = ctypes.c_double
+    lib.efim_ceiling_mfma_bf16.argtypes = [vp, vp, ctypes.c_int, ctypes.c_int, vp]
+    lib.efim_ceiling_read.argtypes = [vp, ctypes.c_size_t, vp, ctypes.c_int, vp]
+    lib.efim_ceiling_copy.argtypes = [vp, vp, ctypes.c_size_t, ctypes.c_int, vp]
+    stream = torch.cuda.current_stream()
+    sp = stream.cuda_stream
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    e0, e1 = E.HipEvent(), E.HipEvent()
+
+    def timed(launch):
+        times = []
+        for _ in range(reps + 2):
+            e0.record(stream)
+            rc = launch()
+            e1.record(stream)
+            e1.synchronize()
+            assert rc == 0, "ceiling kernel failed: %d" % rc
+            times.append(e0.elapsed_ms(e1) * 1e-3)
+        return float(np.median(times[2:]))   # the first two launches warm up
+
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(77)
+    nbytes = lib.efim_ceiling_mfma_operand_bytes(cus)
+    ops = torch.empty(nbytes // 2, dtype=torch.float32, device="cuda").normal_(0.0, 1.0, generator=gen).to(torch.bfloat16)
+    sink = torch.empty(cus * 512, dtype=torch.float32, device="cuda")
+    iters = 2000
+    t_mfma = timed(lambda: lib.efim_ceiling_mfma_bf16(ops.data_ptr(), sink.data_ptr(), cus, iters, sp))
+    flops = lib.efim_ceiling_mfma_flops(cus, iters)
+    size = 2 << 30
+    src = torch.empty(size, dtype=torch.uint8, device="cuda")
+    src.random_(0, 256, generator=gen)
+    dst = torch.empty_like(src)
+    word = torch.zeros(1, dtype=torch.int32, device="cuda")
+    t_read = timed(lambda: lib.efim_ceiling_read(src.data_ptr(), size, word.data_ptr(), cus * 8, sp))
+    t_copy = timed(lambda: lib.efim_ceiling_copy(dst.data_ptr(), src.data_ptr(), size, cus * 8, sp))
+    del src, dst, ops, sink
+    torch.cuda.empty_cache()
+    return {
+        "mfma_TFLOPs": round(flops / t_mfma / 1e12, 1), "mfma_frac_of_peak": round(flops / t_mfma / 1e12 / PEAK_BF16_TFLOPS, 4),
+        "read_GBps": round(size / t_read / 1e9, 1), "read_frac_of_peak": round(size / t_read / 1e9 / PEAK_HBM_GBPS, 4),
+        "copy_GBps": round(2 * size / t_copy / 1e9, 1), "copy_frac_of_peak": round(2 * size / t_copy / 1e9 / PEAK_HBM_GBPS, 4),
+        "what": "libefim_ceilings.so: v_mfma_f32_32x32x16_bf16 from registers (2 waves per SIMD, %d workgroups, N(0,1) "
+                "operands); streaming read of 2 GiB; streaming copy of 2 GiB (read + written bytes)" % cus,
+    }
+
+
 def recorded_traffic(name):
     import hashlib
     rec = MEASURED_TRAFFIC.get(name)
@@ -344,10 +410,10 @@ def cpu_baseline(W, name):
     full = W.make_batch(name, with_history=False, with_tensors=False)
     c, n = full.cached_len, full.new_len
     if name == "c5":
-        hits = [r for r in range(len(c)) if c[r] > 0][:8]
+        hits = [r for r in range(len(c)) if c[r] > 0]
         misses = [r for r in range(len(c)) if c[r] == 0][:4]
         sel = sorted(hits + misses)
-        what = "requests %s of the mixed step (8 hits, 4 misses), all heads" % sel
+        what = "the %d cache hits and the first %d misses of the mixed step, all heads" % (len(hits), len(misses))
     else:
         sel = list(range(min(2, len(c))))
         what = "requests %s, all heads" % sel
@@ -387,6 +453,10 @@ def main():
         del src, dst
         torch.cuda.empty_cache()
 
+    if args.ceilings_only:
+        print(json.dumps({"ceilings": measure_ceilings(torch, E)}))
+        return
+
     if args.decode_only:
         shapes = (args.workload,) if args.workload in ("c2", "c3") else ("c2", "c3")
         print(json.dumps({"decode_step": decode_steps(torch, E, W, iters=args.extra_iters, shapes=shapes)}))
@@ -398,8 +468,12 @@ def main():
         return
 
     name = args.workload
-    copies = 1 if name == "c5" else 3
-    db = DeviceBatch(torch, E, W, name, copies=copies)
+    copies = 3   # independent tensor sets, rotated between steps: the last-level cache cannot hold the K/V
+    lengths = None
+    if args.inc > 0:
+        spec = W.make_batch(name, with_history=False, with_tensors=False)
+        lengths = (spec.cached_len, np.full_like(spec.new_len, args.inc))
+    db = DeviceBatch(torch, E, W, name, lengths=lengths, copies=copies)
 
     # ---- headline: K timed steps, wall clock around a synchronised region ------------
     for it in range(args.warmup):
@@ -424,9 +498,14 @@ def main():
         ach = db.attn_bytes / kernel_us / 1e3
         roofline = {"bound": "hbm", "achieved": round(ach, 1), "peak": PEAK_HBM_GBPS, "unit": "GB/s",
                     "frac": round(ach / PEAK_HBM_GBPS, 4), "traffic": None}
-    roofline["traffic"] = recorded_traffic(name)
+    roofline["traffic"] = recorded_traffic(name) if args.inc == 0 else None
     roofline["kernel"] = "extend_attention_kernel<%d>" % db.host.head_dim
     roofline["kernel_avg_us"] = round(kernel_us, 2)
+    # what this device reaches on the bound operation alone, measured in this run
+    ceilings = None if args.no_ceilings else measure_ceilings(torch, E)
+    if ceilings:
+        roofline["measured_ceiling"] = ceilings["mfma_TFLOPs"] if mfma_bound else ceilings["read_GBps"]
+        roofline["frac_of_measured_ceiling"] = round(ach / roofline["measured_ceiling"], 4)
 
     result = {
         "metric": "extend-attention TFLOP/s over one serving step (rope_append + extend_attention)",
@@ -437,13 +516,16 @@ def main():
         "us_per_step": round(ms_per_step * 1e3, 1),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "%s: %s" % (name, W.SPECS[name].describe), "batch": db.host.batch,
+        "config": {"workload": "%s: %s%s" % (name, W.SPECS[name].describe,
+                                             "; every request with %d new tokens" % args.inc if args.inc > 0 else ""),
+                   "batch": db.host.batch,
                    "total_new_tokens": db.host.total_new, "page_size": db.host.page_size,
                    "heads": "%d/%d" % (db.host.num_q_heads, db.host.num_kv_heads), "head_dim": db.host.head_dim},
         "pct_bf16_mfma_peak": round(100 * db.flops / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 2),
         "step_hbm_GBps": round((db.attn_bytes + db.rope_bytes) / (ms_per_step * 1e-3) / 1e9, 1),
         "headline_parts": head,
         "roofline": roofline,
+        "ceilings": ceilings,
     }
     del db
     torch.cuda.empty_cache()
@@ -461,7 +543,7 @@ def main():
             todo.append(("c4_inc%d" % inc, ("c4", (spec.cached_len, np.full_like(spec.new_len, inc)))))
         for label, over in todo:
             base, lengths = (label, None) if over is None else over
-            d = DeviceBatch(torch, E, W, base, lengths=lengths, copies=1 if base == "c5" else 3)
+            d = DeviceBatch(torch, E, W, base, lengths=lengths, copies=3)
             extra[label] = summarize(d, time_parts(torch, E, d, iters=args.extra_iters, warmup=10))
             del d
             torch.cuda.empty_cache()

@@ -11,6 +11,9 @@ CSRC = os.path.join(PKG, "csrc")
 LIB_DIR = os.path.join(PKG, "lib")
 LIB_PATH = os.path.join(LIB_DIR, "libefim.so")
 SOURCES = ["api.hip", "planner.cpp", "session_pool.cpp", "rope_append.hip", "extend_attention.hip"]
+# measured-ceiling kernels of the benchmark: a library of their own, never part of libefim.so
+CEILINGS_PATH = os.path.join(LIB_DIR, "libefim_ceilings.so")
+CEILINGS_SOURCES = ["ceilings.hip"]
 
 
 def hipcc_path():
@@ -26,7 +29,7 @@ def source_digest():
     import hashlib
     h = hashlib.sha256()
     names = [os.path.join(ROOT, "include", n) for n in sorted(os.listdir(os.path.join(ROOT, "include")))]
-    names += [os.path.join(CSRC, n) for n in sorted(os.listdir(CSRC))]
+    names += [os.path.join(CSRC, n) for n in sorted(os.listdir(CSRC)) if n not in CEILINGS_SOURCES]
     for path in names:
         if os.path.isfile(path):
             h.update(os.path.basename(path).encode() + b"\0")
@@ -64,5 +67,24 @@ def build_library(verbose=False, extra_flags=()):
     return LIB_PATH
 
 
+def build_ceilings(verbose=False):
+    """Compile the benchmark's measured-ceiling kernels (libefim_ceilings.so)."""
+    os.makedirs(LIB_DIR, exist_ok=True)
+    cmd = [
+        hipcc_path(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+        "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+        "-Wno-unused-command-line-argument",
+    ]
+    cmd += [os.path.join(CSRC, s) for s in CEILINGS_SOURCES] + ["-o", CEILINGS_PATH]
+    if verbose:
+        print(" ".join(cmd))
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    err = "\n".join(l for l in res.stderr.splitlines() if "packed-fp32-ops" not in l)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + err)
+    return CEILINGS_PATH
+
+
 if __name__ == "__main__":
     print(build_library(verbose=True))
+    print(build_ceilings(verbose=True))

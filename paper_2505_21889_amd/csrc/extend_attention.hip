@@ -413,12 +413,10 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
   // Rows of a tile past the end of the key range are fetched from the last key of the range
   // instead: every tile then issues the same number of loads, pages that may not exist are
   // never touched, and LDS only ever holds finite data (the scores of those rows are masked).
-  const int64_t last_off =
-      (int64_t)bt[last_page] * page_bytes + head_bytes + ((k_end - 1) & page_mask) * kGRowBytes;
-  // Everything loaded so far (Q operands, page ids) must have landed before the main loop:
-  // inside it the only outstanding vector-memory operations are the gathers, which are
-  // awaited by hand.  (vmcnt(0), expcnt/lgkmcnt untouched)
-  __builtin_amdgcn_s_waitcnt(0x0F70);
+  const int64_t last_off = (int64_t)btc[__builtin_amdgcn_readfirstlane(last_page)] * page_bytes + head_bytes +
+                           ((k_end - 1) & page_mask) * kGRowBytes;
+  // The query loads stay in flight while the first tiles are gathered (the two latencies pass
+  // together); they are awaited, with those gathers, in front of the main loop.
 
   // --- gather of one 64-key tile: the 2 * kLoadsPerMatrix 1 KB loads are dealt to the waves.
   // In the four-wave key-parallel kernel waves 0 and 1 do the products and waves 2 and 3, which
@@ -818,7 +816,13 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
 #pragma unroll
   for (int s0 = 0; s0 < STAGES - 1; ++s0)
     if (s0 < ntiles) issue_tile(s0, s0, fetch_pages(s0));
+  // Everything the compiler knows to be loading (the query operands) must have landed before
+  // the main loop: inside it the only outstanding vector-memory operations are the gathers,
+  // which are awaited by hand.  (vmcnt(0), expcnt/lgkmcnt untouched; the gathers just issued
+  // are waited for as well, which the first tiles would do anyway)
+  if constexpr (!FUSED) __builtin_amdgcn_s_waitcnt(0x0F70);
   if constexpr (FUSED) {
+    __builtin_amdgcn_s_waitcnt(0x0F70);
     // rotary embedding of the tile's query rows and of the new token's key at position C_r
     // (the request's only new token is packed row rq.row_start), same arithmetic as the
     // stand-alone append kernel
