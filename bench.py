@@ -260,10 +260,40 @@ def decode_steps(torch, E, W, iters, shapes=("c2", "c3")):
         one = queued(lambda s: E.efim_decode_step(d.desc, s["q_raw"], s["k_new"], s["v_new"], s["k_cache"],
                                                   s["v_cache"], s["out"], b.rope_base, 0, 0.0, ws, nbytes, stream))
         t2, t1 = float(np.median(two)), float(np.median(one))
+        # the same step as a plan object: work list in the caller's workspace, kernels only; eager,
+        # and captured into a HIP graph of `iters` steps (rotating over the tensor sets)
+        plan = E.Plan(d.desc, decode=True)
+        pbytes = E.efim_plan_workspace_bytes(plan)
+        pws = torch.empty(pbytes, dtype=torch.uint8, device="cuda")
+        E.efim_plan_upload(plan, pws, pbytes, stream)
+        planned_call = lambda s, st=stream: E.efim_decode_step_planned(plan, d.table, s["q_raw"], s["k_new"], s["v_new"],
+                                                                       s["k_cache"], s["v_cache"], s["out"], b.rope_base,
+                                                                       0, 0.0, pws, st)
+        tp = float(np.median(queued(planned_call)))
+        side = torch.cuda.Stream()
+        side.wait_stream(stream)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            cur = torch.cuda.current_stream()
+            for it in range(iters):
+                planned_call(d.sets[it % len(d.sets)], cur)
+        gt = []
+        for _ in range(5):
+            torch.cuda.synchronize()
+            e0.record(stream)
+            graph.replay()
+            e1.record(stream)
+            e1.synchronize()
+            gt.append(e0.elapsed_ms(e1) * 1e3 / iters)
+        tg = float(np.median(gt[1:]))
+        del graph
+        plan.close()
         nbytes_step = d.attn_bytes + d.rope_bytes
         out[base + "_decode"] = {
             "batch": b.batch, "two_call_us": round(t2, 2), "single_launch_us": round(t1, 2),
             "speedup": round(t2 / t1, 3),
+            "planned_us": round(tp, 2), "planned_graph_replay_us": round(tg, 2),
+            "planned_graph_replay_frac_hbm": round(nbytes_step / tg / 1e3 / PEAK_HBM_GBPS, 4),
             "single_launch_GBps": round(nbytes_step / t1 / 1e3, 1),
             "single_launch_frac_hbm": round(nbytes_step / t1 / 1e3 / PEAK_HBM_GBPS, 4),
             "two_call_frac_hbm": round(nbytes_step / t2 / 1e3 / PEAK_HBM_GBPS, 4),

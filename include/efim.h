@@ -26,8 +26,13 @@
  *    2 MiB buffers that hold the work lists of batches launched more than once.
  *    If a kernel is killed half-way (device fault, reset) the counters may be left
  *    non-zero; after such an event the process should not keep using the library.
- *  - Calls may not be captured into a HIP graph: every call rotates host-side state
- *    (staging buffers, counters blocks, completion events).
+ *  - The calls that take a batch description plan their work on the host and rotate
+ *    host-side state (staging buffers, blocks of counters, completion events): they may not
+ *    be captured into a HIP graph.  The plan-object calls at the end of this header launch
+ *    kernels only and may be captured.
+ *  - A stream handed to a call must stay valid until efim_stream_release(stream) has been
+ *    called or the process ends: completion of the calls on it is tracked lazily (an event is
+ *    recorded on the stream of earlier calls when a later call needs it).
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
  *    enqueue work and return; they do not wait for the device.
  *  - Host arrays named in efim_batch_t are read before the call returns and may be
@@ -168,50 +173,10 @@ size_t efim_extend_static_limit_bytes(void);
 int efim_extend_attention_static(const efim_batch_t* batch, const void* q, const void* k_cache,
                                  const void* v_cache, void* out, float sm_scale, void* stream);
 
-/*
- * Work-list introspection (pure host; used by tests and tools).
- * One item = one workgroup's job: rows [row_begin, row_begin + row_count) of the
- * (request, kv head) row space -- row = token * (Hq/Hkv) + head-in-group -- against keys
- * [key_begin, key_end) of that request.  partial_slot < 0: the item covers all visible keys
- * of its rows and writes `out` directly; otherwise it writes partial results that a merge
- * pass combines.  Items with row_count 0 are padding.
- * Returns the number of items (writing at most `capacity` of them; items may be NULL), or a
- * negative efim_status_t.
- */
-typedef struct efim_work_item {
-  int32_t req;
-  int32_t kv_head;
-  int32_t row_begin;
-  int32_t row_count;
-  int32_t key_begin;
-  int32_t key_end;
-  int32_t partial_slot;
-  int32_t merge_id;
-} efim_work_item_t;
-
-int64_t efim_extend_plan_items(const efim_batch_t* batch, efim_work_item_t* items, int64_t capacity);
-
-/*
- * Process-wide tuning knobs for tests and benchmarks (not needed in normal use).
- * Returns EFIM_OK or EFIM_ERR_INVALID_ARG for an unknown key / bad value.
- */
-typedef enum efim_tuning_key {
-  EFIM_TUNE_SPLIT_KV = 0,   /* -1 automatic (default), 0 never split, n > 0 split into chunks of n keys (multiple of 64) */
-  EFIM_TUNE_XCD_GROUPING = 1, /* 1 (default): items sharing K/V are placed on one XCD; 0: plain cost order */
-  EFIM_TUNE_NUM_SLOTS = 2,  /* concurrent workgroup slots assumed by the planner; 0 = query the device */
-  EFIM_TUNE_ROW_TILE = 3,   /* query rows per workgroup: 0 automatic (default), 128 or 256 */
-  EFIM_TUNE_FUSED_MERGE = 4, /* where split key ranges are combined: -1 (default) inside the kernel when no work item has more than 8 query rows (decode steps of the usual head groupings), by a second launch otherwise; 0 always a second launch; 1 always inside the kernel */
-  EFIM_TUNE_DEVICE_PLAN = 5 /* 1 (default): from the second launch of an unchanged batch on, the kernels read their work list from a copy in device memory (work lists up to 2 MiB); 0: always from pinned host memory */
-} efim_tuning_key_t;
-
-int efim_set_tuning(int key, int value);
-
-/*
- * Timing hook for benchmarks.  While both handles (hipEvent_t passed as void*) are non-NULL,
- * every efim_extend_attention call records `start` immediately before and `stop` immediately
- * after its main attention kernel, on the call's stream.  Pass NULLs to clear.  Process-wide.
- */
-int efim_set_kernel_events(void* start, void* stop);
+/* Records what the library still has to record on `stream` (the completion event shared by
+ * its latest calls there).  Call it before destroying a stream that was handed to the library.
+ * Returns EFIM_OK or EFIM_ERR_LAUNCH. */
+int efim_stream_release(void* stream);
 
 const char* efim_status_string(int status);
 int efim_last_hip_error(void); /* hipError_t of the most recent EFIM_ERR_LAUNCH on this thread */
@@ -350,6 +315,57 @@ int64_t efim_session_prompt(efim_session_pool_t* pool, uint64_t user, int32_t* d
 int efim_session_drop(efim_session_pool_t* pool, uint64_t user);
 int64_t efim_session_count(efim_session_pool_t* pool);
 
+
+/* ---------------------------------------------------------------------------------------
+ * Plan objects: the attention call and the decode step as pure kernel launches.
+ *
+ * The calls above plan a batch's work on the host every time the batch changes and keep the
+ * result in process-wide state.  A plan object is the same plan with an explicit owner: built
+ * once from the host fields of a batch (the per-request lengths of Sec. 1's problem statement),
+ * written once into a workspace the caller owns, and from then on every launch reads it from
+ * there.  The planned calls keep no state in the library, touch no host-side ring, record no
+ * event and never wait for the device: they may run from any thread and may be captured into a
+ * HIP graph (they enqueue kernels only, no memset or copy).  This is how an engine replays the
+ * decode step of Sec. 2.2 / Sec. 4.2 (128 output tokens per request) without a launch gap per
+ * kernel.
+ *
+ *   efim_plan_create          HOST only.  Reads batch->cached_len / new_len and the scalar fields
+ *                             (block_table is not looked at); decode != 0 plans a decode step
+ *                             (every new_len 1, at most 32 query heads per kv head, else NULL).
+ *                             Returns NULL for an invalid or unsupported batch.  The caller owns
+ *                             the plan and releases it with efim_plan_destroy (NULL is ok).
+ *   efim_plan_workspace_bytes bytes of DEVICE workspace the plan needs (work list, arrival
+ *                             counters, partial results of split key ranges), at least 256.
+ *   efim_plan_upload          enqueues on `stream` the copy of the work list into `workspace`
+ *                             (DEVICE, 256-byte aligned) and a kernel that clears the arrival
+ *                             counters.  The plan keeps the host image of the list alive, so the
+ *                             call returns at once; the workspace is usable by planned calls
+ *                             enqueued behind it on the same stream (or ordered behind it by
+ *                             events).  Not capturable (it copies).  One workspace belongs to
+ *                             one plan; launches that use the same workspace at the same time
+ *                             race, launches on one stream or in one graph do not.
+ *   efim_extend_attention_planned / efim_decode_step_planned
+ *                             efim_extend_attention / efim_decode_step for the planned batch:
+ *                             same arguments minus the batch description, plus the batch's
+ *                             DEVICE block table (same layout and row stride as when the plan
+ *                             was created).  Same result bit for bit.
+ * Errors: EFIM_ERR_INVALID_ARG (NULL or misaligned pointers, a decode call on an attention plan
+ * or the reverse), EFIM_ERR_WORKSPACE (workspace NULL, misaligned or too small at upload),
+ * EFIM_ERR_LAUNCH.
+ * ------------------------------------------------------------------------------------- */
+typedef struct efim_plan efim_plan_t;
+
+efim_plan_t* efim_plan_create(const efim_batch_t* batch, int decode);
+void efim_plan_destroy(efim_plan_t* plan);
+size_t efim_plan_workspace_bytes(const efim_plan_t* plan);
+int efim_plan_upload(efim_plan_t* plan, void* workspace, size_t workspace_bytes, void* stream);
+int efim_extend_attention_planned(const efim_plan_t* plan, const int32_t* block_table, const void* q,
+                                  const void* k_cache, const void* v_cache, void* out, float sm_scale,
+                                  void* workspace, void* stream);
+int efim_decode_step_planned(const efim_plan_t* plan, const int32_t* block_table, const void* q,
+                             const void* k_new, const void* v_new, void* k_cache, void* v_cache, void* out,
+                             double rope_base, int rope_interleaved, float sm_scale, void* workspace,
+                             void* stream);
 
 #ifdef __cplusplus
 }

@@ -88,6 +88,20 @@ def _load():
     lib.efim_extend_static_limit_bytes.restype = ctypes.c_size_t
     lib.efim_extend_attention_static.argtypes = [bp, vp, vp, vp, vp, ctypes.c_float, vp]
     lib.efim_extend_attention_static.restype = i32
+    lib.efim_plan_create.argtypes = [bp, i32]
+    lib.efim_plan_create.restype = vp
+    lib.efim_plan_destroy.argtypes = [vp]
+    lib.efim_plan_destroy.restype = None
+    lib.efim_plan_workspace_bytes.argtypes = [vp]
+    lib.efim_plan_workspace_bytes.restype = ctypes.c_size_t
+    lib.efim_plan_upload.argtypes = [vp, vp, ctypes.c_size_t, vp]
+    lib.efim_plan_upload.restype = i32
+    lib.efim_extend_attention_planned.argtypes = [vp, vp, vp, vp, vp, vp, ctypes.c_float, vp, vp]
+    lib.efim_extend_attention_planned.restype = i32
+    lib.efim_decode_step_planned.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_double, i32, ctypes.c_float, vp, vp]
+    lib.efim_decode_step_planned.restype = i32
+    lib.efim_stream_release.argtypes = [vp]
+    lib.efim_stream_release.restype = i32
     lib.efim_source_digest.argtypes = []
     lib.efim_source_digest.restype = ctypes.c_char_p
     lib.efim_decode_workspace_bytes.argtypes = [bp]
@@ -149,7 +163,9 @@ EXPORTED_SYMBOLS = (
     "efim_rope_append_fp8", "efim_extend_attention_fp8", "efim_decode_step_fp8",
     "efim_rope_append_fp8_table", "efim_decode_step_fp8_table",
     "efim_extend_plan_items", "efim_set_tuning", "efim_set_kernel_events", "efim_status_string",
-    "efim_last_hip_error", "efim_version", "efim_source_digest",
+    "efim_last_hip_error", "efim_version", "efim_source_digest", "efim_stream_release",
+    "efim_plan_create", "efim_plan_destroy", "efim_plan_workspace_bytes", "efim_plan_upload",
+    "efim_extend_attention_planned", "efim_decode_step_planned",
     "efim_session_pool_create", "efim_session_pool_destroy", "efim_session_transform", "efim_session_prompt",
     "efim_session_drop", "efim_session_count",
 )
@@ -237,6 +253,50 @@ def efim_extend_attention_static(batch, q, k_cache, v_cache, out, sm_scale, stre
     _check(_lib.efim_extend_attention_static(ctypes.byref(batch.c), _ptr(q), _ptr(k_cache), _ptr(v_cache),
                                              _ptr(out), float(sm_scale), _stream_ptr(stream)),
            "efim_extend_attention_static")
+
+
+class Plan:
+    """efim_plan_t: owns the handle; close() (or garbage collection) destroys it."""
+
+    def __init__(self, batch, decode=False):
+        self.handle = _lib.efim_plan_create(ctypes.byref(batch.c), 1 if decode else 0)
+        if not self.handle:
+            raise EfimError(EFIM_ERR_INVALID_ARG, "efim_plan_create")
+
+    def close(self):
+        if getattr(self, "handle", None):
+            _lib.efim_plan_destroy(self.handle)
+            self.handle = None
+
+    __del__ = close
+
+
+def efim_plan_workspace_bytes(plan):
+    return int(_lib.efim_plan_workspace_bytes(plan.handle))
+
+
+def efim_plan_upload(plan, workspace, workspace_bytes, stream=None):
+    _check(_lib.efim_plan_upload(plan.handle, _ptr(workspace), int(workspace_bytes), _stream_ptr(stream)),
+           "efim_plan_upload")
+
+
+def efim_extend_attention_planned(plan, block_table, q, k_cache, v_cache, out, sm_scale, workspace, stream=None):
+    _check(_lib.efim_extend_attention_planned(plan.handle, _ptr(block_table), _ptr(q), _ptr(k_cache), _ptr(v_cache),
+                                              _ptr(out), float(sm_scale), _ptr(workspace), _stream_ptr(stream)),
+           "efim_extend_attention_planned")
+
+
+def efim_decode_step_planned(plan, block_table, q, k_new, v_new, k_cache, v_cache, out, rope_base, rope_interleaved,
+                             sm_scale, workspace, stream=None):
+    _check(_lib.efim_decode_step_planned(plan.handle, _ptr(block_table), _ptr(q), _ptr(k_new), _ptr(v_new),
+                                         _ptr(k_cache), _ptr(v_cache), _ptr(out), float(rope_base),
+                                         int(rope_interleaved), float(sm_scale), _ptr(workspace),
+                                         _stream_ptr(stream)),
+           "efim_decode_step_planned")
+
+
+def efim_stream_release(stream=None):
+    _check(_lib.efim_stream_release(_stream_ptr(stream)), "efim_stream_release")
 
 
 def efim_source_digest():

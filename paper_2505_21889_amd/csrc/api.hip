@@ -1,6 +1,7 @@
 // C ABI entry points of libefim: argument checks, planning, staging of the work list.
 #include <cstring>
 #include <mutex>
+#include <new>
 
 #include "efim_internal.h"
 
@@ -251,6 +252,11 @@ int stage_plan(const Plan& plan, hipStream_t stream, Staged* st) {
       unsigned char* buf = plan_copy_buffer(i);
       if (!buf) break;
       rc = stream_wait_epoch(stream, c.ready);
+      if (rc != EFIM_OK) return rc;
+      // Readers are chained: this call also runs behind the latest reader so far (a no-op on its
+      // own stream).  `last_use` keeps one epoch only, and whoever refills the buffer waits for
+      // that one: an earlier reader on a third stream must therefore have finished by then.
+      rc = stream_wait_epoch(stream, c.last_use);
       if (rc != EFIM_OK) return rc;
       rc = open_epoch(stream);
       if (rc != EFIM_OK) return rc;
@@ -697,6 +703,140 @@ int efim_decode_step_fp8_table(const efim_batch_t* batch, const void* q, const v
   fmt.v_scale = v_scale;
   return decode_step_base(batch, q, k_new, v_new, k_cache, v_cache, out, 0.0, inv_freq, rotary_dim,
                           rope_interleaved, sm_scale, fmt, workspace, workspace_bytes, stream);
+}
+
+// --- plan objects -----------------------------------------------------------------------------
+struct efim_plan {
+  efim::Plan plan;
+  bool decode = false;
+  bool in_kernel_merge = false;
+  // scalar fields of the batch the plan was made for
+  int32_t batch = 0, num_q_heads = 0, num_kv_heads = 0, head_dim = 0, page_size = 0, max_pages = 0;
+  int64_t num_pages = 0, total_new = 0;
+  std::vector<unsigned char> image;  // host image of the work list; alive until the plan is destroyed
+  // layout of the caller's workspace
+  size_t off_tickets = 0, off_partials = 0, total_bytes = 0;
+};
+
+namespace {
+
+efim_batch_t plan_batch_view(const efim_plan* pl, const int32_t* block_table) {
+  efim_batch_t b;
+  b.batch = pl->batch;
+  b.num_q_heads = pl->num_q_heads;
+  b.num_kv_heads = pl->num_kv_heads;
+  b.head_dim = pl->head_dim;
+  b.page_size = pl->page_size;
+  b.max_pages_per_req = pl->max_pages;
+  b.num_pages = pl->num_pages;
+  b.cached_len = nullptr;  // the launch functions read the plan, not the lengths
+  b.new_len = nullptr;
+  b.block_table = block_table;
+  return b;
+}
+
+size_t align256(size_t x) { return (x + 255) / 256 * 256; }
+
+}  // namespace
+
+efim_plan_t* efim_plan_create(const efim_batch_t* batch, int decode) {
+  int64_t total = 0;
+  if ((decode ? validate_decode_batch(batch, &total) : validate_batch(batch, &total)) != EFIM_OK) return nullptr;
+  efim_plan* pl = new (std::nothrow) efim_plan;
+  if (!pl) return nullptr;
+  pl->decode = decode != 0;
+  pl->batch = batch->batch;
+  pl->num_q_heads = batch->num_q_heads;
+  pl->num_kv_heads = batch->num_kv_heads;
+  pl->head_dim = batch->head_dim;
+  pl->page_size = batch->page_size;
+  pl->max_pages = batch->max_pages_per_req;
+  pl->num_pages = batch->num_pages;
+  pl->total_new = total;
+  build_plan(batch, num_slots(), &pl->plan);
+  pl->in_kernel_merge = plan_merges_in_kernel(pl->plan);
+  const Plan& plan = pl->plan;
+  pl->image.assign(plan.header_bytes, 0);
+  DevItem* items = reinterpret_cast<DevItem*>(pl->image.data() + plan.off_items);
+  for (size_t i = 0; i < plan.items.size(); ++i) {
+    const WorkItem& w = plan.items[i];
+    const ReqInfo& rq = plan.reqs[w.row_count > 0 ? w.req : 0];
+    items[i] = DevItem{w, rq.cached, rq.row_start, 0, 0};
+  }
+  if (!plan.merges.empty())
+    std::memcpy(pl->image.data() + plan.off_merges, plan.merges.data(), plan.merges.size() * sizeof(MergeItem));
+  pl->off_tickets = align256(plan.header_bytes);
+  pl->off_partials = pl->off_tickets + align256(plan.merges.size() * sizeof(int32_t));
+  pl->total_bytes = pl->off_partials + plan.total_bytes;
+  return pl;
+}
+
+void efim_plan_destroy(efim_plan_t* plan) { delete plan; }
+
+size_t efim_plan_workspace_bytes(const efim_plan_t* plan) { return plan ? plan->total_bytes : 0; }
+
+int efim_plan_upload(efim_plan_t* plan, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!plan) return EFIM_ERR_INVALID_ARG;
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) || workspace_bytes < plan->total_bytes)
+    return EFIM_ERR_WORKSPACE;
+  if (plan->total_new == 0) return EFIM_OK;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  char* ws = static_cast<char*>(workspace);
+  EFIM_HIP(hipMemcpyAsync(ws, plan->image.data(), plan->image.size(), hipMemcpyHostToDevice, s));
+  return launch_zero_words(reinterpret_cast<int32_t*>(ws + plan->off_tickets), plan->plan.merges.size(), s);
+}
+
+int efim_extend_attention_planned(const efim_plan_t* plan, const int32_t* block_table, const void* q,
+                                  const void* k_cache, const void* v_cache, void* out, float sm_scale,
+                                  void* workspace, void* stream) {
+  if (!plan || plan->decode || !(sm_scale >= 0.f)) return EFIM_ERR_INVALID_ARG;
+  if (plan->total_new == 0) return EFIM_OK;
+  if (!block_table || !q || !k_cache || !v_cache || !out || q == out || out == k_cache || out == v_cache)
+    return EFIM_ERR_INVALID_ARG;
+  if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(out) ||
+      (reinterpret_cast<uintptr_t>(block_table) & 3u))
+    return EFIM_ERR_INVALID_ARG;
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return EFIM_ERR_WORKSPACE;
+  if (sm_scale == 0.f) sm_scale = 1.0f / sqrtf((float)plan->head_dim);
+  const efim_batch_t b = plan_batch_view(plan, block_table);
+  char* ws = static_cast<char*>(workspace);
+  int32_t* tickets = plan->in_kernel_merge ? reinterpret_cast<int32_t*>(ws + plan->off_tickets) : nullptr;
+  return launch_extend_attention(&b, plan->plan, ws, -1, q, k_cache, v_cache, out, sm_scale, CacheFormat(),
+                                 ws + plan->off_partials, static_cast<hipStream_t>(stream), tickets, true);
+}
+
+int efim_decode_step_planned(const efim_plan_t* plan, const int32_t* block_table, const void* q,
+                             const void* k_new, const void* v_new, void* k_cache, void* v_cache, void* out,
+                             double rope_base, int rope_interleaved, float sm_scale, void* workspace,
+                             void* stream) {
+  if (!plan || !plan->decode || !(sm_scale >= 0.f) || !(rope_base > 0.0) ||
+      (rope_interleaved != 0 && rope_interleaved != 1))
+    return EFIM_ERR_INVALID_ARG;
+  if (plan->total_new == 0) return EFIM_OK;
+  if (!block_table || !q || !k_new || !v_new || !k_cache || !v_cache || !out || q == out || out == k_cache ||
+      out == v_cache)
+    return EFIM_ERR_INVALID_ARG;
+  if (!aligned16(q) || !aligned16(k_new) || !aligned16(v_new) || !aligned16(k_cache) || !aligned16(v_cache) ||
+      !aligned16(out) || (reinterpret_cast<uintptr_t>(block_table) & 3u))
+    return EFIM_ERR_INVALID_ARG;
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return EFIM_ERR_WORKSPACE;
+  if (sm_scale == 0.f) sm_scale = 1.0f / sqrtf((float)plan->head_dim);
+  const int D = plan->head_dim;
+  double inv_freq[64];
+  for (int j = 0; j < D / 2; ++j) inv_freq[j] = pow(rope_base, -2.0 * j / D);
+  const efim_batch_t b = plan_batch_view(plan, block_table);
+  char* ws = static_cast<char*>(workspace);
+  int32_t* tickets = plan->in_kernel_merge ? reinterpret_cast<int32_t*>(ws + plan->off_tickets) : nullptr;
+  return launch_decode_step(&b, plan->plan, ws, -1, q, k_new, v_new, k_cache, v_cache, out, inv_freq, D,
+                            rope_interleaved, sm_scale, CacheFormat(), ws + plan->off_partials,
+                            static_cast<hipStream_t>(stream), tickets, true);
+}
+
+int efim_stream_release(void* stream) {
+  std::lock_guard<std::mutex> stage_lock(g_stage_mutex);
+  if (g_epoch_id == 0) return EFIM_OK;
+  if (epoch_entry(g_epoch_id).stream != static_cast<hipStream_t>(stream)) return EFIM_OK;
+  return close_epoch();
 }
 
 int64_t efim_extend_plan_items(const efim_batch_t* batch, efim_work_item_t* items, int64_t capacity) {

@@ -7,6 +7,7 @@
 #include <vector>
 
 #include "efim.h"
+#include "efim_debug.h"
 
 namespace efim {
 
@@ -104,9 +105,14 @@ int launch_rope_append(const efim_batch_t* b, int64_t total_new, void* q, const 
 // `stage_slot` is the index of the call's launch token (0 .. kStageSlots-1): it selects the
 // launch's block of arrival counters.  Negative: no token, split key ranges are combined by the
 // second launch.
+// `tickets` (optional): DEVICE arrival counters owned by the caller (one per split query tile, zero
+// between launches); given, the split key ranges are combined inside the main kernel with these
+// counters and no launch token is needed.  `quiet`: the timing hook is not served (a launch that
+// may be under graph capture records no events).
 int launch_extend_attention(const efim_batch_t* b, const Plan& plan, const char* header, int stage_slot,
                             const void* q, const void* k_cache, const void* v_cache, void* out,
-                            float sm_scale, const CacheFormat& fmt, void* workspace, hipStream_t stream);
+                            float sm_scale, const CacheFormat& fmt, void* workspace, hipStream_t stream,
+                            int32_t* tickets = nullptr, bool quiet = false);
 
 // Fused decode step (every request has exactly one new token): one launch does the rotary
 // embedding, the cache append, the attention and the merge of split key ranges.
@@ -115,7 +121,14 @@ constexpr int kDecodeMaxGroup = 32;  // query heads per kv head the fused kernel
 int launch_decode_step(const efim_batch_t* b, const Plan& plan, const char* header, int stage_slot,
                        const void* q, const void* k_new, const void* v_new, void* k_cache, void* v_cache,
                        void* out, const double* inv_freq, int rotary_dim, int interleaved, float sm_scale,
-                       const CacheFormat& fmt, void* workspace, hipStream_t stream);
+                       const CacheFormat& fmt, void* workspace, hipStream_t stream, int32_t* tickets = nullptr,
+                       bool quiet = false);
+
+// Clears `count` 32-bit words at `words` with a kernel (a fill that a captured graph may hold).
+int launch_zero_words(int32_t* words, size_t count, hipStream_t stream);
+
+// Whether a plan's split key ranges are combined inside the main kernel (policy and knob).
+bool plan_merges_in_kernel(const Plan& plan);
 
 void set_last_hip_error(hipError_t e);
 

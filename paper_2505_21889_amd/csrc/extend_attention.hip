@@ -72,8 +72,9 @@ struct AttnParams {
   uint16_t* k_cache_w;    // the caches again, writable: the new token's K/V are appended
   uint16_t* v_cache_w;
   const MergeItem* merges;
-  int32_t ticket_base;    // first arrival counter of this launch in g_tickets, or -1: the split
-                          // key ranges are combined by merge_kernel in a second launch
+  int32_t ticket_base;    // first arrival counter of this launch in g_tickets (or in `tickets`),
+                          // or -1: the split key ranges are combined by merge_kernel in a second launch
+  int32_t* tickets;       // the caller's arrival counters, or nullptr: the library's own
   int32_t page_shift;     // log2 of the page size (tokens per page)
   int32_t interleaved;    // rotary pairing
   int32_t rotary_dim;     // leading elements of a head row that are rotated
@@ -1033,7 +1034,7 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
   // is drawn.
   if (it.partial_slot >= 0 && p.ticket_base >= 0) {
     const MergeItem mi = p.merges[it.merge_id];
-    int32_t* ticket = g_tickets + p.ticket_base + it.merge_id;
+    int32_t* ticket = (p.tickets ? p.tickets : g_tickets) + p.ticket_base + it.merge_id;
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
     __syncthreads();
     if (tid == 0)
@@ -1089,6 +1090,7 @@ void fill_params(AttnParams* p, const efim_batch_t* b, const Plan& plan, const c
   p->k_cache_w = nullptr;
   p->v_cache_w = nullptr;
   p->ticket_base = -1;
+  p->tickets = nullptr;
   p->merges = reinterpret_cast<const MergeItem*>(header + plan.off_merges);
   p->page_shift = 0;
   while ((1 << p->page_shift) < b->page_size) ++p->page_shift;
@@ -1112,6 +1114,11 @@ bool use_tickets(const Plan& plan) {
   const int knob = tuning().fused_merge;
   const bool want = knob < 0 ? plan.max_item_rows <= kTicketMergeMaxRows : knob != 0;
   return want && !plan.merges.empty() && plan.merges.size() <= (size_t)kTicketsPerSlot;
+}
+
+__global__ void zero_words_kernel(int32_t* words, size_t count) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < count) words[i] = 0;
 }
 
 // few_rows: no work item has more than 32 query rows (always so for the decode step)
@@ -1149,15 +1156,32 @@ int launch_merge(const efim_batch_t* b, const Plan& plan, const AttnParams& p, h
 
 }  // namespace
 
+bool plan_merges_in_kernel(const Plan& plan) { return use_tickets(plan); }
+
+int launch_zero_words(int32_t* words, size_t count, hipStream_t stream) {
+  if (count == 0) return EFIM_OK;
+  zero_words_kernel<<<dim3((unsigned)((count + 255) / 256)), 256, 0, stream>>>(words, count);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) { set_last_hip_error(e); return EFIM_ERR_LAUNCH; }
+  return EFIM_OK;
+}
+
 int launch_extend_attention(const efim_batch_t* b, const Plan& plan, const char* header, int stage_slot,
                             const void* q, const void* k_cache, const void* v_cache, void* out,
-                            float sm_scale, const CacheFormat& fmt, void* workspace, hipStream_t stream) {
+                            float sm_scale, const CacheFormat& fmt, void* workspace, hipStream_t stream,
+                            int32_t* tickets, bool quiet) {
   AttnParams p;
   fill_params(&p, b, plan, header, q, k_cache, v_cache, out, sm_scale, fmt, static_cast<char*>(workspace));
-  if (stage_slot >= 0 && use_tickets(plan)) p.ticket_base = stage_slot * kTicketsPerSlot;
+  if (tickets) {
+    p.tickets = tickets;
+    p.ticket_base = 0;
+  } else if (stage_slot >= 0 && use_tickets(plan)) {
+    p.ticket_base = stage_slot * kTicketsPerSlot;
+  }
 
   const dim3 grid((unsigned)plan.items.size());
-  const Tuning& tn = tuning();
+  Tuning tn = tuning();
+  if (quiet) tn.ev_start = tn.ev_stop = nullptr;
   if (tn.ev_start) (void)hipEventRecord(tn.ev_start, stream);
   const bool wide = plan.rows_per_item == 256;
   launch_kernel<false>(b->head_dim, wide, fmt.fp8, plan.max_item_rows <= 32, grid, p, stream);
@@ -1171,10 +1195,15 @@ int launch_extend_attention(const efim_batch_t* b, const Plan& plan, const char*
 int launch_decode_step(const efim_batch_t* b, const Plan& plan, const char* header, int stage_slot,
                        const void* q, const void* k_new, const void* v_new, void* k_cache, void* v_cache,
                        void* out, const double* inv_freq, int rotary_dim, int interleaved, float sm_scale,
-                       const CacheFormat& fmt, void* workspace, hipStream_t stream) {
+                       const CacheFormat& fmt, void* workspace, hipStream_t stream, int32_t* tickets, bool quiet) {
   AttnParams p;
   fill_params(&p, b, plan, header, q, k_cache, v_cache, out, sm_scale, fmt, static_cast<char*>(workspace));
-  if (use_tickets(plan)) p.ticket_base = stage_slot * kTicketsPerSlot;
+  if (tickets) {
+    p.tickets = tickets;
+    p.ticket_base = 0;
+  } else if (stage_slot >= 0 && use_tickets(plan)) {
+    p.ticket_base = stage_slot * kTicketsPerSlot;
+  }
   p.k_new = static_cast<const uint16_t*>(k_new);
   p.v_new = static_cast<const uint16_t*>(v_new);
   p.k_cache_w = static_cast<uint16_t*>(k_cache);
@@ -1185,7 +1214,8 @@ int launch_decode_step(const efim_batch_t* b, const Plan& plan, const char* head
   for (int j = 0; j < rotary_dim / 2; ++j) p.inv_freq[j] = inv_freq[j];
 
   const dim3 grid((unsigned)plan.items.size());
-  const Tuning& tn = tuning();
+  Tuning tn = tuning();
+  if (quiet) tn.ev_start = tn.ev_stop = nullptr;
   if (tn.ev_start) (void)hipEventRecord(tn.ev_start, stream);
   const bool wide = plan.rows_per_item == 256;
   launch_kernel<true>(D, wide, fmt.fp8, true, grid, p, stream);

@@ -42,6 +42,14 @@ class Case:
         torch.cuda.synchronize()
         return U.host_bits(out)
 
+    def launch(self, E, stream):
+        """Enqueues one call on `stream` without waiting; returns the output tensor."""
+        out = torch.full(self.q.shape, 0x7FC1, dtype=torch.int16, device="cuda")
+        nbytes = E.efim_extend_workspace_bytes(self.desc)
+        ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device="cuda")
+        E.efim_extend_attention(self.desc, self.q, self.kc, self.vc, out, 0.0, ws, nbytes, stream)
+        return out, ws
+
     def baseline(self, E):
         E.efim_set_tuning(E.EFIM_TUNE_DEVICE_PLAN, 0)
         try:
@@ -133,6 +141,37 @@ def test_a_second_stream_reads_the_copy(E, cases):
         assert np.array_equal(d.run(E, side), want_d)
     assert np.array_equal(d.run(E), want_d)
     assert np.array_equal(c.run(E), want)
+
+
+def test_an_older_reader_on_a_third_stream(E, cases):
+    """Stream A reads a work list's device copy behind a long queue of other work; stream B then
+    reads the same copy and goes on to two new work lists, the second of which refills the buffer
+    A's launch is still to read.  The refill must wait for A's launch (readers are chained), so
+    every output is what it is with the copies switched off."""
+    c, d, e = cases
+    want = [x.baseline(E) for x in cases]
+    a_stream, b_stream = torch.cuda.Stream(), torch.cuda.Stream()
+    assert np.array_equal(c.run(E), want[0])            # first launch: enqueues the copy
+    torch.cuda.synchronize()
+    big = torch.empty(8192, 8192, dtype=torch.float32, device="cuda").normal_()
+    held = []
+    with torch.cuda.stream(a_stream):
+        for _ in range(6):
+            big = big @ big * 1e-4                        # keeps stream A busy for a while
+        held.append(c.launch(E, a_stream))                # reader on A, far back in A's queue
+    with torch.cuda.stream(b_stream):
+        held.append(c.launch(E, b_stream))                # reader on B
+        out_d = [d.launch(E, b_stream) for _ in range(2)] # new list: the other buffer
+        out_e = [e.launch(E, b_stream) for _ in range(2)] # new list: refills the buffer A still reads
+    torch.cuda.synchronize()
+    for out, _ in held:
+        assert np.array_equal(U.host_bits(out), want[0])
+    for out, _ in out_d:
+        assert np.array_equal(U.host_bits(out), want[1])
+    for out, _ in out_e:
+        assert np.array_equal(U.host_bits(out), want[2])
+    E.efim_stream_release(a_stream)
+    E.efim_stream_release(b_stream)
 
 
 def test_decode_steps_repeat(E):

@@ -27,8 +27,8 @@ def _desc(c, n, hq=4, hkv=2, d=128, page=16, table=FAKE_DEV, max_pages=None, num
 
 
 def test_library_exports_every_declared_symbol():
-    header = open(os.path.join(ROOT, "include", "efim.h")).read()
-    declared = set(re.findall(r"\b(efim_[a-z0-9_]+)\s*\(", header))
+    header = open(os.path.join(ROOT, "include", "efim.h")).read() + open(os.path.join(ROOT, "include", "efim_debug.h")).read()
+    declared = set(re.findall(r"^[a-z][a-z0-9_ *]*\b(efim_[a-z0-9_]+)\s*\(", header, flags=re.M))
     assert declared, "no declarations found"
     lib = ctypes.CDLL(E.LIBRARY_PATH)
     for name in declared:
@@ -273,3 +273,31 @@ def test_static_call_refuses_batches_beyond_its_fixed_array():
     with pytest.raises(E.EfimError) as err:
         E.efim_extend_attention_static(desc, 1 << 20, 2 << 20, 3 << 20, 4 << 20, 0.0)
     assert err.value.status == E.EFIM_ERR_WORKSPACE
+
+
+def test_plan_objects_on_the_host():
+    """efim_plan_create / efim_plan_workspace_bytes are pure host functions: a plan is made from the
+    lengths alone; a decode plan wants one new token per request."""
+    d = _desc([700, 0, 5000], [40, 300, 3])
+    plan = E.Plan(d)
+    items = E.efim_extend_plan_items(d)
+    split = int((items["partial_slot"] >= 0).sum())
+    need = E.efim_plan_workspace_bytes(plan)
+    # work list (48 bytes per item) + partial results; the batch call's workspace holds the latter only
+    assert need >= 48 * len(items) + (E.efim_extend_workspace_bytes(d) if split else 0)
+    assert need % 256 == 0
+    plan.close()
+    plan.close()   # idempotent
+    with pytest.raises(E.EfimError):
+        E.Plan(d, decode=True)
+    dec = E.Plan(_desc([700, 0, 5000], [1, 1, 1]), decode=True)
+    assert E.efim_plan_workspace_bytes(dec) >= 256
+    with pytest.raises(E.EfimError):   # invalid batch: head_dim
+        E.Plan(_desc([4], [1], d=96))
+    # an upload into a workspace that is too small is refused before any device call
+    with pytest.raises(E.EfimError) as err:
+        E.efim_plan_upload(dec, FAKE_DEV, 64)
+    assert err.value.status == E.EFIM_ERR_WORKSPACE
+    # an empty batch plans to nothing and uploads nothing
+    empty = E.Plan(_desc([5, 6], [0, 0]))
+    E.efim_plan_upload(empty, FAKE_DEV + 0 if FAKE_DEV % 256 == 0 else (FAKE_DEV // 256 + 1) * 256, E.efim_plan_workspace_bytes(empty))
