@@ -12,8 +12,10 @@ Readings (the paper is silent on all of them; each is listed in the design notes
   * quantisation: code = nearest E4M3 value to x / scale, ties to the even code, magnitudes
     beyond 448 saturate to +-448; x is the bf16 value that the bf16 cache would hold (the key
     after its rotary embedding was rounded to bf16, the value as given);
-  * the quotient x / scale is formed in IEEE binary32 (x and scale are binary32 values): this
-    is the precision the device kernel divides in, and the code is decided on that quotient;
+  * the quotient x / scale is formed in IEEE binary32, correctly rounded: the interface gives the
+    scales as binary32 numbers and x (a bf16 value) is one too, and engines that keep an FP8
+    cache for the models the paper serves (Sec. 4) quantise in the activations' working
+    precision, not in a wider one; the code is decided on that binary32 quotient;
   * attention uses the exact products code_value * scale in place of the bf16 cache values;
     queries stay bf16.
 

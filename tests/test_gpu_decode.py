@@ -148,6 +148,49 @@ def test_decode_merge_across_compute_dies(E):
         E.efim_set_tuning(E.EFIM_TUNE_SPLIT_KV, -1)
 
 
+def test_in_kernel_merge_soak_on_three_streams(E):
+    """A bounded soak of the hand-over between the workgroups of a split key range: 360 decode
+    steps queued on three streams, XCD grouping off (the parts of a range land on different dies),
+    every key range cut into 64-key parts, merge inside the kernel; every output compared bit for
+    bit with what the separate merge kernel gives.  Stops at the first mismatch."""
+    c = np.array([3000, 4500, 900, 2222, 5000, 64, 1777, 333], dtype=np.int32)
+    b = W.make_batch("c1", seed=78, lengths=(c, np.ones_like(c)), heads=(16, 4), head_dim=128)
+    kc, vc = U.oracle_cache(b)
+    _, kc_ref, vc_ref, ref = oracle_step(b, kc, vc)
+    E.efim_set_tuning(E.EFIM_TUNE_XCD_GROUPING, 0)
+    E.efim_set_tuning(E.EFIM_TUNE_SPLIT_KV, 64)
+    try:
+        E.efim_set_tuning(E.EFIM_TUNE_FUSED_MERGE, 0)
+        want, _, _, _ = run_decode(E, b, kc, vc)
+        U.assert_close(want, ref, "second-launch merge")
+        E.efim_set_tuning(E.EFIM_TUNE_FUSED_MERGE, 1)
+        table = torch.from_numpy(b.block_table).cuda()
+        desc = U.make_desc(E, b, table)
+        q, k_new, v_new = U.dev_bits(b.q_new), U.dev_bits(b.k_new), U.dev_bits(b.v_new)
+        nbytes = E.efim_decode_workspace_bytes(desc)
+        streams = [torch.cuda.Stream() for _ in range(3)]
+        lanes = []
+        for s_ in streams:   # every stream has its own caches, output and workspace
+            lanes.append((s_, U.dev_bits(kc), U.dev_bits(vc), [torch.empty_like(q) for _ in range(8)],
+                          torch.empty(nbytes, dtype=torch.uint8, device="cuda")))
+        torch.cuda.synchronize()
+        for rnd in range(15):
+            for s_, kcd, vcd, outs, ws in lanes:
+                for o in outs:
+                    E.efim_decode_step(desc, q, k_new, v_new, kcd, vcd, o, b.rope_base, 0, 0.0, ws, nbytes, s_)
+            torch.cuda.synchronize()
+            for li, (s_, kcd, vcd, outs, ws) in enumerate(lanes):
+                for oi, o in enumerate(outs):
+                    assert np.array_equal(U.host_bits(o), want), "round %d stream %d step %d" % (rnd, li, oi)
+        for s_, kcd, vcd, outs, ws in lanes:
+            assert np.array_equal(U.host_bits(kcd), kc_ref) and np.array_equal(U.host_bits(vcd), vc_ref)
+            E.efim_stream_release(s_)
+    finally:
+        E.efim_set_tuning(E.EFIM_TUNE_XCD_GROUPING, 1)
+        E.efim_set_tuning(E.EFIM_TUNE_SPLIT_KV, -1)
+        E.efim_set_tuning(E.EFIM_TUNE_FUSED_MERGE, -1)
+
+
 def test_decode_step_with_the_merge_in_a_second_launch(E):
     """The decode step also works when the parts of a split key range are combined by the
     separate merge kernel (the path taken when a launch has more split tiles than arrival
