@@ -374,6 +374,11 @@ def measure_ceilings(torch, E, reps=7):
     lib.efim_ceiling_mfma_flops.argtypes = [ctypes.c_int, ctypes.c_int]
     lib.efim_ceiling_mfma_flops.restype = ctypes.c_double
     lib.efim_ceiling_mfma_bf16.argtypes = [vp, vp, ctypes.c_int, ctypes.c_int, vp]
+    lib.efim_ceiling_tile_loop_operand_bytes.argtypes = [ctypes.c_int]
+    lib.efim_ceiling_tile_loop_operand_bytes.restype = ctypes.c_size_t
+    lib.efim_ceiling_tile_loop_flops.argtypes = [ctypes.c_int, ctypes.c_int]
+    lib.efim_ceiling_tile_loop_flops.restype = ctypes.c_double
+    lib.efim_ceiling_tile_loop.argtypes = [ctypes.c_int, vp, vp, vp, ctypes.c_int, ctypes.c_int, vp]
     lib.efim_ceiling_read.argtypes = [vp, ctypes.c_size_t, vp, ctypes.c_int, vp]
     lib.efim_ceiling_copy.argtypes = [vp, vp, ctypes.c_size_t, ctypes.c_int, vp]
     stream = torch.cuda.current_stream()
@@ -400,6 +405,18 @@ def measure_ceilings(torch, E, reps=7):
     iters = 2000
     t_mfma = timed(lambda: lib.efim_ceiling_mfma_bf16(ops.data_ptr(), sink.data_ptr(), cus, iters, sp))
     flops = lib.efim_ceiling_mfma_flops(cus, iters)
+    # the attention kernel's tile loop, one ingredient at a time (fixed data, no paging or masks)
+    tl_ops = torch.empty(lib.efim_ceiling_tile_loop_operand_bytes(cus) // 2, dtype=torch.float32,
+                         device="cuda").normal_(0.0, 1.0, generator=gen).to(torch.bfloat16)
+    tl_gather = torch.empty(cus * 131072 // 2, dtype=torch.float32, device="cuda").normal_(0.0, 1.0, generator=gen).to(torch.bfloat16)
+    tiles = 2000
+    tl_flops = lib.efim_ceiling_tile_loop_flops(cus, tiles)
+    tile_loop = {}
+    for mode, label in enumerate(("mfma_only", "with_lds_operands", "with_softmax", "with_gather")):
+        t = timed(lambda: lib.efim_ceiling_tile_loop(mode, tl_ops.data_ptr(), tl_gather.data_ptr(), sink.data_ptr(),
+                                                     cus, tiles, sp))
+        tile_loop[label + "_TFLOPs"] = round(tl_flops / t / 1e12, 1)
+    del tl_ops, tl_gather
     size = 2 << 30
     src = torch.empty(size, dtype=torch.uint8, device="cuda")
     src.random_(0, 256, generator=gen)
@@ -413,8 +430,13 @@ def measure_ceilings(torch, E, reps=7):
         "mfma_TFLOPs": round(flops / t_mfma / 1e12, 1), "mfma_frac_of_peak": round(flops / t_mfma / 1e12 / PEAK_BF16_TFLOPS, 4),
         "read_GBps": round(size / t_read / 1e9, 1), "read_frac_of_peak": round(size / t_read / 1e9 / PEAK_HBM_GBPS, 4),
         "copy_GBps": round(2 * size / t_copy / 1e9, 1), "copy_frac_of_peak": round(2 * size / t_copy / 1e9 / PEAK_HBM_GBPS, 4),
+        # what the tile loop's structure (eight waves of 32 rows, 64-key tiles, a barrier per tile)
+        # reaches as its ingredients are added: MFMAs alone, + K / V^T operands from LDS, + the
+        # softmax arithmetic, + the direct-to-LDS loads of the next tiles
+        "tile_loop": tile_loop,
         "what": "libefim_ceilings.so: v_mfma_f32_32x32x16_bf16 from registers (2 waves per SIMD, %d workgroups, N(0,1) "
-                "operands); streaming read of 2 GiB; streaming copy of 2 GiB (read + written bytes)" % cus,
+                "operands); streaming read of 2 GiB; streaming copy of 2 GiB (read + written bytes); tile_loop: %d workgroups "
+                "of 8 waves x 32 rows over 2000 64-key tiles each, 8.39e6 flop per tile" % (cus, cus),
     }
 
 
