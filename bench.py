@@ -230,15 +230,18 @@ def replay(torch, E, W, iters):
     return out
 
 
-def decode_steps(torch, E, W, iters, shapes=("c2", "c3")):
-    """Decode (one new token per request) at the batch shapes of c2 and c3: device time of the
-    step through the two calls (efim_rope_append + efim_extend_attention) and through the
-    single-launch efim_decode_step; steps queued back to back, HIP events around the queue."""
+def decode_steps(torch, E, W, iters, shapes=("c2", "c3", "c2:8", "c2:16", "c3:4")):
+    """Decode (one new token per request) and other short steps ("c2:16" = 16 new tokens per
+    request) at the batch shapes of c2 and c3: device time of the step through the two calls
+    (efim_rope_append + efim_extend_attention) and through the single-launch efim_decode_step;
+    steps queued back to back, HIP events around the queue."""
     out = {}
     stream = torch.cuda.current_stream()
-    for base in shapes:
+    for shape in shapes:
+        base, _, inc = shape.partition(":")
+        inc = int(inc or 1)
         spec = W.make_batch(base, with_history=False, with_tensors=False)
-        d = DeviceBatch(torch, E, W, base, lengths=(spec.cached_len, np.ones_like(spec.new_len)), copies=3)
+        d = DeviceBatch(torch, E, W, base, lengths=(spec.cached_len, np.full_like(spec.new_len, inc)), copies=3)
         nbytes = E.efim_decode_workspace_bytes(d.desc)
         ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
         e0, e1 = E.HipEvent(), E.HipEvent()
@@ -289,8 +292,8 @@ def decode_steps(torch, E, W, iters, shapes=("c2", "c3")):
         del graph
         plan.close()
         nbytes_step = d.attn_bytes + d.rope_bytes
-        out[base + "_decode"] = {
-            "batch": b.batch, "two_call_us": round(t2, 2), "single_launch_us": round(t1, 2),
+        out[base + ("_decode" if inc == 1 else "_inc%d_one_launch" % inc)] = {
+            "batch": b.batch, "new_tokens_per_request": inc, "two_call_us": round(t2, 2), "single_launch_us": round(t1, 2),
             "speedup": round(t2 / t1, 3),
             "planned_us": round(tp, 2), "planned_graph_replay_us": round(tg, 2),
             "planned_graph_replay_frac_hbm": round(nbytes_step / tg / 1e3 / PEAK_HBM_GBPS, 4),
@@ -510,8 +513,8 @@ def main():
         return
 
     if args.decode_only:
-        shapes = (args.workload,) if args.workload in ("c2", "c3") else ("c2", "c3")
-        print(json.dumps({"decode_step": decode_steps(torch, E, W, iters=args.extra_iters, shapes=shapes)}))
+        kw = {"shapes": (args.workload,)} if args.workload in ("c2", "c3") else {}
+        print(json.dumps({"decode_step": decode_steps(torch, E, W, iters=args.extra_iters, **kw)}))
         return
 
     if args.fp8_only:

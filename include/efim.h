@@ -186,9 +186,11 @@ int efim_version(void);        /* major * 10000 + minor * 100 + patch */
 const char* efim_source_digest(void);
 
 /* ---------------------------------------------------------------------------------------
- * Decode step in one launch.  After the prompt, the engine generates the answer one token per
- * request and step (Sec. 2.2, the prefill / decode breakdown; Sec. 4.2: 128 output tokens per
- * request).  For such a batch -- new_len[r] == 1 for every r, num_q_heads / num_kv_heads <= 32 --
+ * Decode step, and other short steps, in one launch.  After the prompt, the engine generates
+ * the answer one token per request and step (Sec. 2.2, the prefill / decode breakdown; Sec. 4.2:
+ * 128 output tokens per request); and a cache hit on prefix and suffix leaves only a few
+ * incremental tokens per request to compute (Sec. 1, Sec. 3.1).  For a batch of such requests --
+ * every r has 1 <= new_len[r] <= 16 and new_len[r] * (num_q_heads / num_kv_heads) <= 32 --
  * efim_decode_step computes what
  *     efim_rope_append(batch, q, k_new, v_new, k_cache, v_cache, rope_base, rope_interleaved)
  *     efim_extend_attention(batch, q, k_cache, v_cache, out, sm_scale, ...)
@@ -197,8 +199,9 @@ const char* efim_source_digest(void);
  *
  * workspace: DEVICE, 256-byte aligned, at least efim_decode_workspace_bytes(batch) bytes,
  * contents irrelevant (as for efim_extend_attention).
- * Errors: as efim_extend_attention / efim_rope_append; EFIM_ERR_UNSUPPORTED if some
- * new_len[r] != 1 or if there are more than 32 query heads per kv head.
+ * Errors: as efim_extend_attention / efim_rope_append; EFIM_ERR_UNSUPPORTED if some request
+ * has no new token, more than 16 of them, or more than 32 query rows (new tokens x query heads)
+ * per kv head.
  * efim_decode_workspace_bytes returns 0 for a batch efim_decode_step would reject.
  * ------------------------------------------------------------------------------------- */
 size_t efim_decode_workspace_bytes(const efim_batch_t* batch);
@@ -330,8 +333,9 @@ int64_t efim_session_count(efim_session_pool_t* pool);
  * kernel.
  *
  *   efim_plan_create          HOST only.  Reads batch->cached_len / new_len and the scalar fields
- *                             (block_table is not looked at); decode != 0 plans a decode step
- *                             (every new_len 1, at most 32 query heads per kv head, else NULL).
+ *                             (block_table is not looked at); decode != 0 plans a step for
+ *                             efim_decode_step_planned (the batches efim_decode_step takes, else
+ *                             NULL).
  *                             Returns NULL for an invalid or unsupported batch.  The caller owns
  *                             the plan and releases it with efim_plan_destroy (NULL is ok).
  *   efim_plan_workspace_bytes bytes of DEVICE workspace the plan needs (work list, arrival

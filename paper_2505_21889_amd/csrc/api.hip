@@ -593,14 +593,17 @@ int efim_extend_attention_fp8(const efim_batch_t* batch, const void* q, const vo
 
 namespace {
 
-// The fused decode step takes batches in which every request has exactly one new token and
-// whose query heads per kv head fit one wavefront's rows.
+// The fused step takes batches in which every request has between one and kFusedMaxTokens new
+// tokens and the query rows of a request and kv head (tokens x heads of the group) fit one
+// wavefront's rows.
 int validate_decode_batch(const efim_batch_t* batch, int64_t* total) {
   int rc = validate_batch(batch, total);
   if (rc != EFIM_OK) return rc;
-  for (int r = 0; r < batch->batch; ++r)
-    if (batch->new_len[r] != 1) return EFIM_ERR_UNSUPPORTED;
-  if (batch->num_q_heads / batch->num_kv_heads > kDecodeMaxGroup) return EFIM_ERR_UNSUPPORTED;
+  const int g = batch->num_q_heads / batch->num_kv_heads;
+  for (int r = 0; r < batch->batch; ++r) {
+    const int n = batch->new_len[r];
+    if (n < 1 || n > kFusedMaxTokens || (int64_t)n * g > kFusedMaxRows) return EFIM_ERR_UNSUPPORTED;
+  }
   return EFIM_OK;
 }
 

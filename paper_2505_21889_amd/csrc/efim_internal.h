@@ -114,10 +114,12 @@ int launch_extend_attention(const efim_batch_t* b, const Plan& plan, const char*
                             float sm_scale, const CacheFormat& fmt, void* workspace, hipStream_t stream,
                             int32_t* tickets = nullptr, bool quiet = false);
 
-// Fused decode step (every request has exactly one new token): one launch does the rotary
+// Fused short step (every request has 1 .. kFusedMaxTokens new tokens and at most kFusedMaxRows
+// query rows per kv head; the decode step is the case of one token): one launch does the rotary
 // embedding, the cache append, the attention and the merge of split key ranges.
 // inv_freq / rotary_dim as for launch_rope_append.
-constexpr int kDecodeMaxGroup = 32;  // query heads per kv head the fused kernel handles
+constexpr int kFusedMaxRows = 32;    // query rows (new tokens x query heads per kv head) of one request and kv head
+constexpr int kFusedMaxTokens = 16;  // new tokens of one request (their rotated K/V rows wait in LDS)
 int launch_decode_step(const efim_batch_t* b, const Plan& plan, const char* header, int stage_slot,
                        const void* q, const void* k_new, const void* v_new, void* k_cache, void* v_cache,
                        void* out, const double* inv_freq, int rotary_dim, int interleaved, float sm_scale,

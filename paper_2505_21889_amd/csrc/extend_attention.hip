@@ -286,10 +286,12 @@ __device__ __forceinline__ void merge_rows(const AttnParams& p, const MergeItem&
 //                        steps, where each gathered K/V byte is used by twice as many rows and
 //                        the gather runs two tiles ahead.
 //
-// FUSED (decode step, one new token per request, at most 32 query heads per kv head): the
-// kernel also does what efim_rope_append does for that token -- q is rotated on the way in
-// (global q stays raw), the workgroup whose key range ends with the new token rotates its key,
-// stores key and value into the paged cache and patches them into its LDS tile.
+// FUSED (decode step and other short steps: every request has at most kFusedMaxTokens new
+// tokens and at most 32 query rows per kv head, so all rows of a (request, kv head) pair are
+// one tile): the kernel also does what efim_rope_append does for those tokens -- q is rotated
+// on the way in (global q stays raw); every workgroup rotates the new keys of its pair, patches
+// those that fall into its key range into its LDS tiles and stores them, with their values,
+// into the paged cache.
 //
 // KV8: the caches hold E4M3 codes.  The stages then hold code tiles (half the size); both
 // configurations run with three of them -- more tiles in flight measured slower, not faster.
@@ -320,18 +322,19 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
   auto vswz8 = [](int row) {
     return D == 128 ? ((row & 3) | (((row >> 3) & 1) << 2)) : (((row >> 1) & 1) | (((row >> 3) & 1) << 1));
   };
-  // fused decode step: the rotated query rows of the tile, the new token's rotated key and its
-  // value, cos/sin of the token's position -- behind the tile buffers
+  // fused step: the rotated query rows of the tile, then per new token its rotated key and its
+  // value as they go into the cache (bf16 rows or code rows) -- behind the tile buffers.  With
+  // D = 128 that is 16 KB: two 4-wave workgroups with their 64 KB of tile buffers fill the 160 KB
+  // of a compute unit exactly.
   constexpr int kFusedRows = 32;
   constexpr int kTileBufBytes = STAGES * kStageBytes;
-  constexpr int kFusedBytes = FUSED ? kFusedRows * D * 2 + 2 * D * 2 + 128 * 8 : 0;
+  constexpr int kFusedBytes = FUSED ? kFusedRows * D * 2 + kFusedMaxTokens * 2 * kGRowBytes : 0;
   static_assert(STAGES >= 2 && kTileBufBytes + kFusedBytes <= 160 * 1024, "stages must fit the 160 KB LDS");
   // One array, carved by hand.
   __shared__ __attribute__((aligned(1024))) char lds[kTileBufBytes + kFusedBytes];
   char* const stages = lds;
   uint16_t* const s_q = reinterpret_cast<uint16_t*>(lds + kTileBufBytes);
-  uint16_t* const s_kv = s_q + kFusedRows * D;
-  double* const s_cs = reinterpret_cast<double*>(s_kv + 2 * D);
+  char* const s_kv = reinterpret_cast<char*>(s_q + kFusedRows * D);  // token j: key row at j * 2 * kGRowBytes, value row behind it
   // the "this workgroup merges" flag is only used once the tile buffers are dead
   int* const s_last = reinterpret_cast<int*>(lds);
 
@@ -824,48 +827,58 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
   if constexpr (!FUSED) __builtin_amdgcn_s_waitcnt(0x0F70);
   if constexpr (FUSED) {
     __builtin_amdgcn_s_waitcnt(0x0F70);
-    // rotary embedding of the tile's query rows and of the new token's key at position C_r
-    // (the request's only new token is packed row rq.row_start), same arithmetic as the
-    // stand-alone append kernel
-    const int pos = rq.cached;
+    // Rotary embedding of the tile's query rows and of the new tokens' keys (token j of the
+    // request sits at position C_r + j and is packed row rq.row_start + j), same arithmetic as
+    // the stand-alone append kernel.  First the cosines and sines, one task per (token, pair),
+    // into the tile buffer that no gather has been issued into yet (the last one); then one task
+    // per (row, pair) over the query rows and the key rows.
+    const int n_tok = it.row_count / g;  // all rows of the (request, kv head) pair are in this tile
     const int rot_half = p.rotary_dim / 2;  // pairs per head row (D/2 when the whole row rotates)
-    if (tid < rot_half) {
+    double* const s_cs = reinterpret_cast<double*>(stages + (STAGES - 1) * kStageBytes);  // [token][pair] (cos, sin)
+    static_assert(kFusedMaxTokens * (D / 2) * 16 <= kStageBytes, "the cos/sin table must fit one tile buffer");
+    for (int idx = tid; idx < n_tok * rot_half; idx += 64 * WAVES) {
+      const int tk = idx / rot_half, j = idx - tk * rot_half;
       double sn, cs;
-      sincos((double)pos * p.inv_freq[tid], &sn, &cs);
-      s_cs[tid] = cs;
-      s_cs[64 + tid] = sn;
+      sincos((double)(rq.cached + tk) * p.inv_freq[j], &sn, &cs);
+      s_cs[(tk * (D / 2) + j) * 2] = cs;
+      s_cs[(tk * (D / 2) + j) * 2 + 1] = sn;
     }
     __syncthreads();
-    const int64_t kv_row = ((int64_t)rq.row_start * p.num_kv_heads + it.kv_head) * D;
-    for (int idx = tid; idx < (it.row_count + 1) * (D / 2); idx += 64 * WAVES) {
+    // (unrolled so that the element loads of several tasks are in flight together)
+#pragma unroll 4
+    for (int idx = tid; idx < (it.row_count + n_tok) * (D / 2); idx += 64 * WAVES) {
       const int r = idx / (D / 2), j = idx - r * (D / 2);
       // pair j of the rotated part, or two neighbouring elements behind it (passed through)
       const bool rotate = j < rot_half;
       const int e1 = !rotate ? p.rotary_dim + 2 * (j - rot_half) : (p.interleaved ? 2 * j : j);
       const int e2 = !rotate ? e1 + 1 : (p.interleaved ? 2 * j + 1 : j + rot_half);
-      const uint16_t* src = p.k_new + kv_row;
-      uint16_t* dst = s_kv;
-      if (r < it.row_count) {
-        const int rr = it.row_begin + r;
-        const int t_ = rr / g;
-        src = p.q + ((int64_t)(rq.row_start + t_) * p.num_q_heads + it.kv_head * g + (rr - t_ * g)) * D;
-        dst = s_q + r * D;
-      }
+      const bool is_key = r >= it.row_count;  // rows behind the query rows: the new tokens' keys
+      const int tk = is_key ? r - it.row_count : r / g;
+      const int64_t tok_row = rq.row_start + tk;
+      const uint16_t* src = is_key ? p.k_new + (tok_row * p.num_kv_heads + it.kv_head) * D
+                                   : p.q + (tok_row * p.num_q_heads + it.kv_head * g + (r - tk * g)) * D;
       uint32_t y1 = src[e1], y2 = src[e2];
-      if (rotate) rotate_pair_bf16(y1, y2, s_cs[j], s_cs[64 + j], &y1, &y2);
-      if (KV8 && r == it.row_count) {
-        // the key goes into the cache as a code: D bytes, the value's D bytes behind them
-        uint8_t* codes = reinterpret_cast<uint8_t*>(s_kv);
-        codes[e1] = (uint8_t)bf16_bits_to_e4m3(y1, p.k_scale);
-        codes[e2] = (uint8_t)bf16_bits_to_e4m3(y2, p.k_scale);
+      if (rotate) rotate_pair_bf16(y1, y2, s_cs[(tk * (D / 2) + j) * 2], s_cs[(tk * (D / 2) + j) * 2 + 1], &y1, &y2);
+      if (!is_key) {
+        s_q[r * D + e1] = (uint16_t)y1;
+        s_q[r * D + e2] = (uint16_t)y2;
+      } else if constexpr (KV8) {
+        // the key goes into the cache as a code
+        uint8_t* krow = reinterpret_cast<uint8_t*>(s_kv + tk * 2 * kGRowBytes);
+        krow[e1] = (uint8_t)bf16_bits_to_e4m3(y1, p.k_scale);
+        krow[e2] = (uint8_t)bf16_bits_to_e4m3(y2, p.k_scale);
       } else {
-        dst[e1] = (uint16_t)y1;
-        dst[e2] = (uint16_t)y2;
+        uint16_t* krow = reinterpret_cast<uint16_t*>(s_kv + tk * 2 * kGRowBytes);
+        krow[e1] = (uint16_t)y1;
+        krow[e2] = (uint16_t)y2;
       }
     }
-    for (int e = tid; e < D; e += 64 * WAVES) {
-      if constexpr (KV8) reinterpret_cast<uint8_t*>(s_kv)[D + e] = (uint8_t)bf16_bits_to_e4m3(p.v_new[kv_row + e], p.v_scale);
-      else s_kv[D + e] = p.v_new[kv_row + e];
+    for (int idx = tid; idx < n_tok * D; idx += 64 * WAVES) {
+      const int tk = idx / D, e = idx - tk * D;
+      const uint16_t v = p.v_new[((int64_t)(rq.row_start + tk) * p.num_kv_heads + it.kv_head) * D + e];
+      char* vrow = s_kv + tk * 2 * kGRowBytes + kGRowBytes;
+      if constexpr (KV8) reinterpret_cast<uint8_t*>(vrow)[e] = (uint8_t)bf16_bits_to_e4m3(v, p.v_scale);
+      else reinterpret_cast<uint16_t*>(vrow)[e] = v;
     }
     __syncthreads();
   }
@@ -889,25 +902,27 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
         wait_tile(t);
         if (t + kAhead < ntiles) issue_tile(t + kAhead, sl, pages);
         if constexpr (FUSED) {
-          // The key range that ends with the new token: the cache slot of that token has not
-          // been written yet, so its row of the landed tile and the rows behind it (which the
-          // gather fetched from that same slot) are replaced by the rotated key / the value;
-          // the token is also appended to the paged cache.
-          if (k_end == rq.cached + 1 && t == ntiles - 1) {
-            const int pos = rq.cached;
-            const int prow = pos - (k_begin + t * kKeyTile);
+          // Key tiles that reach into the new tokens: their cache slots have not been written
+          // yet, so those rows of the landed tile are replaced by the rotated keys / the values
+          // from LDS, and the tokens are appended to the paged cache (each position by the one
+          // workgroup of its kv head whose key range holds it).  Rows behind the key range,
+          // which the gather fetched from the range's last slot, take that token's rows too.
+          const int key0 = k_begin + t * kKeyTile;
+          if (k_end > rq.cached && key0 + kKeyTile > rq.cached) {
+            const int prow = max(rq.cached - key0, 0);  // first row of the tile that holds a new token
             constexpr int kPerRow = 2 * kGChunks;  // 16-byte chunks of a key row and a value row
             for (int u = tid; u < (kKeyTile - prow) * kPerRow; u += 64 * WAVES) {
               const int row = prow + u / kPerRow;
               const int w = u % kPerRow;
               const bool is_v = w >= kGChunks;
               const int c = is_v ? w - kGChunks : w;
-              const u32x4 val =
-                  *reinterpret_cast<const u32x4*>(reinterpret_cast<const char*>(s_kv) + (is_v ? kGRowBytes : 0) + c * 16);
+              const int pos = min(key0 + row, k_end - 1);
+              const u32x4 val = *reinterpret_cast<const u32x4*>(s_kv + (pos - rq.cached) * 2 * kGRowBytes +
+                                                                (is_v ? kGRowBytes : 0) + c * 16);
               const int swz = KV8 ? (is_v ? vswz8(row) : kswz8(row)) : (is_v ? G::vswz(row) : G::kswz(row));
               char* tile = stages + s0 * kStageBytes + (is_v ? kGTileBytes : 0);
               *reinterpret_cast<u32x4*>(tile + row * kGRowBytes + ((c ^ swz) << 4)) = val;
-              if (row == prow) {
+              if (key0 + row < k_end) {
                 const int64_t page = bt[pos >> ps];
                 char* cache = reinterpret_cast<char*>(is_v ? p.v_cache_w : p.k_cache_w);
                 *reinterpret_cast<u32x4*>(

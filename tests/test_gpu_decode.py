@@ -1,6 +1,7 @@
-"""The fused decode step (one new token per request) against the oracle's rope_append followed by
-its extend_attention, and against the library's own two-call path: caches bit-exact, q left
-untouched, outputs within the attention tolerance and identical to the two-call path."""
+"""The fused step (decode: one new token per request; short steps: up to 16 new tokens and 32
+query rows per kv head) against the oracle's rope_append followed by its extend_attention, and
+against the library's own two-call path: caches bit-exact, q left untouched, outputs within the
+attention tolerance and identical to the two-call path."""
 import numpy as np
 import pytest
 import torch
@@ -89,6 +90,75 @@ def test_decode_step_matches_oracle_and_two_call_path(E, name, cached, heads, d,
         assert np.array_equal(got, got2)
     finally:
         E.efim_set_tuning(E.EFIM_TUNE_SPLIT_KV, -1)
+
+
+SHORT_CASES = [
+    # name,       cached lengths,                              new tokens,                   heads,   D,  interleaved
+    # (cached lengths around multiples of 64: the new keys then lie in two key tiles, and with a
+    #  forced split of 64 keys in two work items)
+    ("mha_16",    [0, 1, 50, 63, 64, 100, 1000, 2047],          [16] * 8,                    (4, 4), 128, 0),
+    ("mha_mixed", [5, 60, 127, 128, 640, 3000, 56, 0],          [1, 2, 3, 16, 7, 8, 5, 9],   (4, 4), 128, 0),
+    ("gqa4",      [60, 63, 64, 56, 120, 0, 127, 4095],          [8, 1, 3, 4, 8, 2, 5, 7],    (8, 2), 128, 0),
+    ("gqa7",      [777, 61, 4096, 0],                           [4, 1, 3, 2],                (28, 4), 128, 1),
+    ("d64_g2",    [0, 100, 1025, 48, 62],                       [16, 9, 1, 12, 16],          (8, 4), 64, 0),
+    ("d64_il",    [33, 2000, 190],                              [3, 11, 16],                 (4, 4), 64, 1),
+]
+
+
+@pytest.mark.parametrize("split", [-1, 64, 0])
+@pytest.mark.parametrize("name,cached,new,heads,d,interleaved", SHORT_CASES)
+def test_short_step_matches_oracle_and_two_call_path(E, name, cached, new, heads, d, interleaved, split):
+    """Several new tokens per request in one launch: every new key is rotated, patched into the
+    tiles that hold it and appended by exactly one workgroup of its kv head."""
+    E.efim_set_tuning(E.EFIM_TUNE_SPLIT_KV, split)
+    try:
+        c, n = np.array(cached, dtype=np.int32), np.array(new, dtype=np.int32)
+        b = W.make_batch("c1", seed=150 + len(cached), lengths=(c, n), heads=heads, head_dim=d)
+        kc, vc = U.oracle_cache(b)
+        q_ref, kc_ref, vc_ref, ref = oracle_step(b, kc, vc, bool(interleaved))
+        got, kc_got, vc_got, ws = run_decode(E, b, kc, vc, interleaved)
+        assert np.array_equal(kc_got, kc_ref) and np.array_equal(vc_got, vc_ref), "cache append must be bit-exact"
+        U.assert_close(got, ref, name)
+        assert np.array_equal(got, two_call_path(E, b, kc, vc, interleaved)), "fused and two-call outputs differ"
+        got2, _, _, _ = run_decode(E, b, kc, vc, interleaved, ws=ws)
+        assert np.array_equal(got, got2)
+    finally:
+        E.efim_set_tuning(E.EFIM_TUNE_SPLIT_KV, -1)
+
+
+@pytest.mark.parametrize("name,cached,new,heads,d,interleaved", [SHORT_CASES[1], SHORT_CASES[4]])
+def test_short_step_in_the_eight_wave_configuration(E, name, cached, new, heads, d, interleaved):
+    E.efim_set_tuning(E.EFIM_TUNE_ROW_TILE, 256)
+    E.efim_set_tuning(E.EFIM_TUNE_SPLIT_KV, 128)
+    try:
+        c, n = np.array(cached, dtype=np.int32), np.array(new, dtype=np.int32)
+        b = W.make_batch("c1", seed=170 + len(cached), lengths=(c, n), heads=heads, head_dim=d)
+        kc, vc = U.oracle_cache(b)
+        _, kc_ref, vc_ref, ref = oracle_step(b, kc, vc, bool(interleaved))
+        got, kc_got, vc_got, _ = run_decode(E, b, kc, vc, interleaved)
+        assert np.array_equal(kc_got, kc_ref) and np.array_equal(vc_got, vc_ref)
+        U.assert_close(got, ref, name)
+        assert np.array_equal(got, two_call_path(E, b, kc, vc, interleaved))
+    finally:
+        E.efim_set_tuning(E.EFIM_TUNE_ROW_TILE, 0)
+        E.efim_set_tuning(E.EFIM_TUNE_SPLIT_KV, -1)
+
+
+@pytest.mark.parametrize("page_size", [8, 256])
+def test_short_step_other_page_sizes(E, page_size):
+    c = np.array([0, 7, 8, 60, 64, 250, 256, 1000, 2049], dtype=np.int32)
+    n = np.array([8, 2, 8, 7, 1, 8, 3, 6, 8], dtype=np.int32)
+    b = W.make_batch("c1", seed=140 + page_size, lengths=(c, n), heads=(8, 2), head_dim=128, page_size=page_size)
+    kc, vc = U.oracle_cache(b)
+    _, kc_ref, vc_ref, ref = oracle_step(b, kc, vc)
+    for split in (-1, 64):
+        E.efim_set_tuning(E.EFIM_TUNE_SPLIT_KV, split)
+        try:
+            got, kc_got, vc_got, _ = run_decode(E, b, kc, vc)
+        finally:
+            E.efim_set_tuning(E.EFIM_TUNE_SPLIT_KV, -1)
+        assert np.array_equal(kc_got, kc_ref) and np.array_equal(vc_got, vc_ref)
+        U.assert_close(got, ref, "page %d split %d" % (page_size, split))
 
 
 @pytest.mark.parametrize("name,cached,heads,d,interleaved", [CASES[0], CASES[3]])
@@ -252,15 +322,17 @@ def test_decode_shapes_of_the_benchmark(E):
 
 def test_decode_step_rejects_other_batches(E):
     c = np.array([10, 20], dtype=np.int32)
-    b = W.make_batch("c1", lengths=(c, np.array([1, 2], dtype=np.int32)), heads=(4, 4), head_dim=64)
-    table = torch.from_numpy(b.block_table).cuda()
-    desc = U.make_desc(E, b, table)
-    assert E.efim_decode_workspace_bytes(desc) == 0
     lib = E.raw_library()
     import ctypes
     fake = 0x10000
-    rc = lib.efim_decode_step(ctypes.byref(desc.c), fake, fake, fake, fake, fake, fake + 0x1000, 1e4, 0, 0.0, fake, 1 << 20, None)
-    assert rc == E.EFIM_ERR_UNSUPPORTED
+    # a request without a new token, with more than 16 of them, with more than 32 query rows per kv head
+    for new, heads in (([1, 0], (4, 4)), ([1, 17], (4, 4)), ([1, 5], (8, 1)), ([9, 1], (8, 2))):
+        b = W.make_batch("c1", lengths=(c, np.array(new, dtype=np.int32)), heads=heads, head_dim=64)
+        table = torch.from_numpy(b.block_table).cuda()
+        desc = U.make_desc(E, b, table)
+        assert E.efim_decode_workspace_bytes(desc) == 0
+        rc = lib.efim_decode_step(ctypes.byref(desc.c), fake, fake, fake, fake, fake, fake + 0x1000, 1e4, 0, 0.0, fake, 1 << 20, None)
+        assert rc == E.EFIM_ERR_UNSUPPORTED, (new, heads)
     b1 = W.make_batch("c1", lengths=(c, np.ones_like(c)), heads=(4, 4), head_dim=64)
     desc1 = U.make_desc(E, b1, torch.from_numpy(b1.block_table).cuda())
     need = E.efim_decode_workspace_bytes(desc1)

@@ -225,6 +225,35 @@ def test_fp8_decode_step(E, name, cached, heads, d, interleaved, page_size, row_
     assert np.array_equal(got, got2)
 
 
+SHORT_CASES8 = [
+    ("mha_mixed", [5, 60, 127, 128, 640, 3000, 56, 0], [1, 2, 3, 16, 7, 8, 5, 9], (4, 4), 128, 0, 16),
+    ("gqa4",      [60, 63, 64, 56, 120, 0, 127, 4095], [8, 1, 3, 4, 8, 2, 5, 7],  (8, 2), 128, 1, 16),
+    ("d64_g2",    [0, 100, 1025, 48, 62],              [16, 9, 1, 12, 16],        (8, 4), 64, 0, 64),
+]
+
+
+@pytest.mark.parametrize("row_tile,split", [(0, -1), (0, 64), (256, 128)])
+@pytest.mark.parametrize("name,cached,new,heads,d,interleaved,page_size", SHORT_CASES8)
+def test_fp8_short_step(E, name, cached, new, heads, d, interleaved, page_size, row_tile, split):
+    """Several new tokens per request through the one-launch step over an 8-bit cache."""
+    k_scale, v_scale = 0.0123, 0.031
+    c, n = np.array(cached, dtype=np.int32), np.array(new, dtype=np.int32)
+    b = W.make_batch("c1", seed=680 + len(cached), lengths=(c, n), heads=heads, head_dim=d, page_size=page_size)
+    kc, vc = oracle_cache8(b, k_scale, v_scale)
+    _, kc_ref, vc_ref, ref = oracle_step8(b, kc, vc, k_scale, v_scale, bool(interleaved))
+    E.efim_set_tuning(E.EFIM_TUNE_ROW_TILE, row_tile)
+    E.efim_set_tuning(E.EFIM_TUNE_SPLIT_KV, split)
+    try:
+        got, kc_got, vc_got, ws = run_decode8(E, b, kc, vc, k_scale, v_scale, interleaved)
+        got2, _, _, _ = run_decode8(E, b, kc, vc, k_scale, v_scale, interleaved, ws=ws)
+    finally:
+        E.efim_set_tuning(E.EFIM_TUNE_ROW_TILE, 0)
+        E.efim_set_tuning(E.EFIM_TUNE_SPLIT_KV, -1)
+    assert np.array_equal(kc_got, kc_ref) and np.array_equal(vc_got, vc_ref), "cache append must be byte-exact"
+    U.assert_close(got, ref, name, large_outputs=True)
+    assert np.array_equal(got, got2)
+
+
 def test_fp8_decode_sequence(E):
     """Six consecutive decode steps: codes and outputs follow the oracle step by step."""
     heads, d, steps = (8, 2), 128, 6

@@ -68,9 +68,10 @@ def test_planned_attention_equals_the_batch_call(E, cached, new, heads, d, knobs
 
 
 class DecodeCase:
-    def __init__(self, E, seed, cached, heads=(8, 2), d=128):
+    def __init__(self, E, seed, cached, heads=(8, 2), d=128, new=None):
         c = np.array(cached, dtype=np.int32)
-        self.b = b = _batch(seed, c, np.ones_like(c), heads, d)
+        n = np.ones_like(c) if new is None else np.array(new, dtype=np.int32)
+        self.b = b = _batch(seed, c, n, heads, d)
         self.kc0, self.vc0 = U.oracle_cache(b)
         kc, vc = self.kc0.copy(), self.vc0.copy()
         q_roped, _ = O.rope_append(b.cached_len, b.new_len, b.block_table, b.page_size, b.q_new, b.k_new, b.v_new,
@@ -113,6 +114,22 @@ def test_planned_decode_step_equals_the_batch_call(E, cached, heads, d):
     case.check("planned decode step")
     assert np.array_equal(U.host_bits(case.out), U.host_bits(want))
     assert np.array_equal(U.host_bits(case.q), b.q_new), "q must stay as given"
+
+
+def test_planned_short_step_equals_the_batch_call(E):
+    """Several new tokens per request through the plan-object call."""
+    case = DecodeCase(E, 540, [60, 63, 64, 56, 120, 0, 127, 4095], (8, 2), 128, new=[8, 1, 3, 4, 8, 2, 5, 7])
+    b = case.b
+    kcd, vcd = U.dev_bits(case.kc0), U.dev_bits(case.vc0)
+    want = torch.full(case.q.shape, 0x7FC1, dtype=torch.int16, device="cuda")
+    nbytes = E.efim_decode_workspace_bytes(case.desc)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    E.efim_decode_step(case.desc, case.q, case.k_new, case.v_new, kcd, vcd, want, b.rope_base, 0, 0.0, ws, nbytes)
+    E.efim_plan_upload(case.plan, case.ws, case.nbytes)
+    case.launch(E)
+    torch.cuda.synchronize()
+    case.check("planned short step")
+    assert np.array_equal(U.host_bits(case.out), U.host_bits(want))
 
 
 def test_captured_decode_step_replays(E):
@@ -180,6 +197,6 @@ def test_planned_calls_reject_bad_arguments(E):
         E.efim_extend_attention_planned(dec, table, 1 << 20, 2 << 20, 3 << 20, 4 << 20, 0.0, ws)
     with pytest.raises(E.EfimError):   # misaligned query pointer
         E.efim_extend_attention_planned(attn, table, (1 << 20) + 2, 2 << 20, 3 << 20, 4 << 20, 0.0, ws)
-    b2 = _batch(552, [40, 3], [1, 2], (4, 4), 64)
+    b2 = _batch(552, [40, 3], [1, 17], (4, 4), 64)
     with pytest.raises(E.EfimError):   # not a decode batch
         E.Plan(U.make_desc(E, b2, table), decode=True)

@@ -111,3 +111,45 @@ def test_random_decode_step(E, seed):
     finally:
         E.efim_set_tuning(E.EFIM_TUNE_SPLIT_KV, -1)
         E.efim_set_tuning(E.EFIM_TUNE_ROW_TILE, 0)
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_short_step(E, seed):
+    """The single-launch step with several new tokens per request (as many as the head grouping
+    allows: at most 16, and at most 32 query rows per kv head) on random batches: caches
+    bit-exact, output within the bar and identical to what the two calls produce."""
+    rng = np.random.default_rng(7500 + seed)
+    batch = int(rng.integers(1, 9))
+    cached = np.array([int(rng.choice(EDGES)) if rng.random() < 0.5 else int(rng.integers(0, 3000))
+                       for _ in range(batch)], dtype=np.int32)
+    heads = HEADS[int(rng.integers(len(HEADS)))]
+    d = int(rng.choice([64, 128]))
+    inter = int(rng.integers(0, 2))
+    most = min(16, 32 // (heads[0] // heads[1]))
+    new = rng.integers(1, most + 1, batch).astype(np.int32)
+    b = W.make_batch("c1", seed=850 + seed, lengths=(cached, new), heads=heads, head_dim=d,
+                     page_size=int(rng.choice([8, 16, 16, 32, 128])))
+    kc, vc = U.oracle_cache(b)
+    kc_ref, vc_ref = kc.copy(), vc.copy()
+    q_ref, _ = O.rope_append(b.cached_len, b.new_len, b.block_table, b.page_size, b.q_new, b.k_new, b.v_new,
+                             kc_ref, vc_ref, b.rope_base, bool(inter))
+    ref = O.extend_attention(b.cached_len, b.new_len, b.block_table, b.page_size, q_ref, kc_ref, vc_ref)
+    E.efim_set_tuning(E.EFIM_TUNE_SPLIT_KV, int(rng.choice([-1, 64, 192, 0])))
+    E.efim_set_tuning(E.EFIM_TUNE_ROW_TILE, int(rng.choice([0, 0, 256])))
+    try:
+        table = torch.from_numpy(b.block_table).cuda()
+        desc = U.make_desc(E, b, table)
+        q = U.dev_bits(b.q_new)
+        kcd, vcd = U.dev_bits(kc), U.dev_bits(vc)
+        out = torch.full(q.shape, 0x7FC1, dtype=torch.int16, device="cuda")
+        nbytes = E.efim_decode_workspace_bytes(desc)
+        ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+        E.efim_decode_step(desc, q, U.dev_bits(b.k_new), U.dev_bits(b.v_new), kcd, vcd, out, b.rope_base, inter, 0.0,
+                           ws, nbytes)
+        torch.cuda.synchronize()
+        assert np.array_equal(U.host_bits(kcd), kc_ref) and np.array_equal(U.host_bits(vcd), vc_ref)
+        U.assert_close(U.host_bits(out), ref, "%s %s %s d%d" % (cached.tolist(), new.tolist(), heads, d), large_outputs=True)
+        assert np.array_equal(U.host_bits(out), U.gpu_extend_attention(E, b, q_ref, kc_ref, vc_ref))
+    finally:
+        E.efim_set_tuning(E.EFIM_TUNE_SPLIT_KV, -1)
+        E.efim_set_tuning(E.EFIM_TUNE_ROW_TILE, 0)

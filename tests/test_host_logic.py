@@ -277,7 +277,8 @@ def test_static_call_refuses_batches_beyond_its_fixed_array():
 
 def test_plan_objects_on_the_host():
     """efim_plan_create / efim_plan_workspace_bytes are pure host functions: a plan is made from the
-    lengths alone; a decode plan wants one new token per request."""
+    lengths alone; a decode plan wants a short step (1..16 new tokens per request, at most 32
+    query rows per kv head)."""
     d = _desc([700, 0, 5000], [40, 300, 3])
     plan = E.Plan(d)
     items = E.efim_extend_plan_items(d)
