@@ -245,8 +245,11 @@ void build_plan(const efim_batch_t* b, int num_slots, Plan* plan) {
     plan->items.reserve(pend.size());
     for (auto& p : pend) plan->items.push_back(p.w);
   } else {
-    std::vector<int64_t> gcost(ngroups, 0);
-    for (auto& p : pend) gcost[p.group] += p.cost;
+    std::vector<int64_t> gcost(ngroups, 0), gmax(ngroups, 0);
+    for (auto& p : pend) {
+      gcost[p.group] += p.cost;
+      gmax[p.group] = std::max<int64_t>(gmax[p.group], p.cost);
+    }
     std::vector<int64_t> order(ngroups);
     for (int64_t i = 0; i < ngroups; ++i) order[i] = i;
     std::stable_sort(order.begin(), order.end(), [&](int64_t a, int64_t c) { return gcost[a] > gcost[c]; });
@@ -277,8 +280,12 @@ void build_plan(const efim_batch_t* b, int num_slots, Plan* plan) {
         longest = std::max(longest, per[x].size());
         continue;
       }
+      // (groups by their LONGEST item first, then by their whole cost: a request with a long
+      // cached context and few new rows is a light group of one or two very long items, and an
+      // item of 120 key tiles that starts last is a tenth of the whole step on its own)
       std::stable_sort(per[x].begin(), per[x].end(), [&](const Pending& a, const Pending& c) {
         if (a.group != c.group) {
+          if (gmax[a.group] != gmax[c.group]) return gmax[a.group] > gmax[c.group];
           if (gcost[a.group] != gcost[c.group]) return gcost[a.group] > gcost[c.group];
           return a.group < c.group;
         }
