@@ -54,8 +54,12 @@ struct AttnParams {
   const uint16_t* k_cache;
   const uint16_t* v_cache;
   uint16_t* out;
-  float* part_o;   // [slot][rows_per_item][D]
-  float* part_ml;  // [slot][rows_per_item][2] = (running max in log2 units, running sum)
+  // Partial result of one part of a split key range, per query row: the unnormalised output
+  // row O as binary16 values O / a with a = max |O| over the row (half the bytes of fp32, on a
+  // path that is bound by them; the row's own scale keeps any magnitude in range and the
+  // relative error at 2^-11 of the row's largest element), and three fp32 values.
+  uint16_t* part_o;  // [slot][rows_per_item][D] binary16 bits
+  float* part_ml;    // [slot][rows_per_item][4] = (running max in log2 units, running sum, a, unused)
   const int32_t* block_table;
   int32_t max_pages;
   int32_t num_q_heads;
@@ -206,6 +210,12 @@ __device__ __forceinline__ void store_coherent(float* at, float a, float b) {
   const uint64_t bits = (uint64_t)__float_as_uint(a) | ((uint64_t)__float_as_uint(b) << 32);
   __hip_atomic_store(reinterpret_cast<uint64_t*>(at), bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+__device__ __forceinline__ void store_coherent_bits(void* at, uint64_t bits) {
+  __hip_atomic_store(reinterpret_cast<uint64_t*>(at), bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ uint64_t load_coherent_bits(const void* at) {
+  return __hip_atomic_load(reinterpret_cast<const uint64_t*>(at), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
 __device__ __forceinline__ void load_coherent(const float* at, float* a, float* b) {
   const uint64_t bits = __hip_atomic_load(reinterpret_cast<const uint64_t*>(at), __ATOMIC_RELAXED,
                                           __HIP_MEMORY_SCOPE_AGENT);
@@ -214,7 +224,8 @@ __device__ __forceinline__ void load_coherent(const float* at, float* a, float* 
 }
 
 // Combines the partial results of a split key range: with M = max_s m_s and
-// w_s = 2^(m_s - M):  out = sum_s w_s O_s / sum_s w_s l_s, splits taken in index order.
+// w_s = 2^(m_s - M):  out = sum_s w_s O_s / sum_s w_s l_s, splits taken in index order
+// (O_s = a_s h_s, h_s the stored binary16 row).
 // nthreads threads (thread index t) share rows [row_lo, row_hi) of the tile, D/4 threads per
 // row.  The splits are taken eight at a time with all their loads issued together (one memory
 // round trip per group instead of one per split); a later group rescales the running sums.
@@ -231,23 +242,24 @@ __device__ __forceinline__ void merge_rows(const AttnParams& p, const MergeItem&
     float mx = -INFINITY, l = 0.f;
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
     for (int s0 = 0; s0 < mi.nsplit; s0 += GROUP) {
-      float m[GROUP], ls[GROUP];
-      f32x4 v[GROUP];
+      float m[GROUP], ls[GROUP], amax[GROUP];
+      uint64_t h[GROUP];
 #pragma unroll
       for (int i = 0; i < GROUP; ++i) {
         // splits past the end re-read the last one and get weight zero
         const int s = min(s0 + i, mi.nsplit - 1);
         const int64_t prow = (int64_t)(mi.first_slot + s) * p.rows_per_item + lr;
         if constexpr (COHERENT) {
-          float v0, v1, v2, v3;
-          load_coherent(p.part_ml + prow * 2, &m[i], &ls[i]);
-          load_coherent(p.part_o + prow * D + dv, &v0, &v1);
-          load_coherent(p.part_o + prow * D + dv + 2, &v2, &v3);
-          v[i] = f32x4{v0, v1, v2, v3};
+          float unused;
+          load_coherent(p.part_ml + prow * 4, &m[i], &ls[i]);
+          load_coherent(p.part_ml + prow * 4 + 2, &amax[i], &unused);
+          h[i] = load_coherent_bits(p.part_o + prow * D + dv);
         } else {
-          m[i] = p.part_ml[prow * 2];
-          ls[i] = p.part_ml[prow * 2 + 1];
-          v[i] = *reinterpret_cast<const f32x4*>(p.part_o + prow * D + dv);
+          const f32x4 mla = *reinterpret_cast<const f32x4*>(p.part_ml + prow * 4);
+          m[i] = mla[0];
+          ls[i] = mla[1];
+          amax[i] = mla[2];
+          h[i] = *reinterpret_cast<const uint64_t*>(p.part_o + prow * D + dv);
         }
       }
       float gmx = mx;
@@ -263,7 +275,10 @@ __device__ __forceinline__ void merge_rows(const AttnParams& p, const MergeItem&
       for (int i = 0; i < GROUP; ++i) {
         const float w = (s0 + i < mi.nsplit) ? __builtin_amdgcn_exp2f(m[i] - mx) : 0.f;
         l += w * ls[i];
-        acc += v[i] * w;
+        typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+        const f16x4 hv = __builtin_bit_cast(f16x4, h[i]);
+        const float wa = w * amax[i];
+        acc += f32x4{(float)hv[0], (float)hv[1], (float)hv[2], (float)hv[3]} * wa;
       }
     }
     const float inv = p.out_scale / l;
@@ -1013,29 +1028,37 @@ __global__ __launch_bounds__(64 * WAVES, 2) void extend_attention_kernel(const A
           }
       } else {
         const int64_t prow = (int64_t)it.partial_slot * p.rows_per_item + local_row;
-        float* dst = p.part_o + prow * D;
+        uint16_t* dst = p.part_o + prow * D;
+        // the row's largest magnitude (this lane holds half of the row, lane +-32 the other half)
+        float amax = 0.f;
+#pragma unroll
+        for (int d = 0; d < G::kDBlocks; ++d)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) amax = fmaxf(amax, fabsf(o[d][r]));
+        amax = cross_half_max(amax);
+        const float to_unit = amax > 0.f ? 1.f / amax : 0.f;  // (a row without visible keys in this part is all zero)
 #pragma unroll
         for (int d = 0; d < G::kDBlocks; ++d)
 #pragma unroll
           for (int rr = 0; rr < 4; ++rr) {
-            f32x4 v;
+            typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+            f16x4 v;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) v[e] = o[d][rr * 4 + e];
-            float* at = dst + d * 32 + rr * 8 + hi * 4;
+            for (int e = 0; e < 4; ++e) v[e] = (_Float16)(o[d][rr * 4 + e] * to_unit);
+            uint16_t* at = dst + d * 32 + rr * 8 + hi * 4;
             if (p.ticket_base >= 0) {
               // device-coherent stores: the workgroup that merges may sit on another XCD
-              store_coherent(at, v[0], v[1]);
-              store_coherent(at + 2, v[2], v[3]);
+              store_coherent_bits(at, __builtin_bit_cast(uint64_t, v));
             } else {
-              *reinterpret_cast<f32x4*>(at) = v;
+              *reinterpret_cast<uint64_t*>(at) = __builtin_bit_cast(uint64_t, v);
             }
           }
         if (hi == 0) {
           if (p.ticket_base >= 0) {
-            store_coherent(p.part_ml + prow * 2, m_run, l_tot);
+            store_coherent(p.part_ml + prow * 4, m_run, l_tot);
+            store_coherent(p.part_ml + prow * 4 + 2, amax, 0.f);
           } else {
-            p.part_ml[prow * 2] = m_run;
-            p.part_ml[prow * 2 + 1] = l_tot;
+            *reinterpret_cast<f32x4*>(p.part_ml + prow * 4) = f32x4{m_run, l_tot, amax, 0.f};
           }
         }
       }
@@ -1084,7 +1107,7 @@ void fill_params(AttnParams* p, const efim_batch_t* b, const Plan& plan, const c
   p->k_cache = static_cast<const uint16_t*>(k_cache);
   p->v_cache = static_cast<const uint16_t*>(v_cache);
   p->out = static_cast<uint16_t*>(out);
-  p->part_o = reinterpret_cast<float*>(partials + plan.off_part_o);
+  p->part_o = reinterpret_cast<uint16_t*>(partials + plan.off_part_o);
   p->part_ml = reinterpret_cast<float*>(partials + plan.off_part_ml);
   p->block_table = b->block_table;
   p->max_pages = b->max_pages_per_req;

@@ -317,9 +317,10 @@ void build_plan(const efim_batch_t* b, int num_slots, Plan* plan) {
   const size_t prows = (size_t)plan->partial_rows;
   off = 0;
   plan->off_part_o = off;
-  off = align_up(off + (size_t)plan->num_partial_slots * prows * D * sizeof(float), 256);
+  // per row: D binary16 values, then (max, sum, scale, unused) as fp32
+  off = align_up(off + (size_t)plan->num_partial_slots * prows * D * sizeof(uint16_t), 256);
   plan->off_part_ml = off;
-  off = align_up(off + (size_t)plan->num_partial_slots * prows * 2 * sizeof(float), 256);
+  off = align_up(off + (size_t)plan->num_partial_slots * prows * 4 * sizeof(float), 256);
   plan->total_bytes = off < 256 ? 256 : off;  // never zero, so callers always pass a real buffer
 }
 
