@@ -499,17 +499,6 @@ def main():
     torch.cuda.set_device(0)
     stream = torch.cuda.current_stream()
 
-    # Bring the device to its working clocks before the first launch of the library: the first
-    # dozen launches of a fresh process otherwise run 5-30 % slow, which the untimed warm-up
-    # steps absorb for the figures below but not for a profiler's per-kernel average.
-    a = torch.randn(4096, 4096, device="cuda", dtype=torch.bfloat16)
-    t0 = time.perf_counter()
-    while time.perf_counter() - t0 < 0.3:
-        for _ in range(20):
-            torch.mm(a, a)
-        torch.cuda.synchronize()
-    del a
-
     if args.calibrate_copy:
         src = torch.zeros(1 << 30, dtype=torch.uint8, device="cuda")
         dst = torch.empty_like(src)
