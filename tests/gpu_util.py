@@ -110,19 +110,21 @@ def oracle_inputs(b):
 
 
 def progress(msg):
-    """A line on the real stdout (past pytest's capture) and in gpurun_out/test_progress.log: the
-    oracle needs minutes for the largest workloads and the run must be seen to be alive."""
+    """A line on the real stdout (past pytest's capture) and in a log file (test_progress.log in
+    the folder EFIM_PROGRESS_DIR names, else in the output folder of the test runs): the oracle
+    needs minutes for the largest workloads and the run must be seen to be alive."""
     import os
     import sys
     import time
+    folder = os.environ.get("EFIM_PROGRESS_DIR", "gpurun_out")
     line = "[%s] %s\n" % (time.strftime("%H:%M:%S"), msg)
     try:
         os.write(sys.__stdout__.fileno(), line.encode())
     except (OSError, ValueError, AttributeError):
         pass
     try:
-        os.makedirs("gpurun_out", exist_ok=True)
-        with open(os.path.join("gpurun_out", "test_progress.log"), "a") as fh:
+        os.makedirs(folder, exist_ok=True)
+        with open(os.path.join(folder, "test_progress.log"), "a") as fh:
             fh.write(line)
     except OSError:
         pass
