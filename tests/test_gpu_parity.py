@@ -123,6 +123,28 @@ def test_extend_attention_split_kv_agrees(E, split):
     assert np.array_equal(got, one_launch)
 
 
+@pytest.mark.parametrize("power", [20, -20, 60])
+def test_split_ranges_scale_exactly_with_the_values(E, power):
+    """Values 2^k times larger give outputs exactly 2^k times larger, also where key ranges are
+    split: the partial results travel as 16-bit rows with a scale of their own, which must
+    neither overflow nor lose small rows.  (No oracle needed: every product and sum scales by a
+    power of two without rounding differently.)"""
+    b = _ragged(96, [900, 130, 2500], [33, 5, 70], heads=(8, 2), head_dim=128)
+    q_roped, kc, vc = _oracle_inputs(b)
+    vc_scaled = O.f64_to_bf16(O.bf16_to_f64(vc) * 2.0 ** power)
+    assert np.array_equal(O.bf16_to_f64(vc_scaled), O.bf16_to_f64(vc) * 2.0 ** power, equal_nan=True)   # (exact; unused slots hold NaN)
+    for merge in (0, 1):
+        E.efim_set_tuning(E.EFIM_TUNE_SPLIT_KV, 128)
+        E.efim_set_tuning(E.EFIM_TUNE_FUSED_MERGE, merge)
+        try:
+            base = U.gpu_extend_attention(E, b, q_roped, kc, vc)
+            scaled = U.gpu_extend_attention(E, b, q_roped, kc, vc_scaled)
+        finally:
+            E.efim_set_tuning(E.EFIM_TUNE_SPLIT_KV, -1)
+            E.efim_set_tuning(E.EFIM_TUNE_FUSED_MERGE, -1)
+        assert np.array_equal(O.bf16_to_f64(scaled), O.bf16_to_f64(base) * 2.0 ** power), "merge path %d" % merge
+
+
 def test_many_splits_and_overlapping_calls(E):
     """More than eight parts per query tile (the merge takes them in groups of eight), and
     several calls in flight on different streams: each uses its own block of arrival counters."""
