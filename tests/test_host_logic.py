@@ -174,6 +174,24 @@ def test_plan_covers_named_workloads(name):
     assert E.efim_extend_workspace_bytes(d) >= 256
 
 
+def test_long_items_of_the_mixed_step_start_early():
+    """The work list of the mixed serving step, XCD by XCD (items whose indices agree modulo 8):
+    the longest items -- cache hits with long contexts and few new rows, light groups of one or
+    two very long items -- are among the first to start, not the last."""
+    b = W.make_batch("c5", with_history=False, with_tensors=False)
+    d = E.BatchDesc(b.cached_len, b.new_len, FAKE_DEV, b.num_q_heads, b.num_kv_heads, b.head_dim,
+                    b.page_size, b.num_pages, b.max_pages_per_req)
+    items = E.efim_extend_plan_items(d)
+    keys = (items["key_end"] - items["key_begin"]).astype(np.int64)
+    for x in range(8):
+        mine = keys[x::8]
+        longest = int(mine.max())
+        where = np.flatnonzero(mine >= 0.9 * longest)
+        assert where.max() < 0.15 * len(mine), (x, where.max(), len(mine))
+        # and the list ends with short items
+        assert mine[-len(mine) // 20:].max() <= 0.5 * longest
+
+
 @pytest.mark.parametrize("split", [-1, 0, 64, 512])
 @pytest.mark.parametrize("xcd", [0, 1])
 def test_plan_covers_random_ragged_batches(split, xcd):
